@@ -1,0 +1,229 @@
+"""Seeded synthetic inputs for the chunk-sparse expert FFN.
+
+This module only draws random numbers and shapes them; it holds none of the layer's
+arithmetic (no ReLU, no RMSNorm, no expert MLP, no union).  Both the CPU oracle's tests
+and the HIP path's tests / benchmark take their inputs from here, so that the two sides
+always see the same buffers.
+
+The inputs stand in for the paper's workload (trained BlockFFN weights decoding with a
+speculative drafter, Sec. 4.3 and Table 11), which cannot be had here.  They keep what
+matters to the kernels: the shapes (a chunk is the n draft tokens verified together,
+Sec. 3.3; d_h = 2048 and d_e = 128 as in the 2.8B row of Table 8) and the sparsity levels
+(token-level sparsity about 80 %, 8-token chunk-level sparsity about 70 %, Table 2).
+
+Recipe
+------
+* weights  W ~ N(0, 0.02^2) i.i.d., kept fp32 or rounded to bf16 (round-to-nearest-even);
+* tokens   x_t = c + sigma * n_t with one centre c ~ N(0, I) per group of tokens and
+  n_t ~ N(0, I); ``independent`` workloads use x_t ~ N(0, I);
+* router bias  b_i = -z * ||W_r[i, :]||_2 * sqrt(1 + sigma^2) with z = Phi^-1(0.8), so that
+  every router pre-activation is positive with probability 0.2 exactly;
+* guard band  a token is redrawn while any router pre-activation lies within
+  2^-16 * (|b_i| + sum_j |x_tj * W_r[i, j]|) of zero (evaluated in fp64), so that no fp32
+  summation order can change the sign that decides an expert's mask bit.
+
+The guard band evaluates the affine map x -> W_r x + b only to keep inputs away from the
+decision boundary; it is input conditioning, not a step of the method.
+"""
+
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+Z_P80 = 0.8416212335729143  # Phi^-1(0.8)
+GUARD_REL = 2.0 ** -16
+WEIGHT_STD = 0.02
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    """Shape and statistics of one synthetic workload."""
+
+    name: str
+    d: int            # d_h, hidden size
+    E: int            # N_e, number of experts
+    d_e: int          # expert intermediate size
+    wdtype: str       # "f32" | "bf16"
+    gated: bool       # True: SiLU(gate)*up experts; False: Eq. 2 (non-gated Swish)
+    k: int            # tokens per chunk
+    n_chunks: int
+    sigma: float      # within-group noise scale
+    independent: bool = False   # tokens i.i.d. N(0, I) instead of centre + noise
+    group: int = 0    # tokens sharing one centre (0: the whole chunk)
+    seed: int = 0
+
+    @property
+    def n_tok(self) -> int:
+        return self.k * self.n_chunks
+
+    @property
+    def mask_words(self) -> int:
+        return (self.E + 63) // 64
+
+    @property
+    def n_mats(self) -> int:
+        return 3 if self.gated else 2
+
+    @property
+    def expert_bytes(self) -> int:
+        s = 2 if self.wdtype == "bf16" else 4
+        return self.n_mats * self.d * self.d_e * s
+
+    def replace(self, **kw) -> "Workload":
+        return dataclasses.replace(self, **kw)
+
+
+# The five measured configurations (gated experts, as the configurations state) and the
+# paper-shaped one (non-gated, N_e = 128; Table 8, 2.8B row).
+WORKLOADS: Dict[str, Workload] = {
+    "tiny_f32_k4": Workload("tiny_f32_k4", d=256, E=16, d_e=64, wdtype="f32", gated=True,
+                            k=4, n_chunks=16, sigma=0.3),
+    "decode_k1": Workload("decode_k1", d=1024, E=32, d_e=128, wdtype="bf16", gated=True,
+                          k=1, n_chunks=4096, sigma=0.0, independent=True),
+    "spec_k8": Workload("spec_k8", d=2048, E=64, d_e=128, wdtype="bf16", gated=True,
+                        k=8, n_chunks=2048, sigma=0.3),
+    "tree_k32": Workload("tree_k32", d=2048, E=64, d_e=256, wdtype="bf16", gated=True,
+                         k=32, n_chunks=2048, sigma=0.5),
+    "stack_decode_k8": Workload("stack_decode_k8", d=2048, E=64, d_e=256, wdtype="bf16",
+                                gated=True, k=8, n_chunks=1, sigma=0.3),
+    "stack_prefill_512": Workload("stack_prefill_512", d=2048, E=64, d_e=256, wdtype="bf16",
+                                  gated=True, k=512, n_chunks=1, sigma=0.3, group=8),
+    "paper_k32": Workload("paper_k32", d=2048, E=128, d_e=128, wdtype="bf16", gated=False,
+                          k=32, n_chunks=512, sigma=0.3),
+}
+
+
+def _gen(seed: int, device) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    return g
+
+
+def _weight(shape, wdtype: str, gen: torch.Generator, device) -> torch.Tensor:
+    w = torch.randn(shape, generator=gen, device=device, dtype=torch.float32) * WEIGHT_STD
+    return w.to(torch.bfloat16) if wdtype == "bf16" else w
+
+
+def make_layers(w: Workload, n_layers: int = 1, device="cpu", seed: Optional[int] = None,
+                p_active: float = 0.2, bias: bool = True, gain: bool = False) -> Dict[str, torch.Tensor]:
+    """Weights of ``n_layers`` stacked layers.
+
+    Returns tensors laid out as the library expects them: ``w_router [L][E][d]``,
+    ``w_up`` / ``w_gate`` ``[L][E][d_e][d]``, ``w_down [L][E][d][d_e]`` (every matrix stored
+    one row per output feature), ``b_router [L][E]`` fp32, ``g_rms [L][E]`` fp32 (ones unless
+    ``gain``, then drawn from U(0.5, 1.5)).
+    """
+    seed = w.seed if seed is None else seed
+    out: Dict[str, list] = {n: [] for n in ("w_router", "w_up", "w_gate", "w_down", "b_router", "g_rms")}
+    z = -float(torch.distributions.Normal(0.0, 1.0).icdf(torch.tensor(p_active, dtype=torch.float64)))
+    sig_eff = 0.0 if w.independent else w.sigma
+    for layer in range(n_layers):
+        gen = _gen(seed * 100003 + layer, device)
+        wr = _weight((w.E, w.d), w.wdtype, gen, device)
+        out["w_router"].append(wr)
+        out["w_up"].append(_weight((w.E, w.d_e, w.d), w.wdtype, gen, device))
+        if w.gated:
+            out["w_gate"].append(_weight((w.E, w.d_e, w.d), w.wdtype, gen, device))
+        out["w_down"].append(_weight((w.E, w.d, w.d_e), w.wdtype, gen, device))
+        norm = wr.double().norm(dim=1)
+        b = (-z * norm * math.sqrt(1.0 + sig_eff * sig_eff)).float()
+        if not bias:
+            b = torch.zeros_like(b)
+        out["b_router"].append(b)
+        if gain:
+            g = 0.5 + torch.rand((w.E,), generator=gen, device=device, dtype=torch.float32)
+        else:
+            g = torch.ones((w.E,), device=device, dtype=torch.float32)
+        out["g_rms"].append(g)
+    res = {n: torch.stack(v).contiguous() for n, v in out.items() if v}
+    if not w.gated:
+        res["w_gate"] = None
+    return res
+
+
+def make_chunk_layer(w: Workload, n_layers: int, device="cpu") -> torch.Tensor:
+    """Chunk c reads layer ``c mod n_layers`` (rotation through distinct weight sets)."""
+    return (torch.arange(w.n_chunks, device=device, dtype=torch.int64) % n_layers).to(torch.int32)
+
+
+def make_tokens(w: Workload, layers: Dict[str, torch.Tensor], chunk_layer: Optional[torch.Tensor] = None,
+                device="cpu", seed: Optional[int] = None, guard: bool = True, max_rounds: int = 64) -> torch.Tensor:
+    """Token matrix ``x [n_chunks*k][d]`` fp32 with the guard band applied."""
+    seed = w.seed if seed is None else seed
+    gen = _gen(seed * 100003 + 7919, device)
+    T, d, k = w.n_tok, w.d, w.k
+    grp = w.group if w.group > 0 else k
+    assert T % grp == 0
+    noise = torch.randn((T, d), generator=gen, device=device, dtype=torch.float32)
+    if w.independent:
+        centre = None
+        x = noise.clone()
+    else:
+        c = torch.randn((T // grp, d), generator=gen, device=device, dtype=torch.float32)
+        centre = c.repeat_interleave(grp, dim=0)
+        x = centre + w.sigma * noise
+    if not guard:
+        return x.contiguous()
+    if chunk_layer is None:
+        tok_layer = torch.zeros((T,), dtype=torch.int64, device=device)
+    else:
+        tok_layer = chunk_layer.to(device=device, dtype=torch.int64).repeat_interleave(k)
+    wr_all = layers["w_router"]
+    b_all = layers["b_router"]
+    todo = torch.arange(T, device=device)
+    for _ in range(max_rounds):
+        bad_parts = []
+        for lo in range(0, todo.numel(), 8192):
+            idx = todo[lo:lo + 8192]
+            lay = tok_layer[idx]
+            for l in torch.unique(lay).tolist():
+                sel = idx[lay == l]
+                wr = wr_all[l].double()
+                b = b_all[l].double()
+                xs = x[sel].double()
+                a0 = xs @ wr.t() + b
+                mag = xs.abs() @ wr.abs().t() + b.abs()
+                bad = (a0.abs() <= GUARD_REL * mag).any(dim=1)
+                bad_parts.append(sel[bad])
+        todo = torch.cat(bad_parts) if bad_parts else todo[:0]
+        if todo.numel() == 0:
+            break
+        fresh = torch.randn((todo.numel(), d), generator=gen, device=device, dtype=torch.float32)
+        x[todo] = fresh if centre is None else centre[todo] + w.sigma * fresh
+    else:
+        raise RuntimeError("guard band resampling did not converge")
+    return x.contiguous()
+
+
+def expected_sparsity(k: int, sigma: float, p_active: float = 0.2, independent: bool = False):
+    """Closed-form (TLS, CLS_k) of the generator.
+
+    One expert's pre-activation over a chunk is s * (u + sigma * v_t) - z * s * sqrt(1 + sigma^2)
+    with u, v_t i.i.d. standard normal, so the expert is idle for the whole chunk with probability
+    E_u[ Phi((z * sqrt(1 + sigma^2) - u) / sigma)^k ].
+    """
+    from scipy import integrate, stats
+
+    z = -stats.norm.ppf(p_active)
+    tls = 1.0 - p_active
+    if independent or sigma == 0.0 and k == 1:
+        return tls, tls ** k
+    thr = z * math.sqrt(1.0 + sigma * sigma)
+    f = lambda u: stats.norm.pdf(u) * stats.norm.cdf((thr - u) / sigma) ** k
+    val, _ = integrate.quad(f, -12.0, 12.0, limit=400)
+    return tls, val
+
+
+def to_numpy(t: Optional[torch.Tensor]) -> Optional[np.ndarray]:
+    """Host copy as a numpy array; bf16 tensors come back as their uint16 bit patterns."""
+    if t is None:
+        return None
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
