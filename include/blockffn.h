@@ -1,0 +1,125 @@
+/*
+ * blockffn.h - C ABI of the MI355X (gfx950) chunk-sparse expert FFN.
+ *
+ * The library runs the inference hot path of a BlockFFN layer for chunks of k consecutive
+ * tokens (the n draft tokens verified together in speculative decoding, Sec. 3.3):
+ *
+ *   router        A^0 = W_router^T x (+ b),  A^1 = ReLU(A^0),  A = RMSNorm(A^1)        (Eq. 3)
+ *   chunk union   Union(x): experts activated by at least one token of the chunk        (Sec. 3.3)
+ *   sparse FFN    FFN(x_t) = sum_{i in Union} [A_i(x_t) > 0] A_i(x_t) E_i(x_t)           (Eq. 1, Sec. 3.3)
+ *   dense FFN     FFN(x_t) = sum_{i=1..N_e} A_i(x_t) E_i(x_t), every expert evaluated   (Eq. 1)
+ *
+ *   E_i(x) = W_down^(i)T Swish(W_up^(i)T x)                         (Eq. 2, the paper's expert)
+ *   E_i(x) = W_down^(i)T [Swish(W_gate^(i)T x) . W_up^(i)T x]       (gated variant, Table 1)
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ * - Every pointer is a DEVICE pointer owned by the caller, except `layer` (host struct, read
+ *   during the call only) and `stream`.  The library never allocates, frees or keeps them.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *   work on it: no synchronisation, no host read-back.  Outputs of one call are valid inputs
+ *   of the next call on the same stream.
+ * - Chunk c is the token range [c*k, (c+1)*k); token t of the batch is row t of x / scores / y.
+ * - W = ceil(N_e / 64) mask words per token or chunk; expert i is bit (i % 64) of word (i / 64);
+ *   bits at or above N_e are zero.
+ * - Weights hold `n_layers` layers stacked in their leading dimension.  `chunk_layer`
+ *   (device int32 [n_chunks], or NULL = layer 0 for all) says which layer's weights chunk c
+ *   reads; values are clamped into [0, n_layers).  This is how a batch of chunks walks through
+ *   distinct weight sets in one launch.
+ * - Every matrix is stored one row per OUTPUT feature with the contraction index contiguous
+ *   (the transposes written in Eq. 2-3): w_router [L][E][d], w_up / w_gate [L][E][d_e][d],
+ *   w_down [L][E][d][d_e].  dtype per `wdtype`: fp32 or bf16.  Weight pointers must be 16-byte
+ *   aligned.  Activations (x, scores, y) are fp32; accumulation is fp32.
+ * - Return value: BLOCKFFN_OK or a negative code; nothing is enqueued when a code is returned
+ *   by argument checking.  No exceptions, no exit, no output to stdout/stderr.
+ * - Inputs are assumed finite.  A NaN pre-activation counts as inactive.
+ *
+ * Limits: 1 <= N_e <= 256, 1 <= k <= 512, d % 8 == 0, d_e % 8 == 0, d_e <= 1024, d <= 16384.
+ */
+#ifndef BLOCKFFN_H
+#define BLOCKFFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { BLOCKFFN_F32 = 0, BLOCKFFN_BF16 = 1 };
+enum { BLOCKFFN_EXPERT_SWISH = 0, /* Eq. 2 */
+       BLOCKFFN_EXPERT_GATED = 1  /* Table 1, gated row */ };
+enum {
+  BLOCKFFN_OK = 0,
+  BLOCKFFN_ERR_INVALID = -1,     /* NULL pointer, size < 1, d or d_e not a multiple of 8, misaligned weights */
+  BLOCKFFN_ERR_UNSUPPORTED = -2, /* shape or dtype outside the limits above */
+  BLOCKFFN_ERR_WORKSPACE = -3,   /* workspace smaller than blockffn_workspace_bytes() */
+  BLOCKFFN_ERR_LAUNCH = -4       /* the HIP runtime refused a launch */
+};
+
+typedef struct blockffn_layer {
+  int32_t d;           /* d_h: hidden size */
+  int32_t n_experts;   /* N_e */
+  int32_t d_e;         /* expert intermediate size */
+  int32_t wdtype;      /* BLOCKFFN_F32 | BLOCKFFN_BF16, for all four weight tensors */
+  int32_t expert_kind; /* BLOCKFFN_EXPERT_SWISH | BLOCKFFN_EXPERT_GATED */
+  int32_t n_layers;    /* L >= 1 layers stacked in each tensor below */
+  float rms_eps;       /* RMSNorm epsilon (inside the root), >= 0 */
+  int32_t reserved;    /* 0 */
+  const void *w_router;  /* [L][E][d] */
+  const float *b_router; /* [L][E] fp32, or NULL (the paper's router has no bias) */
+  const float *g_rms;    /* [L][E] fp32 RMSNorm gain, or NULL (all ones) */
+  const void *w_up;      /* [L][E][d_e][d] */
+  const void *w_gate;    /* [L][E][d_e][d]; NULL iff expert_kind == SWISH */
+  const void *w_down;    /* [L][E][d][d_e] */
+} blockffn_layer;
+
+/* Eq. 3.  scores [n_chunks*k][E] fp32 (A, exact zeros where inactive); token_mask
+ * [n_chunks*k][W] uint64, bit set iff A^0 > 0 (strictly; follows the ReLU pattern A^1, so a
+ * zero gain leaves the bit set).  RMSNorm: mean of squares over all N_e entries, eps inside
+ * the root, then the gain.  An all-inactive token gets an all-zero row. */
+int blockffn_router(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                    int64_t n_chunks, int32_t k, float *scores, uint64_t *token_mask,
+                    void *stream);
+
+/* Sec. 3.3 Union(x) and Sec. 2.1 TLS / CLS counts.  union_mask [n_chunks][W] = OR of the
+ * chunk's token masks; active_idx [n_chunks][E] = set bits in ascending order, tail filled
+ * with -1; n_active [n_chunks] = popcount.  stats (int64[2], or NULL) is ADDED to:
+ * stats[0] += inactive (token, expert) pairs, stats[1] += inactive (chunk, expert) pairs, so
+ * TLS = stats[0] / (tokens * E) and CLS_k = stats[1] / (chunks * E). */
+int blockffn_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int32_t k,
+                         int32_t n_experts, uint64_t *union_mask, int32_t *active_idx,
+                         int32_t *n_active, int64_t *stats, void *stream);
+
+/* Sec. 3.3: streams only the weights of the experts in active_idx[c][0 .. n_active[c]) once
+ * per chunk, applies them to all k tokens, and drops the terms of tokens whose mask bit for
+ * that expert is clear.  Overwrites y [n_chunks*k][d] completely (zeros for an empty union).
+ * scores / token_mask / active_idx / n_active as produced by the two calls above.
+ * workspace: at least blockffn_workspace_bytes() bytes, 256-byte aligned; contents undefined
+ * before and after. */
+int blockffn_sparse_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                        const float *scores, const uint64_t *token_mask,
+                        const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
+                        int32_t k, float *y, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/* Eq. 1 with no sparsity used (the paper's sparsity-ablation setting, App. H): all N_e experts
+ * are streamed for every chunk and weighted by `scores` with no masking.  Same kernels and
+ * workspace as the sparse path. */
+int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                       const float *scores, int64_t n_chunks, int32_t k, float *y,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace the two FFN entry points need for this shape (0 on invalid arguments). */
+size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k);
+
+/* Static description of a return code. */
+const char *blockffn_strerror(int code);
+
+/* ABI version of this header (major * 100 + minor). */
+int blockffn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLOCKFFN_H */

@@ -1,0 +1,182 @@
+"""ctypes binding of ``libblockffn.so``: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (``include/blockffn.h``)
+and passes device pointers of torch tensors straight through; no arithmetic of the layer
+happens in Python.  ``lib()`` raises if the shared library has not been built: there is no
+fallback path.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libblockffn.so")
+
+F32, BF16 = 0, 1
+EXPERT_SWISH, EXPERT_GATED = 0, 1
+OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
+
+EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
+           "blockffn_workspace_bytes", "blockffn_strerror", "blockffn_version")
+
+
+class BlockffnLayer(ctypes.Structure):
+    """Mirror of ``struct blockffn_layer``."""
+
+    _fields_ = [
+        ("d", ctypes.c_int32), ("n_experts", ctypes.c_int32), ("d_e", ctypes.c_int32),
+        ("wdtype", ctypes.c_int32), ("expert_kind", ctypes.c_int32), ("n_layers", ctypes.c_int32),
+        ("rms_eps", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("w_router", ctypes.c_void_p), ("b_router", ctypes.c_void_p), ("g_rms", ctypes.c_void_p),
+        ("w_up", ctypes.c_void_p), ("w_gate", ctypes.c_void_p), ("w_down", ctypes.c_void_p),
+    ]
+
+
+class BlockffnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, strerror(code), code))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it is missing (build it first)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libblockffn.so is not built: run `python -m paper_2507_08771_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        lp = ctypes.POINTER(BlockffnLayer)
+        L.blockffn_router.argtypes = [lp, vp, vp, i64, i32, vp, vp, vp]
+        L.blockffn_chunk_union.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.blockffn_sparse_ffn.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
+        L.blockffn_dense_ffn.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
+        L.blockffn_workspace_bytes.argtypes = [lp, i64, i32]
+        L.blockffn_workspace_bytes.restype = sz
+        L.blockffn_strerror.argtypes = [ctypes.c_int]
+        L.blockffn_strerror.restype = ctypes.c_char_p
+        L.blockffn_version.restype = ctypes.c_int
+        for n in ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn"):
+            getattr(L, n).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().blockffn_strerror(int(code)).decode()
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise BlockffnError(rc, where)
+
+
+class Layer:
+    """Device weights of ``n_layers`` stacked layers plus the C struct describing them."""
+
+    def __init__(self, w_router, w_up, w_down, w_gate=None, b_router=None, g_rms=None, eps: float = 1e-6):
+        if w_router.dim() == 2:   # a single layer given without the leading dimension
+            w_router, w_up, w_down = w_router[None], w_up[None], w_down[None]
+            w_gate = None if w_gate is None else w_gate[None]
+            b_router = None if b_router is None else b_router[None]
+            g_rms = None if g_rms is None else g_rms[None]
+        self.n_layers, self.E, self.d = w_router.shape
+        self.d_e = w_up.shape[2]
+        assert w_up.shape == (self.n_layers, self.E, self.d_e, self.d)
+        assert w_down.shape == (self.n_layers, self.E, self.d, self.d_e)
+        self.wdtype = BF16 if w_router.dtype == torch.bfloat16 else F32
+        self.tensors = [t.contiguous() if t is not None else None
+                        for t in (w_router, b_router, g_rms, w_up, w_gate, w_down)]
+        self.gated = w_gate is not None
+        self.W = (self.E + 63) // 64
+        self.device = w_router.device
+        t = self.tensors
+        self.c = BlockffnLayer(self.d, self.E, self.d_e, self.wdtype,
+                               EXPERT_GATED if self.gated else EXPERT_SWISH, self.n_layers, float(eps), 0,
+                               *[None if q is None else q.data_ptr() for q in t])
+
+    @classmethod
+    def from_dict(cls, layers: Dict[str, torch.Tensor], eps: float = 1e-6, gain: bool = True) -> "Layer":
+        return cls(layers["w_router"], layers["w_up"], layers["w_down"], layers.get("w_gate"),
+                   layers.get("b_router"), layers.get("g_rms") if gain else None, eps)
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def blockffn_workspace_bytes(layer: Layer, n_chunks: int, k: int) -> int:
+    return int(lib().blockffn_workspace_bytes(layer.ref(), n_chunks, k))
+
+
+def blockffn_router(layer: Layer, x: torch.Tensor, n_chunks: int, k: int, scores: torch.Tensor,
+                    token_mask: torch.Tensor, chunk_layer: Optional[torch.Tensor] = None, stream=None):
+    _check(lib().blockffn_router(layer.ref(), _p(chunk_layer), _p(x), n_chunks, k, _p(scores), _p(token_mask),
+                                 _stream(stream)), "blockffn_router")
+
+
+def blockffn_chunk_union(token_mask: torch.Tensor, n_chunks: int, k: int, n_experts: int, union_mask: torch.Tensor,
+                         active_idx: torch.Tensor, n_active: torch.Tensor, stats: Optional[torch.Tensor] = None,
+                         stream=None):
+    _check(lib().blockffn_chunk_union(_p(token_mask), n_chunks, k, n_experts, _p(union_mask), _p(active_idx),
+                                      _p(n_active), _p(stats), _stream(stream)), "blockffn_chunk_union")
+
+
+def blockffn_sparse_ffn(layer: Layer, x, scores, token_mask, active_idx, n_active, n_chunks: int, k: int, y,
+                        workspace: torch.Tensor, chunk_layer=None, stream=None):
+    _check(lib().blockffn_sparse_ffn(layer.ref(), _p(chunk_layer), _p(x), _p(scores), _p(token_mask), _p(active_idx),
+                                     _p(n_active), n_chunks, k, _p(y), _p(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)),
+           "blockffn_sparse_ffn")
+
+
+def blockffn_dense_ffn(layer: Layer, x, scores, n_chunks: int, k: int, y, workspace: torch.Tensor,
+                       chunk_layer=None, stream=None):
+    _check(lib().blockffn_dense_ffn(layer.ref(), _p(chunk_layer), _p(x), _p(scores), n_chunks, k, _p(y),
+                                    _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "blockffn_dense_ffn")
+
+
+class Buffers:
+    """Device buffers for one batch shape: outputs of the three stages and the workspace."""
+
+    def __init__(self, layer: Layer, n_chunks: int, k: int):
+        dev, T = layer.device, n_chunks * k
+        self.n_chunks, self.k = n_chunks, k
+        self.scores = torch.empty((T, layer.E), dtype=torch.float32, device=dev)
+        self.token_mask = torch.empty((T, layer.W), dtype=torch.int64, device=dev)
+        self.union_mask = torch.empty((n_chunks, layer.W), dtype=torch.int64, device=dev)
+        self.active_idx = torch.empty((n_chunks, layer.E), dtype=torch.int32, device=dev)
+        self.n_active = torch.empty((n_chunks,), dtype=torch.int32, device=dev)
+        self.stats = torch.zeros((2,), dtype=torch.int64, device=dev)
+        self.y = torch.empty((T, layer.d), dtype=torch.float32, device=dev)
+        nbytes = max(blockffn_workspace_bytes(layer, n_chunks, k), 256)
+        self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+
+
+def forward_chunks(layer: Layer, x: torch.Tensor, buf: Buffers, chunk_layer=None, stream=None):
+    """Router -> chunk union -> chunk-sparse FFN: three enqueues on one stream, nothing else."""
+    C, k = buf.n_chunks, buf.k
+    blockffn_router(layer, x, C, k, buf.scores, buf.token_mask, chunk_layer, stream)
+    blockffn_chunk_union(buf.token_mask, C, k, layer.E, buf.union_mask, buf.active_idx, buf.n_active, buf.stats,
+                         stream)
+    blockffn_sparse_ffn(layer, x, buf.scores, buf.token_mask, buf.active_idx, buf.n_active, C, k, buf.y,
+                        buf.workspace, chunk_layer, stream)
+    return buf.y

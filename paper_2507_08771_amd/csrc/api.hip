@@ -1,0 +1,147 @@
+// C ABI of the library: argument checking and dispatch.  No kernel lives here.
+#include "common.hpp"
+
+using namespace blockffn;
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Returns BLOCKFFN_OK and fills `v`, or the error code.
+int check_layer(const blockffn_layer *l, LayerView &v) {
+  if (l == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (l->d < 8 || l->d % 8 != 0 || l->d_e < 8 || l->d_e % 8 != 0) return BLOCKFFN_ERR_INVALID;
+  if (l->n_experts < 1 || l->n_layers < 1) return BLOCKFFN_ERR_INVALID;
+  if (!(l->rms_eps >= 0.0f)) return BLOCKFFN_ERR_INVALID;
+  if (l->expert_kind != BLOCKFFN_EXPERT_SWISH && l->expert_kind != BLOCKFFN_EXPERT_GATED)
+    return BLOCKFFN_ERR_INVALID;
+  if (l->w_router == nullptr || l->w_up == nullptr || l->w_down == nullptr) return BLOCKFFN_ERR_INVALID;
+  if ((l->expert_kind == BLOCKFFN_EXPERT_GATED) != (l->w_gate != nullptr)) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(l->w_router, 16) || !aligned(l->w_up, 16) || !aligned(l->w_down, 16) || !aligned(l->w_gate, 16))
+    return BLOCKFFN_ERR_INVALID;
+  if (!aligned(l->b_router, 4) || !aligned(l->g_rms, 4)) return BLOCKFFN_ERR_INVALID;
+  if (l->wdtype != BLOCKFFN_F32 && l->wdtype != BLOCKFFN_BF16) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (l->n_experts > kMaxExperts || l->d_e > kMaxDe || l->d > kMaxD) return BLOCKFFN_ERR_UNSUPPORTED;
+  v.d = l->d;
+  v.E = l->n_experts;
+  v.d_e = l->d_e;
+  v.n_layers = l->n_layers;
+  v.W = (l->n_experts + 63) / 64;
+  v.eps = l->rms_eps;
+  v.w_router = l->w_router;
+  v.b_router = l->b_router;
+  v.g_rms = l->g_rms;
+  v.w_up = l->w_up;
+  v.w_gate = l->w_gate;
+  v.w_down = l->w_down;
+  return BLOCKFFN_OK;
+}
+
+int check_chunks(int64_t n_chunks, int32_t k) {
+  if (n_chunks < 0 || k < 1) return BLOCKFFN_ERR_INVALID;
+  if (k > kMaxK) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (n_chunks > (int64_t)1 << 40) return BLOCKFFN_ERR_UNSUPPORTED;
+  return BLOCKFFN_OK;
+}
+
+size_t workspace_need(const LayerView &v, int64_t n_chunks, int32_t k) {
+  // mid[chunk][slot][token][neuron] fp32, slots sized for the worst case (every expert active)
+  size_t bytes = (size_t)n_chunks * v.E * (size_t)k * v.d_e * sizeof(float);
+  return (bytes + 255) & ~(size_t)255;
+}
+
+int ffn_common(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, const float *scores,
+               const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active, bool dense,
+               int64_t n_chunks, int32_t k, float *y, void *workspace, size_t workspace_bytes, void *stream) {
+  LayerView v;
+  int rc = check_layer(layer, v);
+  if (rc != BLOCKFFN_OK) return rc;
+  rc = check_chunks(n_chunks, k);
+  if (rc != BLOCKFFN_OK) return rc;
+  if (x == nullptr || scores == nullptr || y == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (!dense && (token_mask == nullptr || active_idx == nullptr || n_active == nullptr)) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(x, 16) || !aligned(y, 16) || !aligned(scores, 4)) return BLOCKFFN_ERR_INVALID;
+  if (n_chunks == 0) return BLOCKFFN_OK;
+  const size_t need = workspace_need(v, n_chunks, k);
+  if (workspace == nullptr || !aligned(workspace, 256)) return BLOCKFFN_ERR_INVALID;
+  if (workspace_bytes < need) return BLOCKFFN_ERR_WORKSPACE;
+  const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
+  hipError_t err = launch_ffn_generic(v, layer->wdtype, gated, chunk_layer, x, scores, dense ? nullptr : token_mask,
+                                      dense ? nullptr : active_idx, dense ? nullptr : n_active, n_chunks, k, y,
+                                      static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int blockffn_router(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, int64_t n_chunks,
+                    int32_t k, float *scores, uint64_t *token_mask, void *stream) {
+  LayerView v;
+  int rc = check_layer(layer, v);
+  if (rc != BLOCKFFN_OK) return rc;
+  rc = check_chunks(n_chunks, k);
+  if (rc != BLOCKFFN_OK) return rc;
+  if (x == nullptr || scores == nullptr || token_mask == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(x, 16) || !aligned(scores, 4) || !aligned(token_mask, 8)) return BLOCKFFN_ERR_INVALID;
+  if (n_chunks == 0) return BLOCKFFN_OK;
+  hipError_t err = launch_router(v, layer->wdtype, chunk_layer, x, n_chunks, k, scores, token_mask,
+                                 static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
+int blockffn_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int32_t k, int32_t n_experts,
+                         uint64_t *union_mask, int32_t *active_idx, int32_t *n_active, int64_t *stats,
+                         void *stream) {
+  if (n_experts < 1) return BLOCKFFN_ERR_INVALID;
+  int rc = check_chunks(n_chunks, k);
+  if (rc != BLOCKFFN_OK) return rc;
+  if (n_experts > kMaxExperts) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (token_mask == nullptr || union_mask == nullptr || active_idx == nullptr || n_active == nullptr)
+    return BLOCKFFN_ERR_INVALID;
+  if (!aligned(token_mask, 8) || !aligned(union_mask, 8) || !aligned(active_idx, 4) || !aligned(n_active, 4) ||
+      !aligned(stats, 8))
+    return BLOCKFFN_ERR_INVALID;
+  if (n_chunks == 0) return BLOCKFFN_OK;
+  hipError_t err = launch_chunk_union(token_mask, n_chunks, k, n_experts, union_mask, active_idx, n_active, stats,
+                                      static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
+int blockffn_sparse_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, const float *scores,
+                        const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
+                        int64_t n_chunks, int32_t k, float *y, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+  return ffn_common(layer, chunk_layer, x, scores, token_mask, active_idx, n_active, false, n_chunks, k, y,
+                    workspace, workspace_bytes, stream);
+}
+
+int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, const float *scores,
+                       int64_t n_chunks, int32_t k, float *y, void *workspace, size_t workspace_bytes,
+                       void *stream) {
+  return ffn_common(layer, chunk_layer, x, scores, nullptr, nullptr, nullptr, true, n_chunks, k, y, workspace,
+                    workspace_bytes, stream);
+}
+
+size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k) {
+  LayerView v;
+  if (check_layer(layer, v) != BLOCKFFN_OK) return 0;
+  if (check_chunks(n_chunks, k) != BLOCKFFN_OK) return 0;
+  return workspace_need(v, n_chunks, k);
+}
+
+const char *blockffn_strerror(int code) {
+  switch (code) {
+    case BLOCKFFN_OK: return "ok";
+    case BLOCKFFN_ERR_INVALID: return "invalid argument";
+    case BLOCKFFN_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case BLOCKFFN_ERR_WORKSPACE: return "workspace too small";
+    case BLOCKFFN_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown error code";
+  }
+}
+
+int blockffn_version(void) { return 100; }
+
+}  // extern "C"

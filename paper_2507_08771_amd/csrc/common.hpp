@@ -1,0 +1,98 @@
+// Shared device helpers of the gfx950 kernels: weight widening, 128-bit loads, wave64
+// reductions, and the POD view of a layer that kernels take by value.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/blockffn.h"
+
+namespace blockffn {
+
+constexpr int kWave = 64;
+constexpr int kMaxExperts = 256;
+constexpr int kMaxMaskWords = kMaxExperts / 64;
+constexpr int kMaxK = 512;
+constexpr int kMaxDe = 1024;
+constexpr int kMaxD = 16384;
+
+// What a kernel needs to know about the layer; filled from blockffn_layer after validation.
+struct LayerView {
+  int d, E, d_e, n_layers, W;
+  float eps;
+  const void *w_router;
+  const float *b_router;
+  const float *g_rms;
+  const void *w_up;
+  const void *w_gate;
+  const void *w_down;
+};
+
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// Eight consecutive weights starting at element index `idx` (a multiple of 8), widened to fp32.
+template <typename WT>
+__device__ __forceinline__ void load8(const void *base, size_t idx, float (&w)[8]);
+
+template <>
+__device__ __forceinline__ void load8<float>(const void *base, size_t idx, float (&w)[8]) {
+  const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + idx);
+  float4 a = p[0], b = p[1];
+  w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+  w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+
+template <>
+__device__ __forceinline__ void load8<bf16_t>(const void *base, size_t idx, float (&w)[8]) {
+  const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + idx);
+  w[0] = bf16_lo(v.x); w[1] = bf16_hi(v.x);
+  w[2] = bf16_lo(v.y); w[3] = bf16_hi(v.y);
+  w[4] = bf16_lo(v.z); w[5] = bf16_hi(v.z);
+  w[6] = bf16_lo(v.w); w[7] = bf16_hi(v.w);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+__device__ __forceinline__ uint64_t wave_or(uint64_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v |= __shfl_xor(v, off, kWave);
+  return v;
+}
+
+__device__ __forceinline__ long long wave_sum_i64(long long v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// Swish with beta = 1 (SiLU), full-precision exponential.
+__device__ __forceinline__ float swish(float u) { return u / (1.0f + expf(-u)); }
+
+__device__ __forceinline__ int clamp_layer(const int32_t *chunk_layer, int64_t c, int n_layers) {
+  if (chunk_layer == nullptr) return 0;
+  int l = chunk_layer[c];
+  return l < 0 ? 0 : (l >= n_layers ? n_layers - 1 : l);
+}
+
+// Launchers implemented in the .hip files (host side).  Each returns a hipError_t.
+hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
+                         int64_t n_chunks, int k, float *scores, uint64_t *token_mask, hipStream_t s);
+hipError_t launch_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int k, int E,
+                              uint64_t *union_mask, int32_t *active_idx, int32_t *n_active,
+                              int64_t *stats, hipStream_t s);
+// active_idx == nullptr selects the dense path (every expert, no masking).
+hipError_t launch_ffn_generic(const LayerView &L, int wdtype, bool gated, const int32_t *chunk_layer,
+                              const float *x, const float *scores, const uint64_t *token_mask,
+                              const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
+                              int k, float *y, float *mid, hipStream_t s);
+
+}  // namespace blockffn

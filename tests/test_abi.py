@@ -1,0 +1,112 @@
+"""The C-ABI library loads without a GPU, exports what the header declares, and rejects bad
+arguments with the documented codes before anything is launched."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_08771_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "blockffn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(blockffn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = header_functions()
+    assert set(B.EXPORTS) <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.blockffn_version() == 100
+
+
+def test_binding_has_the_same_names():
+    for n in header_functions():
+        if n in ("blockffn_strerror", "blockffn_version"):
+            continue
+        assert hasattr(B, n), n
+
+
+def test_strerror():
+    assert B.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert B.strerror(code) not in ("ok", "unknown error code")
+    assert B.strerror(-99) == "unknown error code"
+
+
+def layer(**kw):
+    base = dict(d=2048, n_experts=64, d_e=128, wdtype=B.BF16, expert_kind=B.EXPERT_GATED, n_layers=1,
+                rms_eps=1e-6, reserved=0, w_router=0x1000, b_router=None, g_rms=None, w_up=0x2000,
+                w_gate=0x3000, w_down=0x4000)
+    base.update(kw)
+    return B.BlockffnLayer(*[base[f[0]] for f in B.BlockffnLayer._fields_])
+
+
+FAKE = ctypes.c_void_p(0x10000)   # never dereferenced: every call below fails validation or has no chunks
+
+
+def router_rc(lay, n_chunks=1, k=8, x=FAKE, scores=FAKE, mask=FAKE):
+    return B.lib().blockffn_router(ctypes.byref(lay), None, x, n_chunks, k, scores, mask, None)
+
+
+def test_invalid_arguments_are_rejected_without_a_gpu():
+    lib = B.lib()
+    assert router_rc(layer(), n_chunks=0) == B.OK                    # nothing to do is fine
+    assert lib.blockffn_router(None, None, FAKE, 1, 8, FAKE, FAKE, None) == B.ERR_INVALID
+    assert router_rc(layer(), x=None) == B.ERR_INVALID
+    assert router_rc(layer(), scores=None) == B.ERR_INVALID
+    assert router_rc(layer(), k=0) == B.ERR_INVALID
+    assert router_rc(layer(), n_chunks=-1) == B.ERR_INVALID
+    assert router_rc(layer(), k=513) == B.ERR_UNSUPPORTED
+    assert router_rc(layer(d=2044)) == B.ERR_INVALID
+    assert router_rc(layer(d_e=12)) == B.ERR_INVALID
+    assert router_rc(layer(n_experts=0)) == B.ERR_INVALID
+    assert router_rc(layer(n_experts=257)) == B.ERR_UNSUPPORTED
+    assert router_rc(layer(d_e=2048)) == B.ERR_UNSUPPORTED
+    assert router_rc(layer(wdtype=7)) == B.ERR_UNSUPPORTED
+    assert router_rc(layer(expert_kind=3)) == B.ERR_INVALID
+    assert router_rc(layer(n_layers=0)) == B.ERR_INVALID
+    assert router_rc(layer(rms_eps=-1.0)) == B.ERR_INVALID
+    assert router_rc(layer(rms_eps=float("nan"))) == B.ERR_INVALID
+    assert router_rc(layer(w_router=None)) == B.ERR_INVALID
+    assert router_rc(layer(w_up=0x2008)) == B.ERR_INVALID            # not 16-byte aligned
+    assert router_rc(layer(w_gate=None)) == B.ERR_INVALID            # gated needs w_gate
+    assert router_rc(layer(expert_kind=B.EXPERT_SWISH)) == B.ERR_INVALID   # non-gated must not pass one
+    assert router_rc(layer(expert_kind=B.EXPERT_SWISH, w_gate=None), n_chunks=0) == B.OK
+
+
+def test_union_and_ffn_argument_checks():
+    lib = B.lib()
+    assert lib.blockffn_chunk_union(FAKE, 0, 8, 64, FAKE, FAKE, FAKE, None, None) == B.OK
+    assert lib.blockffn_chunk_union(None, 1, 8, 64, FAKE, FAKE, FAKE, None, None) == B.ERR_INVALID
+    assert lib.blockffn_chunk_union(FAKE, 1, 0, 64, FAKE, FAKE, FAKE, None, None) == B.ERR_INVALID
+    assert lib.blockffn_chunk_union(FAKE, 1, 8, 0, FAKE, FAKE, FAKE, None, None) == B.ERR_INVALID
+    assert lib.blockffn_chunk_union(FAKE, 1, 8, 300, FAKE, FAKE, FAKE, None, None) == B.ERR_UNSUPPORTED
+    assert lib.blockffn_chunk_union(FAKE, 1, 600, 64, FAKE, FAKE, FAKE, None, None) == B.ERR_UNSUPPORTED
+    lay = layer()
+    need = lib.blockffn_workspace_bytes(ctypes.byref(lay), 4, 8)
+    assert need >= 4 * 64 * 8 * 128 * 4 and need % 256 == 0
+    assert lib.blockffn_workspace_bytes(ctypes.byref(layer(d=3)), 4, 8) == 0
+    sparse = lambda ws, nbytes, n_act=FAKE: lib.blockffn_sparse_ffn(
+        ctypes.byref(lay), None, FAKE, FAKE, FAKE, FAKE, n_act, 4, 8, FAKE, ws, nbytes, None)
+    assert sparse(FAKE, need - 1) == B.ERR_WORKSPACE
+    assert sparse(None, need) == B.ERR_INVALID
+    assert sparse(ctypes.c_void_p(0x10010), need) == B.ERR_INVALID   # workspace not 256-byte aligned
+    assert sparse(FAKE, need, n_act=None) == B.ERR_INVALID
+    assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 4, 8, FAKE, FAKE, need - 1, None) == B.ERR_WORKSPACE
+    assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, None, 4, 8, FAKE, FAKE, need, None) == B.ERR_INVALID
+    assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 0, 8, FAKE, None, 0, None) == B.OK
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libblockffn.so"))
+    with pytest.raises(RuntimeError):
+        B.lib()

@@ -1,0 +1,180 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Integer results bit-exact; floating point per parity_util."""
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_08771_amd import binding as B
+from paper_2507_08771_amd import workloads as wl
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def both(w, n_layers=1, dense=True, gain=False, eps=1e-6, use_bias=True, x_override=None):
+    layers = wl.make_layers(w, n_layers, gain=gain)
+    cl = wl.make_chunk_layer(w, n_layers) if n_layers > 1 else None
+    x = wl.make_tokens(w, layers, cl) if x_override is None else x_override
+    print("case", w, "layers", n_layers, flush=True)
+    ref = pu.run_oracle(layers, x, w.k, cl, eps=eps, dense=dense, use_gain=gain, use_bias=use_bias)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, cl, eps=eps, dense=dense, use_gain=gain, use_bias=use_bias)
+    return ref, gpu
+
+
+def test_tiny_f32_k4_full_config():
+    w = wl.WORKLOADS["tiny_f32_k4"]
+    ref, gpu = both(w)
+    pu.assert_integers_equal(gpu, ref)
+    errs = pu.assert_floats_close(gpu, ref, "f32", dense=True)
+    print(errs)
+    # sparsity of the generated inputs is what the configuration asks for (about 80 % / 70 %)
+    tls = ref["stats"][0] / (w.n_tok * w.E)
+    assert 0.7 < tls < 0.9
+
+
+@pytest.mark.parametrize("gated", [True, False])
+@pytest.mark.parametrize("wdtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,E,d_e,k,C", [
+    (264, 16, 24, 4, 7),      # d not a multiple of the column block, ragged everything
+    (512, 63, 64, 8, 9),
+    (2048, 64, 128, 8, 6),    # the k = 8 shape
+    (1024, 32, 128, 1, 33),   # single-token decode
+    (256, 65, 16, 3, 5),      # two mask words
+    (512, 130, 32, 9, 4),     # three mask words, token tile with a tail
+    (256, 1, 8, 2, 3),        # a single expert
+    (2304, 64, 136, 12, 3),   # d > one column block
+])
+def test_shapes(d, E, d_e, k, C, wdtype, gated):
+    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype=wdtype, gated=gated, k=k, n_chunks=C, sigma=0.3, seed=d + E + k)
+    ref, gpu = both(w)
+    pu.assert_integers_equal(gpu, ref)
+    print(pu.assert_floats_close(gpu, ref, wdtype, dense=True))
+
+
+@pytest.mark.parametrize("k,d_e", [(32, 256), (40, 64)])
+def test_large_chunks(k, d_e):
+    w = wl.Workload("t", d=2048, E=64, d_e=d_e, wdtype="bf16", gated=True, k=k, n_chunks=3, sigma=0.5, seed=k)
+    ref, gpu = both(w, dense=False)
+    pu.assert_integers_equal(gpu, ref)
+    print(pu.assert_floats_close(gpu, ref, "bf16"))
+
+
+def test_layer_rotation_gain_and_eps():
+    # chunks walk through 5 distinct weight sets; RMSNorm gain drawn at random, large eps
+    w = wl.Workload("t", d=512, E=48, d_e=32, wdtype="bf16", gated=True, k=8, n_chunks=23, sigma=0.3, seed=5)
+    ref, gpu = both(w, n_layers=5, gain=True, eps=0.25)
+    pu.assert_integers_equal(gpu, ref)
+    print(pu.assert_floats_close(gpu, ref, "bf16", dense=True))
+
+
+def test_no_bias_is_the_papers_router():
+    w = wl.Workload("t", d=512, E=64, d_e=32, wdtype="bf16", gated=False, k=8, n_chunks=8, sigma=0.3, seed=6)
+    layers = wl.make_layers(w, 1, bias=False)
+    x = wl.make_tokens(w, layers)
+    ref = pu.run_oracle(layers, x, w.k, use_bias=False)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, use_bias=False)
+    pu.assert_integers_equal(gpu, ref)
+    pu.assert_floats_close(gpu, ref, "bf16")
+    assert 0.4 < ref["stats"][0] / (w.n_tok * w.E) < 0.6    # half of the pre-activations are negative
+
+
+def test_degenerate_chunks():
+    # chunk 0: zero input with negative bias -> empty union, zero output;
+    # chunk 1: strongly positive bias is emulated by a huge positive input along every router row
+    w = wl.Workload("t", d=256, E=40, d_e=16, wdtype="f32", gated=True, k=4, n_chunks=4, sigma=0.3, seed=8)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    x[:4] = 0.0
+    wr = layers["w_router"][0]
+    x[4:8] = 50.0 * wr.sum(dim=0)[None, :] / wr.sum(dim=0).norm() * (w.d ** 0.5)
+    ref = pu.run_oracle(layers, x, w.k, dense=True)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, dense=True)
+    pu.assert_integers_equal(gpu, ref)
+    pu.assert_floats_close(gpu, ref, "f32", dense=True)
+    assert gpu["n_active"][0] == 0 and np.all(gpu["y"][:4] == 0) and np.all(gpu["active_idx"][0] == -1)
+    assert gpu["n_active"][1] > gpu["n_active"][2:].max()
+
+
+def test_zero_gain_keeps_the_mask_bit():
+    w = wl.Workload("t", d=256, E=16, d_e=16, wdtype="f32", gated=False, k=4, n_chunks=6, sigma=0.3, seed=9)
+    layers = wl.make_layers(w, 1, gain=True)
+    layers["g_rms"][0, ::3] = 0.0
+    x = wl.make_tokens(w, layers)
+    ref = pu.run_oracle(layers, x, w.k)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k)
+    np.testing.assert_array_equal(gpu["token_mask"], ref["token_mask"])
+    np.testing.assert_array_equal(gpu["active_idx"], ref["active_idx"])
+    e = pu.row_rel_err(gpu["y"], ref["y"]).max()
+    assert e <= 1e-5
+    assert np.all(gpu["scores"][:, ::3] == 0)
+
+
+def test_exact_arithmetic_router_fixture():
+    # every partial sum of A0 is exact in fp32 (see the oracle pin of the same name), so the
+    # masks must agree with integer arithmetic whatever the summation order of the kernel
+    rng = np.random.default_rng(11)
+    E, d, k, C = 70, 512, 8, 8
+    T = k * C
+    xi = rng.integers(-4, 5, (T, d))
+    wi = rng.integers(-8, 9, (E, d))
+    bi = rng.integers(-300, 300, E)
+    layers = dict(w_router=torch.tensor(wi / 64.0, dtype=torch.float32)[None],
+                  b_router=torch.tensor(bi / 256.0, dtype=torch.float32)[None],
+                  g_rms=torch.ones((1, E)), w_up=torch.zeros((1, E, 8, d)), w_gate=None,
+                  w_down=torch.zeros((1, E, d, 8)))
+    x = torch.tensor(xi / 4.0, dtype=torch.float32)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), k)
+    exact = xi @ wi.T + bi
+    want = np.zeros((T, 2), np.uint64)
+    for t in range(T):
+        for i in np.nonzero(exact[t] > 0)[0]:
+            want[t, i // 64] |= np.uint64(1) << np.uint64(i % 64)
+    np.testing.assert_array_equal(gpu["token_mask"], want)
+    ref = pu.run_oracle(layers, x, k)
+    pu.assert_integers_equal(gpu, ref)
+
+
+def test_stats_accumulate_and_results_repeat_bitwise():
+    w = wl.Workload("t", d=512, E=64, d_e=64, wdtype="bf16", gated=True, k=8, n_chunks=16, sigma=0.3, seed=10)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k)
+    L, buf = gpu["_layer"], gpu["_buf"]
+    y1 = buf.y.clone()
+    B.forward_chunks(L, x.cuda(), buf)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.y, y1)                                   # one writer per element: repeatable
+    np.testing.assert_array_equal(buf.stats.cpu().numpy(), 2 * gpu["stats"])   # counts are added to
+
+
+def test_full_size_spec_k8_sampled_chunks():
+    """The k = 8 configuration at full size, in the launch configuration the benchmark times
+    (2048 chunks rotating through distinct weight sets), checked on sampled chunks."""
+    w = wl.WORKLOADS["spec_k8"]
+    n_layers = 4
+    layers = wl.make_layers(w, n_layers, device="cuda")
+    cl = wl.make_chunk_layer(w, n_layers, device="cuda")
+    x = wl.make_tokens(w, layers, cl, device="cuda")
+    print("generated", flush=True)
+    gpu = pu.run_gpu(layers, x, w.k, cl, dense=True)
+    chunks = [0, 1, 2, 3, 517, 1023, 1024, 2046, 2047]
+    layers_cpu = {n: (None if t is None else t.cpu()) for n, t in layers.items()}
+    ref = pu.run_oracle(layers_cpu, x.cpu(), w.k, cl.cpu(), dense=True, chunks=chunks)
+    pu.assert_integers_equal(gpu, ref, chunks=chunks, k=w.k)
+    rows = (np.asarray(chunks)[:, None] * w.k + np.arange(w.k)[None, :]).reshape(-1)
+    print(pu.assert_floats_close(gpu, ref, "bf16", rows=rows, dense=True))
+    # properties that hold at any size
+    C, E = w.n_chunks, w.E
+    pop = lambda m: np.array([bin(int(v)).count("1") for v in m.reshape(-1)]).reshape(m.shape).sum(axis=1)
+    np.testing.assert_array_equal(pop(gpu["union_mask"]), gpu["n_active"])
+    tm = gpu["token_mask"].reshape(C, w.k)
+    np.testing.assert_array_equal(np.bitwise_or.reduce(tm, axis=1), gpu["union_mask"][:, 0])
+    assert gpu["stats"][1] == C * E - gpu["n_active"].sum()
+    assert gpu["stats"][0] == w.n_tok * E - pop(gpu["token_mask"]).sum()
+    e_tls, e_cls = wl.expected_sparsity(w.k, w.sigma)
+    assert abs(gpu["stats"][0] / (w.n_tok * E) - e_tls) < 0.01
+    assert abs(gpu["stats"][1] / (C * E) - e_cls) < 0.02
+    y = gpu["y"]
+    assert np.isfinite(y).all()
