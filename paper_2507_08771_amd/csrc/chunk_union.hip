@@ -35,6 +35,7 @@ __global__ __launch_bounds__(kThreads) void chunk_union_kernel(const uint64_t *_
       tok_active += __popcll(m);
     }
     u = wave_or(u);
+    if (wd == W - 1 && (E & 63)) u &= (~0ull) >> (64 - (E & 63));   // never trust bits at or above E
     if (lane == 0) union_mask[c * W + wd] = u;
     const int i = wd * 64 + lane;
     const bool bit = (u >> lane) & 1;
