@@ -110,6 +110,21 @@ int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, 
                        const float *scores, int64_t n_chunks, int32_t k, float *y,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* The two halves of blockffn_sparse_ffn as separate enqueues (Sec. 3.3 describes the up and
+ * the down projection as two sparse matrix products with the intermediate `mid` between
+ * them).  `up` fills the workspace with mid = mask . A . Swish-or-gated(W_up^T x) for the
+ * experts of the union; `down` reduces it through W_down into y.  Calling up then down with
+ * the same arguments on one stream equals blockffn_sparse_ffn.  active_idx == NULL (with
+ * token_mask and n_active NULL too) selects the dense path in both. */
+int blockffn_sparse_ffn_up(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                           const float *scores, const uint64_t *token_mask,
+                           const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
+                           int32_t k, void *workspace, size_t workspace_bytes, void *stream);
+int blockffn_sparse_ffn_down(const blockffn_layer *layer, const int32_t *chunk_layer,
+                             const int32_t *active_idx, const int32_t *n_active,
+                             int64_t n_chunks, int32_t k, float *y, const void *workspace,
+                             size_t workspace_bytes, void *stream);
+
 /* Bytes of workspace the two FFN entry points need for this shape (0 on invalid arguments). */
 size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k);
 

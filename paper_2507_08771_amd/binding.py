@@ -22,7 +22,8 @@ EXPERT_SWISH, EXPERT_GATED = 0, 1
 OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
-           "blockffn_workspace_bytes", "blockffn_strerror", "blockffn_version")
+           "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_workspace_bytes", "blockffn_strerror",
+           "blockffn_version")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -59,12 +60,15 @@ def lib() -> ctypes.CDLL:
         L.blockffn_chunk_union.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp]
         L.blockffn_sparse_ffn.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
         L.blockffn_dense_ffn.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
+        L.blockffn_sparse_ffn_up.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
+        L.blockffn_sparse_ffn_down.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
         L.blockffn_workspace_bytes.argtypes = [lp, i64, i32]
         L.blockffn_workspace_bytes.restype = sz
         L.blockffn_strerror.argtypes = [ctypes.c_int]
         L.blockffn_strerror.restype = ctypes.c_char_p
         L.blockffn_version.restype = ctypes.c_int
-        for n in ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn"):
+        for n in ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
+                  "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down"):
             getattr(L, n).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -152,6 +156,21 @@ def blockffn_dense_ffn(layer: Layer, x, scores, n_chunks: int, k: int, y, worksp
     _check(lib().blockffn_dense_ffn(layer.ref(), _p(chunk_layer), _p(x), _p(scores), n_chunks, k, _p(y),
                                     _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "blockffn_dense_ffn")
+
+
+def blockffn_sparse_ffn_up(layer: Layer, x, scores, token_mask, active_idx, n_active, n_chunks: int, k: int,
+                           workspace: torch.Tensor, chunk_layer=None, stream=None):
+    _check(lib().blockffn_sparse_ffn_up(layer.ref(), _p(chunk_layer), _p(x), _p(scores), _p(token_mask),
+                                        _p(active_idx), _p(n_active), n_chunks, k, _p(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)),
+           "blockffn_sparse_ffn_up")
+
+
+def blockffn_sparse_ffn_down(layer: Layer, active_idx, n_active, n_chunks: int, k: int, y, workspace: torch.Tensor,
+                             chunk_layer=None, stream=None):
+    _check(lib().blockffn_sparse_ffn_down(layer.ref(), _p(chunk_layer), _p(active_idx), _p(n_active), n_chunks, k,
+                                          _p(y), _p(workspace), workspace.numel() * workspace.element_size(),
+                                          _stream(stream)), "blockffn_sparse_ffn_down")
 
 
 class Buffers:

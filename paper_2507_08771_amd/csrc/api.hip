@@ -1,4 +1,7 @@
 // C ABI of the library: argument checking and dispatch.  No kernel lives here.
+#include <algorithm>
+#include <cstdlib>
+
 #include "common.hpp"
 
 using namespace blockffn;
@@ -44,31 +47,64 @@ int check_chunks(int64_t n_chunks, int32_t k) {
   return BLOCKFFN_OK;
 }
 
-size_t workspace_need(const LayerView &v, int64_t n_chunks, int32_t k) {
-  // mid[chunk][slot][token][neuron] fp32, slots sized for the worst case (every expert active)
-  size_t bytes = (size_t)n_chunks * v.E * (size_t)k * v.d_e * sizeof(float);
-  return (bytes + 255) & ~(size_t)255;
+// BLOCKFFN_FORCE_GENERIC=1 in the environment keeps every shape on the shape-generic kernels
+// (used to compare the two implementations on the same inputs).
+bool use_stream(const LayerView &v, int wdtype, int32_t k) {
+  const char *e = std::getenv("BLOCKFFN_FORCE_GENERIC");
+  const bool forced = e != nullptr && e[0] == '1';
+  return !forced && stream_supported(v, wdtype, k);
 }
 
-int ffn_common(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, const float *scores,
-               const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active, bool dense,
+size_t workspace_need(const LayerView &v, int wdtype, int64_t n_chunks, int32_t k) {
+  // generic kernels: mid[chunk][slot][token][neuron] fp32, slots sized for the worst case
+  size_t bytes = (size_t)n_chunks * v.E * (size_t)k * v.d_e * sizeof(float);
+  bytes = (bytes + 255) & ~(size_t)255;
+  if (stream_supported(v, wdtype, k)) bytes = std::max(bytes, stream_workspace_bytes(v, n_chunks, k));
+  return bytes;
+}
+
+enum { kPhaseUp = 1, kPhaseDown = 2 };
+
+int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+               const float *scores, const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                int64_t n_chunks, int32_t k, float *y, void *workspace, size_t workspace_bytes, void *stream) {
   LayerView v;
   int rc = check_layer(layer, v);
   if (rc != BLOCKFFN_OK) return rc;
   rc = check_chunks(n_chunks, k);
   if (rc != BLOCKFFN_OK) return rc;
-  if (x == nullptr || scores == nullptr || y == nullptr) return BLOCKFFN_ERR_INVALID;
-  if (!dense && (token_mask == nullptr || active_idx == nullptr || n_active == nullptr)) return BLOCKFFN_ERR_INVALID;
-  if (!aligned(x, 16) || !aligned(y, 16) || !aligned(scores, 4)) return BLOCKFFN_ERR_INVALID;
+  // the dense path is selected by passing no list at all; a partial set of list arguments is an error
+  const bool dense = active_idx == nullptr;
+  if (dense ? (n_active != nullptr || token_mask != nullptr) : (n_active == nullptr)) return BLOCKFFN_ERR_INVALID;
+  if (phases & kPhaseUp) {
+    if (x == nullptr || scores == nullptr || (!dense && token_mask == nullptr)) return BLOCKFFN_ERR_INVALID;
+    if (!aligned(x, 16) || !aligned(scores, 4) || !aligned(token_mask, 8)) return BLOCKFFN_ERR_INVALID;
+  }
+  if (phases & kPhaseDown) {
+    if (y == nullptr || !aligned(y, 16)) return BLOCKFFN_ERR_INVALID;
+  }
+  if (!aligned(active_idx, 4) || !aligned(n_active, 4) || !aligned(chunk_layer, 4)) return BLOCKFFN_ERR_INVALID;
   if (n_chunks == 0) return BLOCKFFN_OK;
-  const size_t need = workspace_need(v, n_chunks, k);
+  const size_t need = workspace_need(v, layer->wdtype, n_chunks, k);
   if (workspace == nullptr || !aligned(workspace, 256)) return BLOCKFFN_ERR_INVALID;
   if (workspace_bytes < need) return BLOCKFFN_ERR_WORKSPACE;
   const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
-  hipError_t err = launch_ffn_generic(v, layer->wdtype, gated, chunk_layer, x, scores, dense ? nullptr : token_mask,
-                                      dense ? nullptr : active_idx, dense ? nullptr : n_active, n_chunks, k, y,
-                                      static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t err = hipSuccess;
+  if (use_stream(v, layer->wdtype, k)) {
+    if (phases & kPhaseUp)
+      err = launch_up_stream(v, gated, chunk_layer, x, scores, token_mask, active_idx, n_active, n_chunks, k,
+                             workspace, s);
+    if (err == hipSuccess && (phases & kPhaseDown))
+      err = launch_down_stream(v, chunk_layer, active_idx, n_active, n_chunks, k, workspace, y, s);
+  } else {
+    float *mid = static_cast<float *>(workspace);
+    if (phases & kPhaseUp)
+      err = launch_up_generic(v, layer->wdtype, gated, chunk_layer, x, scores, token_mask, active_idx, n_active,
+                              n_chunks, k, mid, s);
+    if (err == hipSuccess && (phases & kPhaseDown))
+      err = launch_down_generic(v, layer->wdtype, chunk_layer, active_idx, n_active, n_chunks, k, mid, y, s);
+  }
   return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
 }
 
@@ -113,22 +149,38 @@ int blockffn_sparse_ffn(const blockffn_layer *layer, const int32_t *chunk_layer,
                         const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                         int64_t n_chunks, int32_t k, float *y, void *workspace, size_t workspace_bytes,
                         void *stream) {
-  return ffn_common(layer, chunk_layer, x, scores, token_mask, active_idx, n_active, false, n_chunks, k, y,
+  if (active_idx == nullptr || n_active == nullptr || token_mask == nullptr) return BLOCKFFN_ERR_INVALID;
+  return ffn_common(kPhaseUp | kPhaseDown, layer, chunk_layer, x, scores, token_mask, active_idx, n_active, n_chunks,
+                    k, y, workspace, workspace_bytes, stream);
+}
+
+int blockffn_sparse_ffn_up(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                           const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
+                           const int32_t *n_active, int64_t n_chunks, int32_t k, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  return ffn_common(kPhaseUp, layer, chunk_layer, x, scores, token_mask, active_idx, n_active, n_chunks, k, nullptr,
                     workspace, workspace_bytes, stream);
+}
+
+int blockffn_sparse_ffn_down(const blockffn_layer *layer, const int32_t *chunk_layer, const int32_t *active_idx,
+                             const int32_t *n_active, int64_t n_chunks, int32_t k, float *y, const void *workspace,
+                             size_t workspace_bytes, void *stream) {
+  return ffn_common(kPhaseDown, layer, chunk_layer, nullptr, nullptr, nullptr, active_idx, n_active, n_chunks, k, y,
+                    const_cast<void *>(workspace), workspace_bytes, stream);
 }
 
 int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, const float *scores,
                        int64_t n_chunks, int32_t k, float *y, void *workspace, size_t workspace_bytes,
                        void *stream) {
-  return ffn_common(layer, chunk_layer, x, scores, nullptr, nullptr, nullptr, true, n_chunks, k, y, workspace,
-                    workspace_bytes, stream);
+  return ffn_common(kPhaseUp | kPhaseDown, layer, chunk_layer, x, scores, nullptr, nullptr, nullptr, n_chunks, k, y,
+                    workspace, workspace_bytes, stream);
 }
 
 size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k) {
   LayerView v;
   if (check_layer(layer, v) != BLOCKFFN_OK) return 0;
   if (check_chunks(n_chunks, k) != BLOCKFFN_OK) return 0;
-  return workspace_need(v, n_chunks, k);
+  return workspace_need(v, layer->wdtype, n_chunks, k);
 }
 
 const char *blockffn_strerror(int code) {

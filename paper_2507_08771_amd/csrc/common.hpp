@@ -89,10 +89,24 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
 hipError_t launch_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int k, int E,
                               uint64_t *union_mask, int32_t *active_idx, int32_t *n_active,
                               int64_t *stats, hipStream_t s);
-// active_idx == nullptr selects the dense path (every expert, no masking).
-hipError_t launch_ffn_generic(const LayerView &L, int wdtype, bool gated, const int32_t *chunk_layer,
-                              const float *x, const float *scores, const uint64_t *token_mask,
-                              const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
-                              int k, float *y, float *mid, hipStream_t s);
+// Shape-generic FFN kernels.  active_idx == nullptr selects the dense path (every expert, no
+// masking).  mid is fp32 [chunk][slot][token][neuron] with E slots per chunk.
+hipError_t launch_up_generic(const LayerView &L, int wdtype, bool gated, const int32_t *chunk_layer, const float *x,
+                             const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
+                             const int32_t *n_active, int64_t n_chunks, int k, float *mid, hipStream_t s);
+hipError_t launch_down_generic(const LayerView &L, int wdtype, const int32_t *chunk_layer, const int32_t *active_idx,
+                               const int32_t *n_active, int64_t n_chunks, int k, const float *mid, float *y,
+                               hipStream_t s);
+
+// Weight-streaming matrix-core kernels (bf16 weights, k <= 32, d % 512 == 0, d_e in {64,128,256}).
+// The workspace layout differs from the generic kernels': mid is stored as bf16 hi/lo planes.
+bool stream_supported(const LayerView &L, int wdtype, int k);
+size_t stream_workspace_bytes(const LayerView &L, int64_t n_chunks, int k);
+hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *x,
+                            const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
+                            const int32_t *n_active, int64_t n_chunks, int k, void *ws, hipStream_t s);
+hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
+                              const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
+                              hipStream_t s);
 
 }  // namespace blockffn

@@ -119,6 +119,11 @@ __global__ __launch_bounds__(kThreads) void down_generic_kernel(LayerView L, con
       for (int i = threadIdx.x; i < nt * d_e; i += kThreads) mid_s[i / d_e][i % d_e] = mid_cs[i];
       __syncthreads();
       if (col_ok) {
+        // one expert's contribution is summed on its own and then added: the rounding error grows
+        // with sqrt(d_e) + sqrt(slots) instead of sqrt(d_e * slots)
+        float part[kTok];
+#pragma unroll
+        for (int t = 0; t < kTok; ++t) part[t] = 0.0f;
         const size_t row = (((size_t)layer * E + e) * d + col) * d_e;
         for (int j = 0; j < d_e; j += 8) {
           float w[8];
@@ -127,10 +132,12 @@ __global__ __launch_bounds__(kThreads) void down_generic_kernel(LayerView L, con
           for (int t = 0; t < kTok; ++t) {
             if (t < nt) {
 #pragma unroll
-              for (int q = 0; q < 8; ++q) acc[t] = fmaf(w[q], mid_s[t][j + q], acc[t]);
+              for (int q = 0; q < 8; ++q) part[t] = fmaf(w[q], mid_s[t][j + q], part[t]);
             }
           }
         }
+#pragma unroll
+        for (int t = 0; t < kTok; ++t) acc[t] += part[t];
       }
     }
     if (col_ok) {
@@ -143,17 +150,14 @@ __global__ __launch_bounds__(kThreads) void down_generic_kernel(LayerView L, con
 
 }  // namespace
 
-hipError_t launch_ffn_generic(const LayerView &L, int wdtype, bool gated, const int32_t *chunk_layer,
-                              const float *x, const float *scores, const uint64_t *token_mask,
-                              const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
-                              int k, float *y, float *mid, hipStream_t s) {
+hipError_t launch_up_generic(const LayerView &L, int wdtype, bool gated, const int32_t *chunk_layer, const float *x,
+                             const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
+                             const int32_t *n_active, int64_t n_chunks, int k, float *mid, hipStream_t s) {
   if (n_chunks <= 0) return hipSuccess;
   const int64_t up_blocks = n_chunks * L.E;
-  const int col_tiles = (L.d + kThreads - 1) / kThreads;
-  const int64_t down_blocks = n_chunks * col_tiles;
-  if (up_blocks > 0x7fffffffLL || down_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (up_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   dim3 block(kThreads);
-#define BLOCKFFN_UP(WT, G)                                                                            \
+#define BLOCKFFN_UP(WT, G)                                                                                  \
   hipLaunchKernelGGL((up_generic_kernel<WT, G>), dim3((unsigned)up_blocks), block, 0, s, L, chunk_layer, x, \
                      scores, token_mask, active_idx, n_active, k, mid)
   if (wdtype == BLOCKFFN_BF16) {
@@ -162,8 +166,17 @@ hipError_t launch_ffn_generic(const LayerView &L, int wdtype, bool gated, const 
     if (gated) BLOCKFFN_UP(float, true); else BLOCKFFN_UP(float, false);
   }
 #undef BLOCKFFN_UP
-  hipError_t err = hipGetLastError();
-  if (err != hipSuccess) return err;
+  return hipGetLastError();
+}
+
+hipError_t launch_down_generic(const LayerView &L, int wdtype, const int32_t *chunk_layer, const int32_t *active_idx,
+                               const int32_t *n_active, int64_t n_chunks, int k, const float *mid, float *y,
+                               hipStream_t s) {
+  if (n_chunks <= 0) return hipSuccess;
+  const int col_tiles = (L.d + kThreads - 1) / kThreads;
+  const int64_t down_blocks = n_chunks * col_tiles;
+  if (down_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  dim3 block(kThreads);
   if (wdtype == BLOCKFFN_BF16)
     hipLaunchKernelGGL(down_generic_kernel<bf16_t>, dim3((unsigned)down_blocks), block, 0, s, L, chunk_layer,
                        active_idx, n_active, k, col_tiles, mid, y);

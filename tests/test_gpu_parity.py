@@ -34,6 +34,16 @@ def test_tiny_f32_k4_full_config():
     assert 0.7 < tls < 0.9
 
 
+@pytest.fixture(params=["auto", "generic"])
+def impl(request, monkeypatch):
+    """auto: the library picks its kernels by shape; generic: every shape on the shape-generic kernels."""
+    if request.param == "generic":
+        monkeypatch.setenv("BLOCKFFN_FORCE_GENERIC", "1")
+    else:
+        monkeypatch.delenv("BLOCKFFN_FORCE_GENERIC", raising=False)
+    return request.param
+
+
 @pytest.mark.parametrize("gated", [True, False])
 @pytest.mark.parametrize("wdtype", ["f32", "bf16"])
 @pytest.mark.parametrize("d,E,d_e,k,C", [
@@ -45,8 +55,13 @@ def test_tiny_f32_k4_full_config():
     (512, 130, 32, 9, 4),     # three mask words, token tile with a tail
     (256, 1, 8, 2, 3),        # a single expert
     (2304, 64, 136, 12, 3),   # d > one column block
+    (4096, 40, 256, 5, 3),    # two K-chunks of the streaming up kernel
+    (1536, 64, 64, 16, 5),    # two token tiles
+    (512, 130, 128, 20, 4),   # four token tiles with a ragged last one, three mask words
 ])
-def test_shapes(d, E, d_e, k, C, wdtype, gated):
+def test_shapes(d, E, d_e, k, C, wdtype, gated, impl):
+    if impl == "generic" and wdtype == "f32":
+        pytest.skip("fp32 weights always take the generic kernels")
     w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype=wdtype, gated=gated, k=k, n_chunks=C, sigma=0.3, seed=d + E + k)
     ref, gpu = both(w)
     pu.assert_integers_equal(gpu, ref)
@@ -54,7 +69,7 @@ def test_shapes(d, E, d_e, k, C, wdtype, gated):
 
 
 @pytest.mark.parametrize("k,d_e", [(32, 256), (40, 64)])
-def test_large_chunks(k, d_e):
+def test_large_chunks(k, d_e, impl):
     w = wl.Workload("t", d=2048, E=64, d_e=d_e, wdtype="bf16", gated=True, k=k, n_chunks=3, sigma=0.5, seed=k)
     ref, gpu = both(w, dense=False)
     pu.assert_integers_equal(gpu, ref)
@@ -147,6 +162,14 @@ def test_stats_accumulate_and_results_repeat_bitwise():
     torch.cuda.synchronize()
     assert torch.equal(buf.y, y1)                                   # one writer per element: repeatable
     np.testing.assert_array_equal(buf.stats.cpu().numpy(), 2 * gpu["stats"])   # counts are added to
+    # the two halves enqueued separately give the same bits as the combined entry point
+    y2 = torch.full_like(buf.y, float("nan"))
+    xd = x.cuda()
+    B.blockffn_sparse_ffn_up(L, xd, buf.scores, buf.token_mask, buf.active_idx, buf.n_active, w.n_chunks, w.k,
+                             buf.workspace)
+    B.blockffn_sparse_ffn_down(L, buf.active_idx, buf.n_active, w.n_chunks, w.k, y2, buf.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y1)
 
 
 def test_full_size_spec_k8_sampled_chunks():
