@@ -275,8 +275,10 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     const size_t row = ((size_t)layer * E + e) * d + col0 + r;
     return static_cast<const char *>(L.w_down) + row * (d_e * 2) + g * 16;
   };
-  // fragment f of a slot: K-step f / MW, row tile f % MW
-  auto frag_off = [&](int f) { return (size_t)(f % MW) * 16 * d_e * 2 + (size_t)(f / MW) * 64; };
+  // fragment f of a slot: row tile f / KSD, K-step f % KSD.  The K-steps of one row tile are
+  // consecutive so that the 64-byte halves of each 128-byte line are requested back to back
+  // (requested several loads apart they were fetched from the fabric twice).
+  auto frag_off = [&](int f) { return (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)(f % KSD) * 64; };
 
   f32x4 acc[MW][NT];
 #pragma unroll
@@ -321,15 +323,13 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       const char *cur = slot_ptr(e);
       const uint4 *bS = midS[s & 1];
 #pragma unroll
-      for (int ks = 0; ks < KSD; ++ks) {
-        uint4 b[NT];
+      for (int tile = 0; tile < MW; ++tile) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) b[nt] = bS[(ks * NT + nt) * 64 + lane];
+        for (int ks = 0; ks < KSD; ++ks) {
+          const int f = tile * KSD + ks;
 #pragma unroll
-        for (int tile = 0; tile < MW; ++tile) {
-          const int f = ks * MW + tile;
-#pragma unroll
-          for (int nt = 0; nt < NT; ++nt) acc[tile][nt] = mfma16(ring[f % kRing], b[nt], acc[tile][nt]);
+          for (int nt = 0; nt < NT; ++nt)
+            acc[tile][nt] = mfma16(ring[f % kRing], bS[(ks * NT + nt) * 64 + lane], acc[tile][nt]);
           const int fn = f + kRing;
           if (fn < kFrag) ring[f % kRing] = *reinterpret_cast<const uint4 *>(cur + frag_off(fn));
           else if (has_next) ring[f % kRing] = *reinterpret_cast<const uint4 *>(nxt + frag_off(fn - kFrag));

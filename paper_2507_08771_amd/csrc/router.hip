@@ -18,17 +18,26 @@ constexpr int kThreads = 256;  // 4 waves
 constexpr int kColsPerBlock = kThreads * 8;
 
 // v[q] (q = 0..63) summed over the 64 lanes; lane q returns the total of entry q.
-__device__ __forceinline__ float reduce_scatter64(float (&v)[64], int lane) {
+// Each step halves the number of live entries: a lane keeps the half selected by one bit of
+// its id and receives the partner's copy of the same half.
+template <int HALF>
+__device__ __forceinline__ void reduce_scatter_step(float (&v)[64], int lane) {
+  const bool upper = (lane & HALF) != 0;
 #pragma unroll
-  for (int half = 32; half >= 1; half >>= 1) {
-    const bool upper = (lane & half) != 0;
-#pragma unroll
-    for (int i = 0; i < half; ++i) {
-      const float send = upper ? v[i] : v[i + half];
-      const float keep = upper ? v[i + half] : v[i];
-      v[i] = keep + __shfl_xor(send, half, kWave);
-    }
+  for (int i = 0; i < HALF; ++i) {
+    const float send = upper ? v[i] : v[i + HALF];
+    const float keep = upper ? v[i + HALF] : v[i];
+    v[i] = keep + __shfl_xor(send, HALF, kWave);
   }
+}
+
+__device__ __forceinline__ float reduce_scatter64(float (&v)[64], int lane) {
+  reduce_scatter_step<32>(v, lane);
+  reduce_scatter_step<16>(v, lane);
+  reduce_scatter_step<8>(v, lane);
+  reduce_scatter_step<4>(v, lane);
+  reduce_scatter_step<2>(v, lane);
+  reduce_scatter_step<1>(v, lane);
   return v[0];
 }
 
