@@ -30,6 +30,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK = 8.0e12  # bytes/s, MI355X HBM3E
 
+# HBM bytes per launch of the up kernel from rocprofv3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
+# factors a plain 1 GiB device copy gives), keyed by (workload, replicas, gated); see profiles/.
+MEASURED_TRAFFIC = {("spec_k8", 32, True): 22903297 * 1024 * 2.0 + 177160 * 1024 * 1.0}
+
 
 def parse():
     p = argparse.ArgumentParser()
@@ -43,6 +47,8 @@ def parse():
     p.add_argument("--dense-steps", type=int, default=3)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-chunks", type=int, default=512)
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
     p.add_argument("--traffic-bytes", type=float, default=None,
                    help="HBM bytes per launch of the dominant kernel from rocprofv3 counters, if known")
     return p.parse_args()
@@ -97,6 +103,14 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     dev = "cuda"
+    if args.calibrate_copy:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
     w = wl.WORKLOADS[args.workload]
     if args.chunks:
         w = w.replace(n_chunks=args.chunks)
@@ -187,7 +201,9 @@ def main():
                                % (" and W_gate" if w.gated else ""),
                      "bound": "hbm", "achieved": up_bytes / up_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": up_bytes / up_s / HBM_PEAK,
-                     "traffic": args.traffic_bytes, "algorithmic_bytes": up_bytes,
+                     "traffic": args.traffic_bytes if args.traffic_bytes is not None
+                     else (MEASURED_TRAFFIC.get((w.name, R, w.gated)) if not args.chunks else None),
+                     "algorithmic_bytes": up_bytes,
                      "avg_launch_us": stage_us["up"]},
     }
     if not args.no_cpu_baseline:
