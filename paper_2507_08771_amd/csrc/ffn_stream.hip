@@ -7,10 +7,16 @@
 // a v_mfma_f32_16x16x32_bf16 takes 16 weight rows x 32 contraction elements as its A operand
 // straight from the registers the loads land in (lane l = row l%16, 16 bytes at element
 // 8*(l/16)), so no unpacking, no cross-lane reduction and no LDS staging of weights is needed.
-// The fp32 activations are carried as two bf16 halves (x = hi + lo, 16 significant bits): the
-// 16 columns of the B operand are 8 tokens' hi parts and the same tokens' lo parts, and the
-// two column groups are added after the contraction.  Products of bf16 pairs are exact in
-// fp32 and accumulation is fp32, so the result is within ~2^-17 of an fp32-activation product.
+// The fp32 activations are carried as two bf16 halves (x = hi + lo, 16 significant bits).
+// Products of bf16 pairs are exact in fp32 and accumulation is fp32, so the result is within
+// ~2^-17 of an fp32-activation product.
+//
+// B-operand fragments (16 token columns x 32 contraction elements each), NB per K-step:
+//   k <= 8   NB = 1: columns 0-7 are the tokens' hi halves, columns 8-15 their lo halves; the two
+//                    column groups of the accumulator are added at the end;
+//   k <= 16  NB = 2: fragment 0 = hi, fragment 1 = lo of 16 tokens, both accumulated into the
+//                    same tile;
+//   k <= 32  NB = 4: (group 0 hi, group 0 lo, group 1 hi, group 1 lo), two accumulator tiles.
 //
 //   up    persistent workgroups walk a flat list of (chunk, slot) items.  The chunk's x is split
 //         into hi/lo bf16 once per item into LDS in B-operand order; each wave owns distinct
@@ -44,13 +50,17 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
-// x = hi + lo with hi = bf16(x) and lo = bf16(x - hi); returns hi in the low half, lo in the high half
+// x = hi + lo with hi = bf16(x) and lo = bf16(x - hi); 16-bit patterns in the low halves
 __device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
   hi = bf16_bits(x);
   lo = bf16_bits(x - __uint_as_float(hi << 16));
 }
 
-// Flat (chunk, slot) work list: item i of chunk c is slot i - offset[c].
+constexpr int acc_tiles(int NB) { return NB == 4 ? 2 : 1; }
+constexpr int acc_of(int NB, int bf) { return NB == 4 ? bf / 2 : 0; }
+constexpr int tokens_of(int NB) { return NB == 1 ? 8 : (NB == 2 ? 16 : 32); }
+
+// Flat (chunk, slot) work list: items[i] = chunk * E + slot for every slot below n_active[chunk].
 __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restrict__ n_active, int64_t n_chunks, int E,
                                                         int32_t *__restrict__ items, int32_t *__restrict__ total) {
   __shared__ int wave_tot[16];
@@ -83,22 +93,23 @@ __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restric
 
 // ------------------------------------------------------------------------------------------------ up
 
-// NT: 16-column token tiles (8 tokens each, hi and lo); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
+// NB: B fragments per K-step (see the top of the file); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
 // groups of the expert (d_e = 64 * RT).  Wave w owns row tiles rr*4 + w.
-template <int NT, int NM, int RT>
+template <int NB, int NM, int RT>
 __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, int k, uint16_t *__restrict__ midB) {
-  extern __shared__ uint4 xB[];   // [K-step][NT][64 lanes] of 8 bf16
-  constexpr int KC = 2048 / NT;   // contraction elements per LDS fill
+  extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
+  constexpr int KC = 2048 / NB;   // contraction elements per LDS fill
+  constexpr int NA = acc_tiles(NB);
+  constexpr int TOK = tokens_of(NB);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int total = *total_ptr;
   const size_t row_bytes = (size_t)d * 2;
 
-  // per-lane byte pointer to the first fragment of (item, tile rr, matrix m)
   auto item_expert = [&](int item, int64_t &c, int &s, int &e) {
     const int code = items[item];   // chunk * E + slot
     c = code / E;
@@ -106,6 +117,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     e = active_idx ? active_idx[c * E + s] : s;
     e = min(max(e, 0), E - 1);
   };
+  // per-lane byte pointer to the first fragment of (layer, expert, tile rr, matrix m)
   auto tile_ptr = [&](int layer, int e, int rr, int m) -> const char * {
     const char *w = static_cast<const char *>(m == 0 ? L.w_up : L.w_gate);
     const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + r;
@@ -135,22 +147,22 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       layer_n = clamp_layer(chunk_layer, c_n, L.n_layers);
     }
 
-    f32x4 acc[RT][NM][NT];
+    f32x4 acc[RT][NM][NA];
 #pragma unroll
     for (int a = 0; a < RT; ++a)
 #pragma unroll
       for (int m = 0; m < NM; ++m)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[a][m][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < NA; ++q) acc[a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int kc0 = 0; kc0 < d; kc0 += KC) {
       const int kc_len = min(KC, d - kc0);
       const int nkb = kc_len / 512;
       __syncthreads();   // every wave is done with the previous contents of xB
       // split x[c*k + tok][kc0 .. kc0 + kc_len) into hi/lo bf16 in B-operand order
-      for (int it = tid; it < (kc_len / 8) * (8 * NT); it += kThreads) {
-        const int tok = it % (8 * NT), cg = it / (8 * NT);   // cg: group of 8 columns
-        const int kstep = cg >> 2, gg = cg & 3, nt = tok >> 3, n = tok & 7;
+      for (int it = tid; it < (kc_len / 8) * TOK; it += kThreads) {
+        const int tok = it % TOK, cg = it / TOK;   // cg: group of 8 columns
+        const int kstep = cg >> 2, gg = cg & 3;
         uint32_t hi[8], lo[8];
         if (tok < k) {
           const float4 *p = reinterpret_cast<const float4 *>(x + (c * k + tok) * d + kc0 + cg * 8);
@@ -162,9 +174,18 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 #pragma unroll
           for (int q = 0; q < 8; ++q) hi[q] = lo[q] = 0;
         }
-        uint4 *dst = xB + ((size_t)(kstep * NT + nt) * 64 + gg * 16 + n);
-        dst[0] = make_uint4(hi[0] | hi[1] << 16, hi[2] | hi[3] << 16, hi[4] | hi[5] << 16, hi[6] | hi[7] << 16);
-        dst[8] = make_uint4(lo[0] | lo[1] << 16, lo[2] | lo[3] << 16, lo[4] | lo[5] << 16, lo[6] | lo[7] << 16);
+        const uint4 vhi = make_uint4(hi[0] | hi[1] << 16, hi[2] | hi[3] << 16, hi[4] | hi[5] << 16, hi[6] | hi[7] << 16);
+        const uint4 vlo = make_uint4(lo[0] | lo[1] << 16, lo[2] | lo[3] << 16, lo[4] | lo[5] << 16, lo[6] | lo[7] << 16);
+        if (NB == 1) {
+          uint4 *dst = xB + (size_t)kstep * 64 + gg * 16 + tok;
+          dst[0] = vhi;
+          dst[8] = vlo;
+        } else {
+          const int grp = tok >> 4, n = tok & 15;
+          uint4 *dst = xB + (size_t)(kstep * NB + grp * 2) * 64 + gg * 16 + n;
+          dst[0] = vhi;
+          dst[64] = vlo;
+        }
       }
       __syncthreads();
       const bool last_kc = kc0 + KC >= d;
@@ -173,7 +194,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
           const char *cur = tile_ptr(layer, e, rr, m) + (size_t)kc0 * 2;
-          // first block of the tile that follows this one in (kc, rr, m) order
+          // first block of the tile that follows this one in (K-chunk, rr, m) order
           const char *nxt_tile;
           bool nxt_ok = true;
           if (m + 1 < NM) nxt_tile = tile_ptr(layer, e, rr, m + 1) + (size_t)kc0 * 2;
@@ -190,9 +211,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 #pragma unroll
             for (int i = 0; i < kRing; ++i) {
 #pragma unroll
-              for (int nt = 0; nt < NT; ++nt) {
-                const uint4 b = xB[(size_t)((kb * kRing + i) * NT + nt) * 64 + lane];
-                acc[rr][m][nt] = mfma16(ring[i], b, acc[rr][m][nt]);
+              for (int bf = 0; bf < NB; ++bf) {
+                const uint4 b = xB[(size_t)((kb * kRing + i) * NB + bf) * 64 + lane];
+                acc[rr][m][acc_of(NB, bf)] = mfma16(ring[i], b, acc[rr][m][acc_of(NB, bf)]);
               }
               if (ok) ring[i] = *reinterpret_cast<const uint4 *>(nxt + i * 64);
             }
@@ -204,8 +225,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     // epilogue, entirely inside the wave: lane (n = lane%16, g) holds rows 4g..4g+3 of each tile
     const int n = lane & 15;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int t = nt * 8 + (n & 7);
+    for (int q = 0; q < NA; ++q) {
+      const int t = NB == 1 ? (n & 7) : q * 16 + n;
       float f = 0.0f;
       bool on = false;
       if (t < k) {
@@ -215,26 +236,32 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       }
 #pragma unroll
       for (int rr = 0; rr < RT; ++rr) {
-        uint32_t packed[4];
+        uint32_t phi[4], plo[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float u = acc[rr][0][nt][q];
-          u += __shfl_xor(u, 8, kWave);
+        for (int j = 0; j < 4; ++j) {
+          float u = acc[rr][0][q][j];
+          if (NB == 1) u += __shfl_xor(u, 8, kWave);
           float h;
           if (NM == 2) {
-            float gt = acc[rr][NM - 1][nt][q];
-            gt += __shfl_xor(gt, 8, kWave);
+            float gt = acc[rr][NM - 1][q][j];
+            if (NB == 1) gt += __shfl_xor(gt, 8, kWave);
             h = swish(gt) * u;
           } else {
             h = swish(u);
           }
-          const float mval = on ? f * h : 0.0f;
-          uint32_t hi, lo;
-          split_bf16(mval, hi, lo);
-          packed[q] = n < 8 ? hi : lo;
+          split_bf16(on ? f * h : 0.0f, phi[j], plo[j]);
         }
-        uint16_t *dst = midB + ((((size_t)c * E + s) * NT + nt) * 16 + n) * d_e + (rr * 4 + wave) * 16 + 4 * g;
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+        const uint2 vhi = make_uint2(phi[0] | phi[1] << 16, phi[2] | phi[3] << 16);
+        const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
+        const size_t col = (rr * 4 + wave) * 16 + 4 * g;
+        uint16_t *base = midB + ((size_t)c * E + s) * NB * 16 * d_e;
+        if (NB == 1) {
+          // fragment row n: hi for n < 8, lo of token n - 8 for n >= 8
+          *reinterpret_cast<uint2 *>(base + (size_t)n * d_e + col) = n < 8 ? vhi : vlo;
+        } else {
+          *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2) * 16 + n) * d_e + col) = vhi;
+          *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2 + 1) * 16 + n) * d_e + col) = vlo;
+        }
       }
     }
 
@@ -247,15 +274,16 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 // ------------------------------------------------------------------------------------------------ down
 
 // KSD = d_e / 32 K-steps per slot, MW row tiles (16 output columns each) per wave.
-template <int NT, int KSD, int MW>
+template <int NB, int KSD, int MW>
 __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, int k, int col_blocks, const uint16_t *__restrict__ midB,
     float *__restrict__ y) {
   constexpr int kFrag = KSD * MW;             // weight fragments per slot and wave
   static_assert(kFrag % kRing == 0, "ring must divide the fragments of a slot");
-  constexpr int kStage = KSD * NT * 64;       // uint4 of mid per slot
+  constexpr int kStage = KSD * NB * 64;       // uint4 of mid per slot
   constexpr int kPerThread = (kStage + kThreads - 1) / kThreads;
+  constexpr int NA = acc_tiles(NB);
   __shared__ uint4 midS[2][kStage];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -280,11 +308,11 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   // (requested several loads apart they were fetched from the fabric twice).
   auto frag_off = [&](int f) { return (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)(f % KSD) * 64; };
 
-  f32x4 acc[MW][NT];
+  f32x4 acc[MW][NA];
 #pragma unroll
   for (int a = 0; a < MW; ++a)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[a][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < NA; ++q) acc[a][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   if (n_act > 0) {
     uint4 ring[kRing];
@@ -294,12 +322,12 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 #pragma unroll
       for (int i = 0; i < kRing; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + frag_off(i));
     }
-    const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NT * 16) * d_e);
-    // mid of one slot is [NT][16][d_e] bf16; B-operand order is [K-step][NT][lane = g*16 + n]
+    const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NB * 16) * d_e);
+    // mid of one slot is [NB][16][d_e] bf16; B-operand order is [K-step][NB][lane = g*16 + n]
     auto stage_src = [&](int s, int idx) {
-      const int ln = idx & 63, nt = (idx >> 6) % NT, ks = idx / (64 * NT);
+      const int ln = idx & 63, bf = (idx >> 6) % NB, ks = idx / (64 * NB);
       const int n = ln & 15, gg = ln >> 4;
-      return mid_c + (((size_t)s * NT + nt) * 16 + n) * (d_e / 8) + ks * 4 + gg;
+      return mid_c + (((size_t)s * NB + bf) * 16 + n) * (d_e / 8) + ks * 4 + gg;
     };
 #pragma unroll
     for (int q = 0; q < kPerThread; ++q) {
@@ -312,13 +340,14 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       const bool has_next = s + 1 < n_act;
       const int e_n = has_next ? slot_expert(s + 1) : e;
       const char *nxt = slot_ptr(e_n);
+      // mid of the next slot (the last slot re-reads itself; the copy is harmless and keeps the
+      // staging registers unconditional)
+      const int s_stage = has_next ? s + 1 : s;
       uint4 stage[kPerThread];
-      if (has_next) {
 #pragma unroll
-        for (int q = 0; q < kPerThread; ++q) {
-          const int idx = tid + q * kThreads;
-          if (idx < kStage) stage[q] = *stage_src(s + 1, idx);
-        }
+      for (int q = 0; q < kPerThread; ++q) {
+        const int idx = tid + q * kThreads;
+        stage[q] = *stage_src(s_stage, idx < kStage ? idx : 0);
       }
       const char *cur = slot_ptr(e);
       const uint4 *bS = midS[s & 1];
@@ -328,19 +357,18 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
         for (int ks = 0; ks < KSD; ++ks) {
           const int f = tile * KSD + ks;
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            acc[tile][nt] = mfma16(ring[f % kRing], bS[(ks * NT + nt) * 64 + lane], acc[tile][nt]);
+          for (int bf = 0; bf < NB; ++bf)
+            acc[tile][acc_of(NB, bf)] =
+                mfma16(ring[f % kRing], bS[(ks * NB + bf) * 64 + lane], acc[tile][acc_of(NB, bf)]);
           const int fn = f + kRing;
           if (fn < kFrag) ring[f % kRing] = *reinterpret_cast<const uint4 *>(cur + frag_off(fn));
           else if (has_next) ring[f % kRing] = *reinterpret_cast<const uint4 *>(nxt + frag_off(fn - kFrag));
         }
       }
-      if (has_next) {
 #pragma unroll
-        for (int q = 0; q < kPerThread; ++q) {
-          const int idx = tid + q * kThreads;
-          if (idx < kStage) midS[(s + 1) & 1][idx] = stage[q];
-        }
+      for (int q = 0; q < kPerThread; ++q) {
+        const int idx = tid + q * kThreads;
+        if (idx < kStage) midS[(s + 1) & 1][idx] = stage[q];
       }
       __syncthreads();
       e = e_n;
@@ -349,19 +377,19 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 
   const int n = lane & 15;
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int t = nt * 8 + (n & 7);
+  for (int q = 0; q < NA; ++q) {
+    const int t = NB == 1 ? (n & 7) : q * 16 + n;
+    const bool writer = (NB == 1 ? n < 8 : true) && t < k;
 #pragma unroll
     for (int tile = 0; tile < MW; ++tile) {
       float4 v;
       float *vp = reinterpret_cast<float *>(&v);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float a = acc[tile][nt][q];
-        vp[q] = a + __shfl_xor(a, 8, kWave);
+      for (int j = 0; j < 4; ++j) {
+        const float a = acc[tile][q][j];
+        vp[j] = NB == 1 ? a + __shfl_xor(a, 8, kWave) : a;
       }
-      if (n < 8 && t < k)
-        *reinterpret_cast<float4 *>(y + (c * k + t) * d + col0 + tile * 16 + 4 * g) = v;
+      if (writer) *reinterpret_cast<float4 *>(y + (c * k + t) * d + col0 + tile * 16 + 4 * g) = v;
     }
   }
 }
@@ -380,12 +408,12 @@ int num_cus() {
   return g_num_cus;
 }
 
-template <int NT, int NM, int RT>
+template <int NB, int NM, int RT>
 hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float *x, const float *scores,
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *items,
                      const int32_t *total, int64_t max_items, int k, uint16_t *midB, hipStream_t s) {
   static bool attr_set = false;
-  auto kern = up_stream_kernel<NT, NM, RT>;
+  auto kern = up_stream_kernel<NB, NM, RT>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kXBytes);
@@ -398,20 +426,38 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float
   return hipGetLastError();
 }
 
-template <int NT, int KSD>
+template <int NB, int KSD>
 hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
                        const int32_t *n_active, int64_t n_chunks, int k, const uint16_t *midB, float *y,
                        hipStream_t s) {
-  constexpr int MW = 8;
+  constexpr int MW = (NB == 4 && KSD >= 4) ? 4 : 8;   // two accumulator tiles per row tile at NB = 4
   const int col_blocks = L.d / (4 * MW * 16);
   const int64_t grid = n_chunks * col_blocks;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((down_stream_kernel<NT, KSD, MW>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
+  hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
                      active_idx, n_active, k, col_blocks, midB, y);
   return hipGetLastError();
 }
 
-int token_tiles(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
+int b_frags(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
+
+struct StreamWs {
+  uint16_t *midB;
+  int32_t *items, *total;
+};
+
+size_t mid_bytes(const LayerView &L, int64_t n_chunks, int k) {
+  return ((size_t)n_chunks * L.E * b_frags(k) * 16 * L.d_e * 2 + 255) & ~(size_t)255;
+}
+
+StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
+  char *p = static_cast<char *>(ws);
+  StreamWs w;
+  w.midB = reinterpret_cast<uint16_t *>(p);
+  w.total = reinterpret_cast<int32_t *>(p + mid_bytes(L, n_chunks, k));
+  w.items = w.total + 64;
+  return w;
+}
 
 }  // namespace
 
@@ -421,27 +467,10 @@ bool stream_supported(const LayerView &L, int wdtype, int k) {
 }
 
 size_t stream_workspace_bytes(const LayerView &L, int64_t n_chunks, int k) {
-  // mid as bf16 hi/lo planes [chunk][slot][NT][16][d_e], then the item list and its length
-  const size_t mid = (size_t)n_chunks * L.E * token_tiles(k) * 16 * L.d_e * 2;
+  // mid as bf16 hi/lo fragments [chunk][slot][NB][16][d_e], then the item count and the item list
   const size_t items = ((size_t)n_chunks * L.E + 64) * sizeof(int32_t);
-  return ((mid + 255) & ~(size_t)255) + ((items + 255) & ~(size_t)255);
+  return mid_bytes(L, n_chunks, k) + ((items + 255) & ~(size_t)255);
 }
-
-namespace {
-struct StreamWs {
-  uint16_t *midB;
-  int32_t *items, *total;
-};
-StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
-  const size_t mid = (size_t)n_chunks * L.E * token_tiles(k) * 16 * L.d_e * 2;
-  char *p = static_cast<char *>(ws);
-  StreamWs w;
-  w.midB = reinterpret_cast<uint16_t *>(p);
-  w.total = reinterpret_cast<int32_t *>(p + ((mid + 255) & ~(size_t)255));
-  w.items = w.total + 64;
-  return w;
-}
-}  // namespace
 
 hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *x,
                             const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
@@ -452,11 +481,11 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   hipLaunchKernelGGL(worklist_kernel, dim3(1), dim3(1024), 0, s, n_active, n_chunks, L.E, w.items, w.total);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  const int NT = token_tiles(k), RT = L.d_e / 64;
+  const int NB = b_frags(k), RT = L.d_e / 64;
   const int64_t max_items = n_chunks * L.E;
-#define BLOCKFFN_CASE(nt, nm, rt)                                                                         \
-  if (NT == nt && (gated ? 2 : 1) == nm && RT == rt)                                                      \
-    return launch_up<nt, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, w.items, w.total, max_items, k, \
+#define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
+  if (NB == nb && (gated ? 2 : 1) == nm && RT == rt)                                                      \
+    return launch_up<nb, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, w.items, w.total, max_items, k, \
                                  w.midB, s);
   BLOCKFFN_CASE(1, 1, 1) BLOCKFFN_CASE(1, 1, 2) BLOCKFFN_CASE(1, 1, 4)
   BLOCKFFN_CASE(1, 2, 1) BLOCKFFN_CASE(1, 2, 2) BLOCKFFN_CASE(1, 2, 4)
@@ -473,9 +502,9 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
                               hipStream_t s) {
   if (n_chunks <= 0) return hipSuccess;
   StreamWs w = carve(L, n_chunks, k, const_cast<void *>(ws));
-  const int NT = token_tiles(k), KSD = L.d_e / 32;
-#define BLOCKFFN_CASE(nt, ksd) \
-  if (NT == nt && KSD == ksd) return launch_down<nt, ksd>(L, chunk_layer, active_idx, n_active, n_chunks, k, w.midB, y, s);
+  const int NB = b_frags(k), KSD = L.d_e / 32;
+#define BLOCKFFN_CASE(nb, ksd) \
+  if (NB == nb && KSD == ksd) return launch_down<nb, ksd>(L, chunk_layer, active_idx, n_active, n_chunks, k, w.midB, y, s);
   BLOCKFFN_CASE(1, 2) BLOCKFFN_CASE(1, 4) BLOCKFFN_CASE(1, 8)
   BLOCKFFN_CASE(2, 2) BLOCKFFN_CASE(2, 4) BLOCKFFN_CASE(2, 8)
   BLOCKFFN_CASE(4, 2) BLOCKFFN_CASE(4, 4) BLOCKFFN_CASE(4, 8)
