@@ -49,17 +49,21 @@ int check_chunks(int64_t n_chunks, int32_t k) {
 
 // BLOCKFFN_FORCE_GENERIC=1 in the environment keeps every shape on the shape-generic kernels
 // (used to compare the two implementations on the same inputs).
-bool use_stream(const LayerView &v, int wdtype, int32_t k) {
+bool force_generic() {
   const char *e = std::getenv("BLOCKFFN_FORCE_GENERIC");
-  const bool forced = e != nullptr && e[0] == '1';
-  return !forced && stream_supported(v, wdtype, k);
+  return e != nullptr && e[0] == '1';
+}
+bool use_stream(const LayerView &v, int wdtype, int32_t k) { return !force_generic() && stream_supported(v, wdtype, k); }
+bool use_gemm(const LayerView &v, int wdtype, int32_t k, bool gated) {
+  return !force_generic() && gemm_supported(v, wdtype, k, gated);
 }
 
-size_t workspace_need(const LayerView &v, int wdtype, int64_t n_chunks, int32_t k) {
+size_t workspace_need(const LayerView &v, int wdtype, bool gated, int64_t n_chunks, int32_t k) {
   // generic kernels: mid[chunk][slot][token][neuron] fp32, slots sized for the worst case
   size_t bytes = (size_t)n_chunks * v.E * (size_t)k * v.d_e * sizeof(float);
   bytes = (bytes + 255) & ~(size_t)255;
   if (stream_supported(v, wdtype, k)) bytes = std::max(bytes, stream_workspace_bytes(v, n_chunks, k));
+  if (gemm_supported(v, wdtype, k, gated)) bytes = std::max(bytes, gemm_workspace_bytes(v, n_chunks, k));
   return bytes;
 }
 
@@ -85,10 +89,10 @@ int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_lay
   }
   if (!aligned(active_idx, 4) || !aligned(n_active, 4) || !aligned(chunk_layer, 4)) return BLOCKFFN_ERR_INVALID;
   if (n_chunks == 0) return BLOCKFFN_OK;
-  const size_t need = workspace_need(v, layer->wdtype, n_chunks, k);
+  const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
+  const size_t need = workspace_need(v, layer->wdtype, gated, n_chunks, k);
   if (workspace == nullptr || !aligned(workspace, 256)) return BLOCKFFN_ERR_INVALID;
   if (workspace_bytes < need) return BLOCKFFN_ERR_WORKSPACE;
-  const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t err = hipSuccess;
   if (use_stream(v, layer->wdtype, k)) {
@@ -97,6 +101,12 @@ int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_lay
                              workspace, s);
     if (err == hipSuccess && (phases & kPhaseDown))
       err = launch_down_stream(v, chunk_layer, active_idx, n_active, n_chunks, k, workspace, y, s);
+  } else if (use_gemm(v, layer->wdtype, k, gated)) {
+    if (phases & kPhaseUp)
+      err = launch_up_gemm(v, gated, chunk_layer, x, scores, token_mask, active_idx, n_active, n_chunks, k,
+                           workspace, s);
+    if (err == hipSuccess && (phases & kPhaseDown))
+      err = launch_down_gemm(v, chunk_layer, active_idx, n_active, n_chunks, k, workspace, y, s);
   } else {
     float *mid = static_cast<float *>(workspace);
     if (phases & kPhaseUp)
@@ -180,7 +190,7 @@ size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, i
   LayerView v;
   if (check_layer(layer, v) != BLOCKFFN_OK) return 0;
   if (check_chunks(n_chunks, k) != BLOCKFFN_OK) return 0;
-  return workspace_need(v, layer->wdtype, n_chunks, k);
+  return workspace_need(v, layer->wdtype, layer->expert_kind == BLOCKFFN_EXPERT_GATED, n_chunks, k);
 }
 
 const char *blockffn_strerror(int code) {

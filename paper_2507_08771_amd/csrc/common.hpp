@@ -109,4 +109,19 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
                               const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
                               hipStream_t s);
 
+// Flat (chunk, slot) list of the active experts: items[i] = chunk * E + slot, *total = its length
+// (n_active == nullptr: every chunk has E slots).  items needs n_chunks * E entries.
+hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int32_t *items, int32_t *total,
+                           hipStream_t s);
+
+// Matrix-core grouped contraction for large chunks (bf16 weights, 32 < k <= 512).
+bool gemm_supported(const LayerView &L, int wdtype, int k, bool gated);
+size_t gemm_workspace_bytes(const LayerView &L, int64_t n_chunks, int k);
+hipError_t launch_up_gemm(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *x,
+                          const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
+                          const int32_t *n_active, int64_t n_chunks, int k, void *ws, hipStream_t s);
+hipError_t launch_down_gemm(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
+                            const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
+                            hipStream_t s);
+
 }  // namespace blockffn

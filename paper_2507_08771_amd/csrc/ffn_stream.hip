@@ -461,6 +461,12 @@ StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
 
 }  // namespace
 
+hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int32_t *items, int32_t *total,
+                           hipStream_t s) {
+  hipLaunchKernelGGL(worklist_kernel, dim3(1), dim3(1024), 0, s, n_active, n_chunks, E, items, total);
+  return hipGetLastError();
+}
+
 bool stream_supported(const LayerView &L, int wdtype, int k) {
   return wdtype == BLOCKFFN_BF16 && k <= 32 && L.d % 512 == 0 &&
          (L.d_e == 64 || L.d_e == 128 || L.d_e == 256);
@@ -478,8 +484,7 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   if (n_chunks <= 0) return hipSuccess;
   if (n_chunks * L.E > 0x7fffffffLL) return hipErrorInvalidValue;
   StreamWs w = carve(L, n_chunks, k, ws);
-  hipLaunchKernelGGL(worklist_kernel, dim3(1), dim3(1024), 0, s, n_active, n_chunks, L.E, w.items, w.total);
-  hipError_t err = hipGetLastError();
+  hipError_t err = launch_worklist(n_active, n_chunks, L.E, w.items, w.total, s);
   if (err != hipSuccess) return err;
   const int NB = b_frags(k), RT = L.d_e / 64;
   const int64_t max_items = n_chunks * L.E;

@@ -21,6 +21,13 @@ RTOL = {"f32": 1e-5, "bf16": 2e-2}
 # fp32 accumulation with activations carried as two bf16 halves (16 significant bits) on the
 # matrix-core path: error is a few 1e-6 of the row rms; 1e-4 leaves a wide margin.
 TIGHT = {"f32": 1e-5, "bf16": 1e-4}
+# Large chunks (k > 32) run as a bf16 x bf16 grouped contraction: x and mid are rounded to bf16
+# (relative error uniform in +-2^-9 per element).  Three such roundings (x into the up and the
+# gate product, mid into the down product) leave about 3e-3 of the row rms per output element
+# (measured: L2-relative 2.9e-3 .. 4.1e-3), and the largest of a row's 2048 elements sits at
+# 4 to 6 sigma.  Held: the stated bar on the row maximum, and 5e-3 on the row's L2-relative error.
+GEMM_BAR = 2e-2
+GEMM_L2_BAR = 5e-3
 
 
 def oracle_layer(layers, l, eps=1e-6, use_gain=True, use_bias=True):
@@ -111,15 +118,21 @@ def assert_integers_equal(gpu, ref, chunks=None, k=None):
             np.testing.assert_array_equal(gpu[n][cs], ref[n][cs], err_msg=n)
 
 
-def assert_floats_close(gpu, ref, wdtype, rows=None, dense=False, tight=True):
+def assert_floats_close(gpu, ref, wdtype, rows=None, dense=False, tight=True, bar=None, l2_bar=None):
     sl = slice(None) if rows is None else rows
-    bar = TIGHT[wdtype] if tight else RTOL[wdtype]
+    if bar is None:
+        bar = TIGHT[wdtype] if tight else RTOL[wdtype]
     e_scores = row_rel_err(gpu["scores"][sl], ref["scores"][sl]).max(initial=0.0)
     assert e_scores <= 1e-5, "router scores off by %.3g" % e_scores
     # zero pattern of the scores is part of the integer bar
     np.testing.assert_array_equal(gpu["scores"][sl] == 0, ref["scores"][sl] == 0)
     e_y = row_rel_err(gpu["y"][sl], ref["y"][sl]).max(initial=0.0)
     assert e_y <= bar, "sparse FFN output off by %.3g (bar %.1g)" % (e_y, bar)
+    if l2_bar is not None:
+        num = ((gpu["y"][sl] - ref["y"][sl]) ** 2).sum(axis=1)
+        den = (ref["y"][sl] ** 2).sum(axis=1)
+        l2 = np.sqrt(num[den > 0] / den[den > 0]).max(initial=0.0)
+        assert l2 <= l2_bar, "sparse FFN output L2-relative error %.3g (bar %.1g)" % (l2, l2_bar)
     e_d = 0.0
     if dense:
         e_d = row_rel_err(gpu["y_dense"][sl], ref["y_dense"][sl]).max(initial=0.0)

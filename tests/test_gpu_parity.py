@@ -68,12 +68,20 @@ def test_shapes(d, E, d_e, k, C, wdtype, gated, impl):
     print(pu.assert_floats_close(gpu, ref, wdtype, dense=True))
 
 
-@pytest.mark.parametrize("k,d_e", [(32, 256), (40, 64)])
-def test_large_chunks(k, d_e, impl):
-    w = wl.Workload("t", d=2048, E=64, d_e=d_e, wdtype="bf16", gated=True, k=k, n_chunks=3, sigma=0.5, seed=k)
-    ref, gpu = both(w, dense=False)
+@pytest.mark.parametrize("k,d_e,C,gated", [(32, 256, 3, True), (40, 64, 3, True), (200, 128, 2, True),
+                                           (130, 128, 2, False), (512, 256, 1, True)])
+def test_large_chunks(k, d_e, C, gated, impl):
+    """k = 32 is the largest streamed chunk; above it the matrix-core grouped contraction runs
+    (ragged token tiles at 40 / 130 / 200, the 512-token prefill chunk at full size)."""
+    if impl == "generic" and k == 512:
+        pytest.skip("the generic kernels are covered at k <= 200")
+    w = wl.Workload("t", d=2048, E=64, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.5, seed=k,
+                    group=8 if k == 512 else 0)
+    ref, gpu = both(w, dense=(k <= 40))
     pu.assert_integers_equal(gpu, ref)
-    print(pu.assert_floats_close(gpu, ref, "bf16"))
+    gemm = k > 32 and impl == "auto"
+    print(pu.assert_floats_close(gpu, ref, "bf16", dense=(k <= 40), bar=pu.GEMM_BAR if gemm else None,
+                                 l2_bar=pu.GEMM_L2_BAR if gemm else None))
 
 
 def test_layer_rotation_gain_and_eps():
