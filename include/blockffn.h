@@ -122,7 +122,7 @@ int blockffn_sparse_ffn_up(const blockffn_layer *layer, const int32_t *chunk_lay
                            int32_t k, void *workspace, size_t workspace_bytes, void *stream);
 int blockffn_sparse_ffn_down(const blockffn_layer *layer, const int32_t *chunk_layer,
                              const int32_t *active_idx, const int32_t *n_active,
-                             int64_t n_chunks, int32_t k, float *y, const void *workspace,
+                             int64_t n_chunks, int32_t k, float *y, void *workspace,
                              size_t workspace_bytes, void *stream);
 
 /* Bytes of workspace the two FFN entry points need for this shape (0 on invalid arguments). */

@@ -173,10 +173,10 @@ int blockffn_sparse_ffn_up(const blockffn_layer *layer, const int32_t *chunk_lay
 }
 
 int blockffn_sparse_ffn_down(const blockffn_layer *layer, const int32_t *chunk_layer, const int32_t *active_idx,
-                             const int32_t *n_active, int64_t n_chunks, int32_t k, float *y, const void *workspace,
+                             const int32_t *n_active, int64_t n_chunks, int32_t k, float *y, void *workspace,
                              size_t workspace_bytes, void *stream) {
   return ffn_common(kPhaseDown, layer, chunk_layer, nullptr, nullptr, nullptr, active_idx, n_active, n_chunks, k, y,
-                    const_cast<void *>(workspace), workspace_bytes, stream);
+                    workspace, workspace_bytes, stream);
 }
 
 int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, const float *scores,

@@ -271,16 +271,112 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   }
 }
 
+// ------------------------------------------------------------------------------------------------ up, few chunks
+
+// Small launches (e.g. a single chunk walking through a layer stack) do not have enough (chunk,
+// slot) items to occupy the chip with one workgroup per item.  Here one workgroup takes one
+// 16-row tile of one item; its four waves split the contraction, each keeps its quarter of the
+// chunk's split x in registers (no LDS fill, no barrier before the stream starts) and the four
+// partial tiles meet in LDS once at the end.  k <= 8 only; FW = d / 128 fragments per wave.
+template <int NM, int FW>
+__global__ __launch_bounds__(kThreads) void up_split_kernel(
+    LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
+    const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
+    const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, int k, uint16_t *__restrict__ midB) {
+  __shared__ float red[4][NM][4][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4, n = lane & 15;
+  const int E = L.E, d = L.d, d_e = L.d_e;
+  const int tiles = d_e / 16;
+  const int item = blockIdx.x / tiles, rt = blockIdx.x % tiles;
+  if (item >= *total_ptr) return;
+  const int code = items[item];
+  const int64_t c = code / E;
+  const int s = code - (int)c * E;
+  int e = active_idx ? active_idx[c * E + s] : s;
+  e = min(max(e, 0), E - 1);
+  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  const int kq0 = wave * (d / 4);
+
+  uint4 a[NM][FW];
+#pragma unroll
+  for (int m = 0; m < NM; ++m) {
+    const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
+    const uint16_t *row = w + (((size_t)layer * E + e) * d_e + rt * 16 + r) * d + kq0 + g * 8;
+#pragma unroll
+    for (int i = 0; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row + i * 32);
+  }
+  // keep every weight load of this wave in flight before anything waits on x
+  __builtin_amdgcn_sched_barrier(0);
+  f32x4 acc[NM];
+#pragma unroll
+  for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int tok = n & 7;
+  const float *xrow = x + (c * k + min(tok, k - 1)) * d + kq0 + g * 8;
+#pragma unroll
+  for (int i = 0; i < FW; ++i) {
+    const float4 *p = reinterpret_cast<const float4 *>(xrow + i * 32);
+    const float4 v0 = p[0], v1 = p[1];
+    const float xv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    uint32_t h[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      uint32_t hi, lo;
+      split_bf16(xv[q], hi, lo);
+      h[q] = (tok < k) ? (n < 8 ? hi : lo) : 0u;
+    }
+    const uint4 b = make_uint4(h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16);
+#pragma unroll
+    for (int m = 0; m < NM; ++m) acc[m] = mfma16(a[m][i], b, acc[m]);
+  }
+#pragma unroll
+  for (int m = 0; m < NM; ++m)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[wave][m][q][lane] = acc[m][q];
+  __syncthreads();
+  if (wave != 0) return;
+
+  float f = 0.0f;
+  bool on = false;
+  if (tok < k) {
+    const int64_t t = c * k + tok;
+    on = token_mask ? (bool)((token_mask[t * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
+    f = scores[t * E + e];
+  }
+  uint32_t packed[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float u = (red[0][0][q][lane] + red[1][0][q][lane]) + (red[2][0][q][lane] + red[3][0][q][lane]);
+    u += __shfl_xor(u, 8, kWave);
+    float h;
+    if (NM == 2) {
+      float gt = (red[0][NM - 1][q][lane] + red[1][NM - 1][q][lane]) + (red[2][NM - 1][q][lane] + red[3][NM - 1][q][lane]);
+      gt += __shfl_xor(gt, 8, kWave);
+      h = swish(gt) * u;
+    } else {
+      h = swish(u);
+    }
+    uint32_t hi, lo;
+    split_bf16(on ? f * h : 0.0f, hi, lo);
+    packed[q] = n < 8 ? hi : lo;
+  }
+  uint16_t *dst = midB + (((size_t)c * E + s) * 16 + n) * d_e + rt * 16 + 4 * g;
+  *reinterpret_cast<uint2 *>(dst) = make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+}
+
 // ------------------------------------------------------------------------------------------------ down
 
-// KSD = d_e / 32 K-steps per slot, MW row tiles (16 output columns each) per wave.
-template <int NB, int KSD, int MW>
+// KSD = d_e / 32 K-steps per slot, MW row tiles (16 output columns each) per wave, RING loads in
+// flight per lane.  With splits > 1 the union's slots are divided among `splits` workgroups per
+// (chunk, column block); each writes its partial sum to out + split * split_stride and a second
+// kernel adds them in a fixed order (used when a launch has too few chunks to fill the chip).
+template <int NB, int KSD, int MW, int RING>
 __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ n_active, int k, int col_blocks, const uint16_t *__restrict__ midB,
-    float *__restrict__ y) {
+    const int32_t *__restrict__ n_active, int k, int col_blocks, int splits, const uint16_t *__restrict__ midB,
+    float *__restrict__ out, size_t split_stride) {
   constexpr int kFrag = KSD * MW;             // weight fragments per slot and wave
-  static_assert(kFrag % kRing == 0, "ring must divide the fragments of a slot");
+  static_assert(kFrag % RING == 0, "ring must divide the fragments of a slot");
   constexpr int kStage = KSD * NB * 64;       // uint4 of mid per slot
   constexpr int kPerThread = (kStage + kThreads - 1) / kThreads;
   constexpr int NA = acc_tiles(NB);
@@ -290,10 +386,14 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   const int r = lane & 15, g = lane >> 4;
   const int E = L.E, d = L.d;
   constexpr int d_e = KSD * 32;
-  const int64_t c = blockIdx.x / col_blocks;
-  const int col0 = (int)(blockIdx.x % col_blocks) * (4 * MW * 16) + wave * (MW * 16);
+  const int sp = (int)(blockIdx.x % splits);
+  const int64_t cb = blockIdx.x / splits;
+  const int64_t c = cb / col_blocks;
+  const int col0 = (int)(cb % col_blocks) * (4 * MW * 16) + wave * (MW * 16);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
+  const int s_lo = (int)((int64_t)n_act * sp / splits), s_hi = (int)((int64_t)n_act * (sp + 1) / splits);
+  float *y = out + (size_t)sp * split_stride;
 
   auto slot_expert = [&](int s) {
     int e = active_idx ? active_idx[c * E + s] : s;
@@ -314,13 +414,13 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 #pragma unroll
     for (int q = 0; q < NA; ++q) acc[a][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (n_act > 0) {
-    uint4 ring[kRing];
-    int e = slot_expert(0);
+  if (s_hi > s_lo) {
+    uint4 ring[RING];
+    int e = slot_expert(s_lo);
     {
       const char *p = slot_ptr(e);
 #pragma unroll
-      for (int i = 0; i < kRing; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + frag_off(i));
+      for (int i = 0; i < RING; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + frag_off(i));
     }
     const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NB * 16) * d_e);
     // mid of one slot is [NB][16][d_e] bf16; B-operand order is [K-step][NB][lane = g*16 + n]
@@ -332,12 +432,12 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 #pragma unroll
     for (int q = 0; q < kPerThread; ++q) {
       const int idx = tid + q * kThreads;
-      if (idx < kStage) midS[0][idx] = *stage_src(0, idx);
+      if (idx < kStage) midS[0][idx] = *stage_src(s_lo, idx);
     }
     __syncthreads();
 
-    for (int s = 0; s < n_act; ++s) {
-      const bool has_next = s + 1 < n_act;
+    for (int s = s_lo; s < s_hi; ++s) {
+      const bool has_next = s + 1 < s_hi;
       const int e_n = has_next ? slot_expert(s + 1) : e;
       const char *nxt = slot_ptr(e_n);
       // mid of the next slot (the last slot re-reads itself; the copy is harmless and keeps the
@@ -350,7 +450,7 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
         stage[q] = *stage_src(s_stage, idx < kStage ? idx : 0);
       }
       const char *cur = slot_ptr(e);
-      const uint4 *bS = midS[s & 1];
+      const uint4 *bS = midS[(s - s_lo) & 1];
 #pragma unroll
       for (int tile = 0; tile < MW; ++tile) {
 #pragma unroll
@@ -359,16 +459,16 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 #pragma unroll
           for (int bf = 0; bf < NB; ++bf)
             acc[tile][acc_of(NB, bf)] =
-                mfma16(ring[f % kRing], bS[(ks * NB + bf) * 64 + lane], acc[tile][acc_of(NB, bf)]);
-          const int fn = f + kRing;
-          if (fn < kFrag) ring[f % kRing] = *reinterpret_cast<const uint4 *>(cur + frag_off(fn));
-          else if (has_next) ring[f % kRing] = *reinterpret_cast<const uint4 *>(nxt + frag_off(fn - kFrag));
+                mfma16(ring[f % RING], bS[(ks * NB + bf) * 64 + lane], acc[tile][acc_of(NB, bf)]);
+          const int fn = f + RING;
+          if (fn < kFrag) ring[f % RING] = *reinterpret_cast<const uint4 *>(cur + frag_off(fn));
+          else if (has_next) ring[f % RING] = *reinterpret_cast<const uint4 *>(nxt + frag_off(fn - kFrag));
         }
       }
 #pragma unroll
       for (int q = 0; q < kPerThread; ++q) {
         const int idx = tid + q * kThreads;
-        if (idx < kStage) midS[(s + 1) & 1][idx] = stage[q];
+        if (idx < kStage) midS[(s - s_lo + 1) & 1][idx] = stage[q];
       }
       __syncthreads();
       e = e_n;
@@ -426,16 +526,54 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float
   return hipGetLastError();
 }
 
+__global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const float *__restrict__ part, int splits,
+                                                                   size_t split_stride, size_t n4,
+                                                                   float *__restrict__ y) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    float4 a = reinterpret_cast<const float4 *>(part)[i];
+    for (int sp = 1; sp < splits; ++sp) {
+      const float4 b = reinterpret_cast<const float4 *>(part + (size_t)sp * split_stride)[i];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    reinterpret_cast<float4 *>(y)[i] = a;
+  }
+}
+
+// Few chunks: narrow column blocks (8 fragments per slot and wave) and up to 8 slot splits, so
+// that one chunk still spreads over the whole chip.
+int down_splits(const LayerView &L, int64_t n_chunks) {
+  const int64_t wide = n_chunks * (L.d / 512);
+  if (wide >= 2 * num_cus()) return 0;   // 0: the wide, unsplit configuration
+  const int ksd = L.d_e / 32;
+  const int64_t narrow = n_chunks * (L.d / (64 * (8 / ksd)));
+  return (int)std::min<int64_t>(8, std::max<int64_t>(1, (num_cus() + narrow - 1) / narrow));
+}
+
 template <int NB, int KSD>
 hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
-                       const int32_t *n_active, int64_t n_chunks, int k, const uint16_t *midB, float *y,
+                       const int32_t *n_active, int64_t n_chunks, int k, const uint16_t *midB, float *part, float *y,
                        hipStream_t s) {
-  constexpr int MW = (NB == 4 && KSD >= 4) ? 4 : 8;   // two accumulator tiles per row tile at NB = 4
+  const int splits = down_splits(L, n_chunks);
+  const size_t stride = (size_t)n_chunks * k * L.d;
+  if (splits == 0) {
+    constexpr int MW = (NB == 4 && KSD >= 4) ? 4 : 8;   // two accumulator tiles per row tile at NB = 4
+    const int col_blocks = L.d / (4 * MW * 16);
+    const int64_t grid = n_chunks * col_blocks;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, kRing>), dim3((unsigned)grid), dim3(kThreads), 0, s, L,
+                       chunk_layer, active_idx, n_active, k, col_blocks, 1, midB, y, stride);
+    return hipGetLastError();
+  }
+  constexpr int MW = 8 / KSD;
   const int col_blocks = L.d / (4 * MW * 16);
-  const int64_t grid = n_chunks * col_blocks;
-  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
-                     active_idx, n_active, k, col_blocks, midB, y);
+  const int64_t grid = n_chunks * col_blocks * splits;
+  hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
+                     active_idx, n_active, k, col_blocks, splits, midB, splits > 1 ? part : y, stride);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess || splits == 1) return err;
+  const size_t n4 = stride / 4;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)std::min<size_t>((n4 + kThreads - 1) / kThreads, 1024)),
+                     dim3(kThreads), 0, s, part, splits, stride, n4, y);
   return hipGetLastError();
 }
 
@@ -444,10 +582,15 @@ int b_frags(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
 struct StreamWs {
   uint16_t *midB;
   int32_t *items, *total;
+  float *part;   // partial sums of the split down projection (few chunks only)
 };
 
 size_t mid_bytes(const LayerView &L, int64_t n_chunks, int k) {
   return ((size_t)n_chunks * L.E * b_frags(k) * 16 * L.d_e * 2 + 255) & ~(size_t)255;
+}
+
+size_t item_bytes(const LayerView &L, int64_t n_chunks) {
+  return (((size_t)n_chunks * L.E + 64) * sizeof(int32_t) + 255) & ~(size_t)255;
 }
 
 StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
@@ -456,6 +599,7 @@ StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
   w.midB = reinterpret_cast<uint16_t *>(p);
   w.total = reinterpret_cast<int32_t *>(p + mid_bytes(L, n_chunks, k));
   w.items = w.total + 64;
+  w.part = reinterpret_cast<float *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks));
   return w;
 }
 
@@ -474,8 +618,10 @@ bool stream_supported(const LayerView &L, int wdtype, int k) {
 
 size_t stream_workspace_bytes(const LayerView &L, int64_t n_chunks, int k) {
   // mid as bf16 hi/lo fragments [chunk][slot][NB][16][d_e], then the item count and the item list
-  const size_t items = ((size_t)n_chunks * L.E + 64) * sizeof(int32_t);
-  return mid_bytes(L, n_chunks, k) + ((items + 255) & ~(size_t)255);
+  size_t b = mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks);
+  const int splits = down_splits(L, n_chunks);
+  if (splits > 1) b += ((size_t)splits * n_chunks * k * L.d * sizeof(float) + 255) & ~(size_t)255;
+  return b;
 }
 
 hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *x,
@@ -488,6 +634,17 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   if (err != hipSuccess) return err;
   const int NB = b_frags(k), RT = L.d_e / 64;
   const int64_t max_items = n_chunks * L.E;
+  if (NB == 1 && max_items <= 2048 && (L.d == 1024 || L.d == 2048)) {
+    // few chunks: one workgroup per (item, 16-row tile)
+    const dim3 grid((unsigned)(max_items * (L.d_e / 16)));
+#define BLOCKFFN_SPLIT(nm, fw)                                                                             \
+  hipLaunchKernelGGL((up_split_kernel<nm, fw>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, scores, token_mask, \
+                     active_idx, w.items, w.total, k, w.midB)
+    if (L.d == 2048) { if (gated) BLOCKFFN_SPLIT(2, 16); else BLOCKFFN_SPLIT(1, 16); }
+    else { if (gated) BLOCKFFN_SPLIT(2, 8); else BLOCKFFN_SPLIT(1, 8); }
+#undef BLOCKFFN_SPLIT
+    return hipGetLastError();
+  }
 #define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
   if (NB == nb && (gated ? 2 : 1) == nm && RT == rt)                                                      \
     return launch_up<nb, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, w.items, w.total, max_items, k, \
@@ -509,7 +666,8 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
   StreamWs w = carve(L, n_chunks, k, const_cast<void *>(ws));
   const int NB = b_frags(k), KSD = L.d_e / 32;
 #define BLOCKFFN_CASE(nb, ksd) \
-  if (NB == nb && KSD == ksd) return launch_down<nb, ksd>(L, chunk_layer, active_idx, n_active, n_chunks, k, w.midB, y, s);
+  if (NB == nb && KSD == ksd) \
+    return launch_down<nb, ksd>(L, chunk_layer, active_idx, n_active, n_chunks, k, w.midB, w.part, y, s);
   BLOCKFFN_CASE(1, 2) BLOCKFFN_CASE(1, 4) BLOCKFFN_CASE(1, 8)
   BLOCKFFN_CASE(2, 2) BLOCKFFN_CASE(2, 4) BLOCKFFN_CASE(2, 8)
   BLOCKFFN_CASE(4, 2) BLOCKFFN_CASE(4, 4) BLOCKFFN_CASE(4, 8)
