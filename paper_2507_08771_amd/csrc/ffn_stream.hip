@@ -282,18 +282,22 @@ template <int NM, int FW>
 __global__ __launch_bounds__(kThreads) void up_split_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, int k, uint16_t *__restrict__ midB) {
+    const int32_t *__restrict__ n_active, int k, uint16_t *__restrict__ midB) {
   __shared__ float red[4][NM][4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4, n = lane & 15;
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int tiles = d_e / 16;
-  const int item = blockIdx.x / tiles, rt = blockIdx.x % tiles;
-  if (item >= *total_ptr) return;
-  const int code = items[item];
+  // the grid covers every (chunk, slot, tile); slots at or above n_active leave at once (no item
+  // list here: it would add a launch and two dependent loads to a path that is latency bound)
+  const int code = blockIdx.x / tiles, rt = blockIdx.x % tiles;
   const int64_t c = code / E;
   const int s = code - (int)c * E;
-  int e = active_idx ? active_idx[c * E + s] : s;
+  int e = s;
+  if (active_idx) {
+    e = active_idx[c * E + s];
+    if (s >= n_active[c]) return;
+  }
   e = min(max(e, 0), E - 1);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int kq0 = wave * (d / 4);
@@ -630,8 +634,6 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   if (n_chunks <= 0) return hipSuccess;
   if (n_chunks * L.E > 0x7fffffffLL) return hipErrorInvalidValue;
   StreamWs w = carve(L, n_chunks, k, ws);
-  hipError_t err = launch_worklist(n_active, n_chunks, L.E, w.items, w.total, s);
-  if (err != hipSuccess) return err;
   const int NB = b_frags(k), RT = L.d_e / 64;
   const int64_t max_items = n_chunks * L.E;
   if (NB == 1 && max_items <= 2048 && (L.d == 1024 || L.d == 2048)) {
@@ -639,12 +641,14 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
     const dim3 grid((unsigned)(max_items * (L.d_e / 16)));
 #define BLOCKFFN_SPLIT(nm, fw)                                                                             \
   hipLaunchKernelGGL((up_split_kernel<nm, fw>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, scores, token_mask, \
-                     active_idx, w.items, w.total, k, w.midB)
+                     active_idx, n_active, k, w.midB)
     if (L.d == 2048) { if (gated) BLOCKFFN_SPLIT(2, 16); else BLOCKFFN_SPLIT(1, 16); }
     else { if (gated) BLOCKFFN_SPLIT(2, 8); else BLOCKFFN_SPLIT(1, 8); }
 #undef BLOCKFFN_SPLIT
     return hipGetLastError();
   }
+  hipError_t err = launch_worklist(n_active, n_chunks, L.E, w.items, w.total, s);
+  if (err != hipSuccess) return err;
 #define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
   if (NB == nb && (gated ? 2 : 1) == nm && RT == rt)                                                      \
     return launch_up<nb, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, w.items, w.total, max_items, k, \

@@ -41,7 +41,11 @@ __device__ __forceinline__ float reduce_scatter64(float (&v)[64], int lane) {
   return v[0];
 }
 
-template <typename WT>
+// SPLIT = false: one workgroup runs all experts of its token tile and finishes the tokens.
+// SPLIT = true (few tokens in the launch): blockIdx.y selects one group of 8 experts; the
+// workgroup writes that group's pre-activations A^0 into `scores` and router_finish_kernel
+// normalises in place.  Both give the same bits: the summation order of A^0 is the same.
+template <typename WT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                           const float *__restrict__ x, int k, int tiles_per_chunk,
                                                           float *__restrict__ scores,
@@ -58,8 +62,9 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
   const int d = L.d, E = L.E;
   const size_t wr_base = (size_t)layer * E * d;
   const int n_groups = (E + 7) / 8;
+  const int g_lo = SPLIT ? (int)blockIdx.y : 0, g_hi = SPLIT ? (int)blockIdx.y + 1 : n_groups;
 
-  for (int g = 0; g < n_groups; ++g)
+  for (int g = g_lo; g < g_hi; ++g)
     if (lane < 64) part[wave][g * 8 + (lane >> 3)][lane & 7] = 0.0f;   // each lane owns one entry per group
 
   for (int cb = 0; cb < d; cb += kColsPerBlock) {
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
         for (int q = 0; q < 8; ++q) xr[t][q] = 0.0f;
       }
     }
-    for (int g = 0; g < n_groups; ++g) {
+    for (int g = g_lo; g < g_hi; ++g) {
       float v[64];
 #pragma unroll
       for (int el = 0; el < 8; ++el) {
@@ -103,6 +108,19 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
     }
   }
   __syncthreads();
+
+  if (SPLIT) {
+    // thread (el, t) of the first wave writes A^0 of expert g_lo*8 + el, token t
+    if (wave == 0) {
+      const int i = g_lo * 8 + (lane >> 3), t = lane & 7;
+      if (i < E && t < nt) {
+        float a0 = L.b_router ? L.b_router[(size_t)layer * E + i] : 0.0f;
+        a0 += (part[0][i][t] + part[1][i][t]) + (part[2][i][t] + part[3][i][t]);
+        scores[(tok0 + t) * E + i] = a0;
+      }
+    }
+    return;
+  }
 
   // Each wave finishes tokens wave, wave+4: lanes run over experts, one mask word at a time.
   for (int t = wave; t < nt; t += 4) {
@@ -141,6 +159,45 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
   }
 }
 
+// Second half of the split router: one wave per token turns A^0 (in `scores`) into the mask word(s)
+// and the RMSNorm'ed scores, in place.
+__global__ __launch_bounds__(kThreads) void router_finish_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
+                                                                 int64_t n_tok, int k, float *__restrict__ scores,
+                                                                 uint64_t *__restrict__ token_mask) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t tok = (int64_t)blockIdx.x * 4 + wave;
+  if (tok >= n_tok) return;
+  const int E = L.E;
+  const int layer = clamp_layer(chunk_layer, tok / k, L.n_layers);
+  float a1[kMaxMaskWords];
+  float sumsq = 0.0f;
+#pragma unroll
+  for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+    a1[wd] = 0.0f;
+    if (wd < L.W) {
+      const int i = wd * 64 + lane;
+      const float a0 = i < E ? scores[tok * E + i] : 0.0f;
+      const bool active = (i < E) && (a0 > 0.0f);
+      const uint64_t word = __ballot(active);
+      if (lane == 0) token_mask[tok * L.W + wd] = word;
+      a1[wd] = active ? a0 : 0.0f;
+      sumsq = fmaf(a1[wd], a1[wd], sumsq);
+    }
+  }
+  const float ms = wave_sum(sumsq) / (float)E;
+  const float rms = sqrtf(ms + L.eps);
+#pragma unroll
+  for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+    if (wd < L.W) {
+      const int i = wd * 64 + lane;
+      if (i < E) {
+        const float g = L.g_rms ? L.g_rms[(size_t)layer * E + i] : 1.0f;
+        scores[tok * E + i] = a1[wd] > 0.0f ? g * a1[wd] / rms : 0.0f;
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
@@ -149,11 +206,27 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
   const int64_t blocks = n_chunks * tiles;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  dim3 grid((unsigned)blocks), block(kThreads);
+  dim3 block(kThreads);
+  const int n_groups = (L.E + 7) / 8;
+  if (blocks * 2 <= 256 && n_groups > 1) {
+    // few token tiles: spread the expert groups over workgroups, then normalise
+    dim3 grid((unsigned)blocks, (unsigned)n_groups);
+    if (wdtype == BLOCKFFN_BF16)
+      hipLaunchKernelGGL((router_kernel<bf16_t, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+    else
+      hipLaunchKernelGGL((router_kernel<float, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const int64_t n_tok = n_chunks * k;
+    hipLaunchKernelGGL(router_finish_kernel, dim3((unsigned)((n_tok + 3) / 4)), block, 0, s, L, chunk_layer, n_tok, k,
+                       scores, token_mask);
+    return hipGetLastError();
+  }
+  dim3 grid((unsigned)blocks);
   if (wdtype == BLOCKFFN_BF16)
-    hipLaunchKernelGGL(router_kernel<bf16_t>, grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+    hipLaunchKernelGGL((router_kernel<bf16_t, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
   else
-    hipLaunchKernelGGL(router_kernel<float>, grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+    hipLaunchKernelGGL((router_kernel<float, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
   return hipGetLastError();
 }
 
