@@ -3,13 +3,14 @@
 // contraction over the experts of the union and the matrix cores are the bound, not HBM.
 //
 //   x  -> bf16 once (round to nearest even); products are bf16 x bf16 accumulated in fp32.
-//   up    one workgroup = (item of the (chunk, slot) list, 128 tokens, 64 neurons): a
-//         128 x 128 x d contraction (64 W_up rows and the 64 matching W_gate rows against 128
-//         tokens), both operands staged through double-buffered LDS in MFMA fragment order
-//         (global loads use the lane pattern of the operand, so LDS writes and reads are
-//         linear in the lane id and conflict free).  Swish/gating, score and mask are applied
-//         on the accumulators; mid is written as bf16 [chunk][slot][token][neuron].
-//   down  one workgroup = (chunk, 128 output columns, 128 tokens, split): the contraction runs
+//   up    one workgroup = (item of the (chunk, slot) list, TN tokens, TM/2 neurons): a
+//         TM x TN x d contraction (TM/2 W_up rows and the matching W_gate rows against TN
+//         tokens; TM = TN = 256, or 128 for short chunks), both operands staged through
+//         double-buffered LDS in MFMA fragment order (global loads use the lane pattern of the
+//         operand, so LDS writes and reads are linear in the lane id and conflict free).
+//         Swish/gating, score and mask are applied on the accumulators; mid is written as
+//         bf16 [chunk][slot][token][neuron].
+//   down  one workgroup = (chunk, TM output columns, TN tokens, split): the contraction runs
 //         over the slots of the split and the expert's neurons.  When a launch would have too
 //         few workgroups to fill the chip the slots are split and the partial sums are added
 //         by a second kernel in a fixed order (no atomics; results repeat bit for bit).
@@ -28,11 +29,28 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int kTileM = 128;               // weight rows per workgroup
-constexpr int kTileN = 128;               // tokens per workgroup
-constexpr int kTileK = 64;                // contraction elements per stage (two MFMA K-steps)
-constexpr int kStageVec = (kTileM + kTileN) * kTileK * 2 / 16;   // uint4 per stage (2048)
-constexpr int kLdsBytes = 2 * kStageVec * 16;                    // two stages, 64 KiB
+constexpr int kTileK = 64;   // contraction elements per stage (two MFMA K-steps)
+
+// Workgroup tile: TM weight rows x TN tokens, WR x WC waves.  The chip's L2 delivers about
+// 10-15 TB/s to the CUs (measured), the matrix cores want 2.5 PFLOP/s: a tile has to reuse every
+// byte it pulls from L2 for > 100 flop, which takes 256 x 256 (128 flop per byte); 128 x 128
+// (64 flop per byte) is kept for chunks too short to fill 256 token columns.
+template <int TM_, int TN_, int WR_, int WC_>
+struct Tile {
+  static constexpr int TM = TM_, TN = TN_, WR = WR_, WC = WC_;
+  static constexpr int WAVES = WR * WC, THREADS = WAVES * 64;
+  static constexpr int FA = TM / 16, FB = TN / 16;        // operand fragments per K-step
+  static constexpr int KS = kTileK / 32;                   // K-steps per stage
+  static constexpr int FI = FA / WR, FJ = FB / WC;         // a wave's tile, in fragments
+  static constexpr int NL = (FA + FB) * KS / WAVES;        // fragment loads per wave and stage
+  static constexpr int STAGE_VEC = (FA + FB) * KS * 64;    // uint4 per stage
+  static constexpr int LDS_BYTES = 2 * STAGE_VEC * 16;
+  static constexpr int A_WAVES = FA * KS / NL;             // waves [0, A_WAVES) load the A operand
+  static_assert(FA * KS % NL == 0 && (FA + FB) * KS % WAVES == 0, "loads must split evenly over the waves");
+  static_assert(NL % KS == 0 && (FA / 2) % (NL / KS) == 0, "a wave's A fragments must not straddle W_up / W_gate");
+};
+using TileSmall = Tile<128, 128, 2, 2>;   // 4 waves, 64 KiB LDS, 2 workgroups per CU
+using TileBig = Tile<256, 256, 2, 4>;     // 8 waves, 128 KiB LDS, 1 workgroup per CU
 
 __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
@@ -56,59 +74,65 @@ __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restr
   }
 }
 
-// One stage in LDS: fragments [0, 16) are the A operand (8 row fragments x 2 K-steps), [16, 32)
-// the B operand (8 token fragments x 2 K-steps); fragment = 64 lanes x 16 bytes.
-// Wave w loads fragments [8w, 8w + 8) of every stage.
-struct StageRegs {
-  uint4 v[8];
-};
-
-// Shared main loop.  a_ptr[f] / b_ptr[f] (f = 0..3: the 4 of this wave's 8 fragments that are
-// A resp. B ... ) are not used: every wave computes its own 8 source pointers with `src`.
-template <typename SrcFn>
-__device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, SrcFn src, f32x4 (&acc)[4][4],
-                                              const int (&a_frag)[4], int wc) {
+// One stage in LDS: fragment id = (operand fragment) * KS + K-step, A fragments first; a fragment
+// is 64 lanes x 16 bytes in lane order.  Wave w loads ids [w * NL, (w + 1) * NL): the first
+// A_WAVES waves the A operand, the others the B operand, so a wave's loads of a stage share one
+// base pointer (base(stage), uniform over the wave) and differ only by the lane offsets off[]
+// (elements), fixed for the whole loop: no divergent control flow around the loads.  Loads for
+// stage st+1 are issued before stage st is computed and written to the other LDS buffer after.
+template <typename T, typename BaseFn>
+__device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseFn base, const int (&off)[T::NL],
+                                              f32x4 (&acc)[T::FI][T::FJ], int a_lo, int a_hi, int wc) {
+  // this wave's A fragments: a_lo + i for the first FI/2, a_hi + (i - FI/2) for the rest
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  StageRegs regs;
-  if (n_stages > 0) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) regs.v[i] = src(0, wave * 8 + i);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) lds[(wave * 8 + i) * 64 + lane] = regs.v[i];
+  if (n_stages <= 0) return;   // uniform over the workgroup
+  static_assert(T::NL == 8, "the staging registers below are written out for 8 loads per wave");
+  // eight named staging registers (an array here was left in scratch memory by the compiler)
+  uint4 r0, r1, r2, r3, r4, r5, r6, r7;
+#define BLOCKFFN_LOAD8(ptr)                                                                      \
+  r0 = *reinterpret_cast<const uint4 *>((ptr) + off[0]); r1 = *reinterpret_cast<const uint4 *>((ptr) + off[1]); \
+  r2 = *reinterpret_cast<const uint4 *>((ptr) + off[2]); r3 = *reinterpret_cast<const uint4 *>((ptr) + off[3]); \
+  r4 = *reinterpret_cast<const uint4 *>((ptr) + off[4]); r5 = *reinterpret_cast<const uint4 *>((ptr) + off[5]); \
+  r6 = *reinterpret_cast<const uint4 *>((ptr) + off[6]); r7 = *reinterpret_cast<const uint4 *>((ptr) + off[7]);
+#define BLOCKFFN_STORE8(dst)                                                                     \
+  (dst)[0 * 64] = r0; (dst)[1 * 64] = r1; (dst)[2 * 64] = r2; (dst)[3 * 64] = r3;                \
+  (dst)[4 * 64] = r4; (dst)[5 * 64] = r5; (dst)[6 * 64] = r6; (dst)[7 * 64] = r7;
+  const int my = wave * T::NL * 64 + lane;   // this lane's slot in the first of its 8 fragments
+  {
+    const uint16_t *b0 = base(0);
+    BLOCKFFN_LOAD8(b0)
+    BLOCKFFN_STORE8(lds + my)
   }
   __syncthreads();
   for (int st = 0; st < n_stages; ++st) {
-    const bool more = st + 1 < n_stages;
-    if (more) {
+    const uint16_t *bn = base(min(st + 1, n_stages - 1));   // past the end: a harmless reload
+    BLOCKFFN_LOAD8(bn)
+    const uint4 *cur = lds + (st & 1) * T::STAGE_VEC;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) regs.v[i] = src(st + 1, wave * 8 + i);
+    for (int ks = 0; ks < T::KS; ++ks) {
+      uint4 a[T::FI], b[T::FJ];
+#pragma unroll
+      for (int i = 0; i < T::FI; ++i)
+        a[i] = cur[((i < T::FI / 2 ? a_lo + i : a_hi + i - T::FI / 2) * T::KS + ks) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < T::FJ; ++j) b[j] = cur[((T::FA + wc * T::FJ + j) * T::KS + ks) * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < T::FI; ++i)
+#pragma unroll
+        for (int j = 0; j < T::FJ; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
     }
-    const uint4 *cur = lds + (st & 1) * kStageVec;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      uint4 a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = cur[(a_frag[i] * 2 + ks) * 64 + lane];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = cur[(16 + (wc * 4 + j) * 2 + ks) * 64 + lane];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
-    }
-    if (more) {
-      uint4 *nxt = lds + ((st + 1) & 1) * kStageVec;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) nxt[(wave * 8 + i) * 64 + lane] = regs.v[i];
-    }
+    uint4 *nxt = lds + ((st + 1) & 1) * T::STAGE_VEC + my;
+    BLOCKFFN_STORE8(nxt)
     __syncthreads();
   }
+#undef BLOCKFFN_LOAD8
+#undef BLOCKFFN_STORE8
 }
 
 // ------------------------------------------------------------------------------------------------ up
 
-template <int NM>
-__global__ __launch_bounds__(kThreads, 2) void up_gemm_kernel(
+template <typename T, int NM>
+__global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint16_t *__restrict__ xb,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, int k, int tiles_t, int tiles_j,
@@ -127,58 +151,61 @@ __global__ __launch_bounds__(kThreads, 2) void up_gemm_kernel(
   int e = active_idx ? active_idx[c * E + s] : s;
   e = min(max(e, 0), E - 1);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
-  const int t0 = tt * kTileN;
-  constexpr int kNeurons = NM == 2 ? 64 : 128;   // neurons per workgroup
+  const int t0 = tt * T::TN;
+  constexpr int kNeurons = T::TM / NM;   // neurons per workgroup
   const int j0 = tj * kNeurons;
   const size_t w_expert = ((size_t)layer * E + e) * d_e;
-  const int wr = wave & 1, wc = wave >> 1;
+  const int wr = wave % T::WR, wc = wave / T::WR;
 
-  // A fragment fa (0..7): NM == 2: fa < 4 -> W_up rows j0 + 16 fa, else W_gate rows j0 + 16 (fa - 4);
-  //                       NM == 1: W_up rows j0 + 16 fa.
-  auto src = [&](int st, int id) -> uint4 {
-    const int part = id >> 4, frag = (id >> 1) & 7, ks = id & 1;
-    const size_t koff = (size_t)st * kTileK + ks * 32 + g * 8;
-    if (part == 0) {
-      const void *w = (NM == 2 && frag >= 4) ? L.w_gate : L.w_up;
-      const int row = j0 + (NM == 2 ? (frag & 3) : frag) * 16 + r;
-      return *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(w) + (w_expert + row) * d + koff);
-    }
-    const int t = t0 + frag * 16 + r;
-    if (t >= k) return make_uint4(0, 0, 0, 0);
-    return *reinterpret_cast<const uint4 *>(xb + (size_t)(c * k + t) * d + koff);
-  };
+  // A fragment f: gated: f < FA/2 -> W_up rows j0 + 16 f, else W_gate rows j0 + 16 (f - FA/2);
+  // Eq. 2: W_up rows j0 + 16 f.  B fragment f: tokens t0 + 16 f.  A token index past the chunk
+  // is clamped: its column of the product comes from a valid row and is never stored.
+  const bool is_a = wave < T::A_WAVES;
+  const int f0 = (is_a ? wave : wave - T::A_WAVES) * (T::NL / T::KS);   // first fragment this wave loads
+  const bool gate_wave = NM == 2 && is_a && f0 >= T::FA / 2;
+  int off[T::NL];
+#pragma unroll
+  for (int i = 0; i < T::NL; ++i) {
+    const int f = f0 + i / T::KS, ks = i % T::KS;
+    int row;
+    if (is_a) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + r;
+    else row = min(t0 + f * 16 + r, k - 1);
+    off[i] = row * d + ks * 32 + g * 8;
+  }
+  const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
+  const uint16_t *base0 = is_a ? wsel : xb + (size_t)c * k * d;
+  auto base = [&](int st) { return base0 + (size_t)st * kTileK; };
 
-  f32x4 acc[4][4];
+  f32x4 acc[T::FI][T::FJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < T::FI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // this wave's A fragments: NM == 2: up {2wr, 2wr+1} and the matching gate {4+2wr, 5+2wr}
-  int a_frag[4];
-  if (NM == 2) { a_frag[0] = 2 * wr; a_frag[1] = 2 * wr + 1; a_frag[2] = 4 + 2 * wr; a_frag[3] = 5 + 2 * wr; }
-  else { a_frag[0] = 4 * wr; a_frag[1] = 4 * wr + 1; a_frag[2] = 4 * wr + 2; a_frag[3] = 4 * wr + 3; }
-  gemm_mainloop(lds, d / kTileK, src, acc, a_frag, wc);
+    for (int j = 0; j < T::FJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // this wave's A fragments: gated: FI/2 up fragments and the FI/2 matching gate fragments
+  const int a_lo = NM == 2 ? wr * (T::FI / 2) : wr * T::FI;
+  const int a_hi = NM == 2 ? T::FA / 2 + wr * (T::FI / 2) : wr * T::FI + T::FI / 2;
+  gemm_mainloop<T>(lds, d / kTileK, base, off, acc, a_lo, a_hi, wc);
 
   // D[i = neuron 4g + q of the fragment][j = token n of the fragment]
   const int n = lane & 15;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int t = t0 + wc * 64 + j * 16 + n;
+  for (int j = 0; j < T::FJ; ++j) {
+    const int t = t0 + (wc * T::FJ + j) * 16 + n;
     if (t >= k) continue;
     const int64_t tok = c * k + t;
     const bool on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
     const float f = scores[tok * E + e];
-    constexpr int kOut = NM == 2 ? 2 : 4;
+    constexpr int kOut = T::FI / NM;
 #pragma unroll
     for (int i = 0; i < kOut; ++i) {
       uint32_t p[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float u = acc[i][j][q];
-        const float h = NM == 2 ? swish(acc[i + 2][j][q]) * u : swish(u);
+        const float h = NM == 2 ? swish(acc[i + (NM - 1) * kOut][j][q]) * u : swish(u);
         p[q] = bf16_bits(on ? f * h : 0.0f);
       }
-      const int neuron = j0 + (NM == 2 ? (2 * wr + i) : (4 * wr + i)) * 16 + 4 * g;
+      const int neuron = j0 + (wr * kOut + i) * 16 + 4 * g;
       *reinterpret_cast<uint2 *>(H + (((size_t)c * E + s) * k + t) * d_e + neuron) =
           make_uint2(p[0] | p[1] << 16, p[2] | p[3] << 16);
     }
@@ -187,7 +214,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_gemm_kernel(
 
 // ------------------------------------------------------------------------------------------------ down
 
-__global__ __launch_bounds__(kThreads, 2) void down_gemm_kernel(
+template <typename T>
+__global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, int k, int tiles_t, int tiles_c, int splits,
     const uint16_t *__restrict__ H, float *__restrict__ out, size_t split_stride) {
@@ -203,42 +231,48 @@ __global__ __launch_bounds__(kThreads, 2) void down_gemm_kernel(
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
   const int s_lo = (int)((int64_t)n_act * sp / splits), s_hi = (int)((int64_t)n_act * (sp + 1) / splits);
-  const int t0 = tt * kTileN, col0 = tc * kTileM;
-  const int wr = wave & 1, wc = wave >> 1;
+  const int t0 = tt * T::TN, col0 = tc * T::TM;
+  const int wr = wave % T::WR, wc = wave / T::WR;
   const int st_per_slot = d_e / kTileK;
 
-  auto src = [&](int st, int id) -> uint4 {
-    const int part = id >> 4, frag = (id >> 1) & 7, ks = id & 1;
+  // A fragment f: W_down rows col0 + 16 f of the stage's expert; B fragment f: mid rows of tokens
+  // t0 + 16 f (clamped as in the up kernel) of the stage's slot.
+  const bool is_a = wave < T::A_WAVES;
+  const int f0 = (is_a ? wave : wave - T::A_WAVES) * (T::NL / T::KS);
+  int off[T::NL];
+#pragma unroll
+  for (int i = 0; i < T::NL; ++i) {
+    const int f = f0 + i / T::KS, ks = i % T::KS;
+    const int row = is_a ? col0 + f * 16 + r : min(t0 + f * 16 + r, k - 1);
+    off[i] = row * d_e + ks * 32 + g * 8;
+  }
+  auto base = [&](int st) -> const uint16_t * {
     const int s = s_lo + st / st_per_slot;
-    const size_t koff = (size_t)(st % st_per_slot) * kTileK + ks * 32 + g * 8;
-    if (part == 0) {
+    const size_t koff = (size_t)(st % st_per_slot) * kTileK;
+    if (is_a) {
       int e = active_idx ? active_idx[c * E + s] : s;
       e = min(max(e, 0), E - 1);
-      const size_t row = ((size_t)layer * E + e) * d + col0 + frag * 16 + r;
-      return *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(L.w_down) + row * d_e + koff);
+      return static_cast<const uint16_t *>(L.w_down) + ((size_t)layer * E + e) * d * d_e + koff;
     }
-    const int t = t0 + frag * 16 + r;
-    if (t >= k) return make_uint4(0, 0, 0, 0);
-    return *reinterpret_cast<const uint4 *>(H + (((size_t)c * E + s) * k + t) * d_e + koff);
+    return H + ((size_t)c * E + s) * k * d_e + koff;
   };
 
-  f32x4 acc[4][4];
+  f32x4 acc[T::FI][T::FJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < T::FI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int a_frag[4] = {4 * wr, 4 * wr + 1, 4 * wr + 2, 4 * wr + 3};
-  gemm_mainloop(lds, (s_hi - s_lo) * st_per_slot, src, acc, a_frag, wc);
+    for (int j = 0; j < T::FJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  gemm_mainloop<T>(lds, (s_hi - s_lo) * st_per_slot, base, off, acc, wr * T::FI, wr * T::FI + T::FI / 2, wc);
 
   const int n = lane & 15;
   float *dst = out + (size_t)sp * split_stride;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int t = t0 + wc * 64 + j * 16 + n;
+  for (int j = 0; j < T::FJ; ++j) {
+    const int t = t0 + (wc * T::FJ + j) * 16 + n;
     if (t >= k) continue;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int col = col0 + (4 * wr + i) * 16 + 4 * g;
+    for (int i = 0; i < T::FI; ++i) {
+      const int col = col0 + (wr * T::FI + i) * 16 + 4 * g;
       *reinterpret_cast<float4 *>(dst + (size_t)(c * k + t) * d + col) =
           make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
     }
@@ -260,10 +294,18 @@ __global__ __launch_bounds__(kThreads) void reduce_splits_kernel(const float *__
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// 256-wide tiles when the chunk fills them and the shape divides; else 128-wide.
+bool big_up(const LayerView &L, int k, bool gated) {
+  return k >= 192 && L.d % 256 == 0 && L.d_e % (gated ? 128 : 256) == 0;
+}
+bool big_down(const LayerView &L, int k) { return k >= 192 && L.d % 256 == 0; }
+
 int down_splits(const LayerView &L, int64_t n_chunks, int k) {
-  const int64_t base = n_chunks * ((k + kTileN - 1) / kTileN) * (L.d / kTileM);
-  if (base >= 512) return 1;
-  return (int)std::min<int64_t>(8, (512 + base - 1) / base);
+  const bool big = big_down(L, k);
+  const int tile = big ? 256 : 128, want = big ? 256 : 512;
+  const int64_t base = n_chunks * ((k + tile - 1) / tile) * (L.d / tile);
+  if (base >= want) return 1;
+  return (int)std::min<int64_t>(16, (want + base - 1) / base);
 }
 
 struct GemmWs {
@@ -284,6 +326,50 @@ GemmWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
   p += align256(((size_t)n_chunks * L.E + 64) * sizeof(int32_t));
   w.part = reinterpret_cast<float *>(p);
   return w;
+}
+
+template <typename T>
+hipError_t launch_up_tile(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *scores,
+                          const uint64_t *token_mask, const int32_t *active_idx, const GemmWs &w, int64_t n_chunks,
+                          int k, hipStream_t s) {
+  const int tiles_t = (k + T::TN - 1) / T::TN, tiles_j = L.d_e / (T::TM / (gated ? 2 : 1));
+  const int64_t grid = n_chunks * L.E * tiles_t * tiles_j;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 1>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 2>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    if (e1 != hipSuccess || e2 != hipSuccess) return e1 != hipSuccess ? e1 : e2;
+    attr_set = true;
+  }
+  if (gated)
+    hipLaunchKernelGGL((up_gemm_kernel<T, 2>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
+                       w.xb, scores, token_mask, active_idx, w.items, w.total, k, tiles_t, tiles_j, w.H);
+  else
+    hipLaunchKernelGGL((up_gemm_kernel<T, 1>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
+                       w.xb, scores, token_mask, active_idx, w.items, w.total, k, tiles_t, tiles_j, w.H);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_down_tile(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
+                            const int32_t *n_active, int64_t n_chunks, int k, int splits, const uint16_t *H,
+                            float *out, size_t stride, hipStream_t s) {
+  const int tiles_t = (k + T::TN - 1) / T::TN, tiles_c = L.d / T::TM;
+  const int64_t grid = n_chunks * tiles_t * tiles_c * splits;
+  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(down_gemm_kernel<T>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((down_gemm_kernel<T>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
+                     active_idx, n_active, k, tiles_t, tiles_c, splits, H, out, stride);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -312,25 +398,9 @@ hipError_t launch_up_gemm(const LayerView &L, bool gated, const int32_t *chunk_l
   if (err != hipSuccess) return err;
   err = launch_worklist(n_active, n_chunks, L.E, w.items, w.total, s);
   if (err != hipSuccess) return err;
-  const int tiles_t = (k + kTileN - 1) / kTileN, tiles_j = L.d_e / (gated ? 64 : 128);
-  const int64_t grid = n_chunks * L.E * tiles_t * tiles_j;
-  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<1>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<2>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e1 != hipSuccess || e2 != hipSuccess) return e1 != hipSuccess ? e1 : e2;
-    attr_set = true;
-  }
-  if (gated)
-    hipLaunchKernelGGL(up_gemm_kernel<2>, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, s, L, chunk_layer, w.xb,
-                       scores, token_mask, active_idx, w.items, w.total, k, tiles_t, tiles_j, w.H);
-  else
-    hipLaunchKernelGGL(up_gemm_kernel<1>, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, s, L, chunk_layer, w.xb,
-                       scores, token_mask, active_idx, w.items, w.total, k, tiles_t, tiles_j, w.H);
-  return hipGetLastError();
+  if (big_up(L, k, gated))
+    return launch_up_tile<TileBig>(L, gated, chunk_layer, scores, token_mask, active_idx, w, n_chunks, k, s);
+  return launch_up_tile<TileSmall>(L, gated, chunk_layer, scores, token_mask, active_idx, w, n_chunks, k, s);
 }
 
 hipError_t launch_down_gemm(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
@@ -339,21 +409,12 @@ hipError_t launch_down_gemm(const LayerView &L, const int32_t *chunk_layer, cons
   if (n_chunks <= 0) return hipSuccess;
   GemmWs w = carve(L, n_chunks, k, const_cast<void *>(ws));
   const int splits = down_splits(L, n_chunks, k);
-  const int tiles_t = (k + kTileN - 1) / kTileN, tiles_c = L.d / kTileM;
-  const int64_t grid = n_chunks * tiles_t * tiles_c * splits;
-  if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(down_gemm_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   const size_t stride = (size_t)n_chunks * k * L.d;
   float *out = splits > 1 ? w.part : y;
-  hipLaunchKernelGGL(down_gemm_kernel, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, s, L, chunk_layer, active_idx,
-                     n_active, k, tiles_t, tiles_c, splits, w.H, out, stride);
-  hipError_t err = hipGetLastError();
+  hipError_t err =
+      big_down(L, k)
+          ? launch_down_tile<TileBig>(L, chunk_layer, active_idx, n_active, n_chunks, k, splits, w.H, out, stride, s)
+          : launch_down_tile<TileSmall>(L, chunk_layer, active_idx, n_active, n_chunks, k, splits, w.H, out, stride, s);
   if (err != hipSuccess || splits == 1) return err;
   const size_t n4 = stride / 4;
   hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)std::min<size_t>((n4 + kThreads - 1) / kThreads, 4096)),

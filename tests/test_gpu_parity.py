@@ -69,7 +69,7 @@ def test_shapes(d, E, d_e, k, C, wdtype, gated, impl):
 
 
 @pytest.mark.parametrize("k,d_e,C,gated", [(32, 256, 3, True), (40, 64, 3, True), (200, 128, 2, True),
-                                           (130, 128, 2, False), (512, 256, 1, True)])
+                                           (130, 128, 2, False), (300, 256, 1, False), (512, 256, 1, True)])
 def test_large_chunks(k, d_e, C, gated, impl):
     """k = 32 is the largest streamed chunk; above it the matrix-core grouped contraction runs
     (ragged token tiles at 40 / 130 / 200, the 512-token prefill chunk at full size)."""
