@@ -44,6 +44,9 @@ def parse():
     p.add_argument("--replicas", type=int, default=32, help="distinct weight sets the chunks rotate through")
     p.add_argument("--chunks", type=int, default=0, help="override the number of chunks")
     p.add_argument("--swish", action="store_true", help="non-gated experts (Eq. 2) instead of the gated ones")
+    p.add_argument("--sequential", action="store_true",
+                   help="enqueue the chunks one after the other (one chunk per launch), as a layer stack does: "
+                        "with --workload stack_decode_k8 --chunks 24 --replicas 24 a step is a 24-layer decode step")
     p.add_argument("--dense-steps", type=int, default=3)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--cpu-sample-chunks", type=int, default=512)
@@ -127,7 +130,23 @@ def main():
     C, k = w.n_chunks, w.k
     stages = ("router", "union", "up", "down")
 
+    def step_sequential():
+        for c in range(C):
+            t0_, t1_ = c * k, (c + 1) * k
+            cl = chunk_layer[c:c + 1]
+            B.blockffn_router(L, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], cl)
+            B.blockffn_chunk_union(buf.token_mask[t0_:t1_], 1, k, L.E, buf.union_mask[c:c + 1], buf.active_idx[c:c + 1],
+                                   buf.n_active[c:c + 1], buf.stats)
+            B.blockffn_sparse_ffn(L, x[t0_:t1_], buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], buf.active_idx[c:c + 1],
+                                  buf.n_active[c:c + 1], 1, k, buf.y[t0_:t1_], buf.workspace, cl)
+
     def step(ev=None):
+        if args.sequential:
+            if ev: ev[0].record()
+            step_sequential()
+            if ev:
+                for e in ev[1:]: e.record()
+            return
         if ev: ev[0].record()
         B.blockffn_router(L, x, C, k, buf.scores, buf.token_mask, chunk_layer)
         if ev: ev[1].record()
@@ -163,7 +182,7 @@ def main():
 
     # dense FFN of equal parameter count: same kernels, every expert, no masks
     dense_ms = None
-    if args.dense_steps > 0:
+    if args.dense_steps > 0 and not args.sequential:
         B.blockffn_dense_ffn(L, x, buf.scores, C, k, y_dense, buf.workspace, chunk_layer)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -176,6 +195,9 @@ def main():
     ffn_ms = (stage_us["up"] + stage_us["down"]) / 1e3
 
     up_s = stage_us["up"] * 1e-6
+    if args.sequential:   # no per-kernel split in this mode: price the whole step against all active bytes
+        up_s, up_bytes = ms_per_step * 1e-3, active_bytes
+        args.dense_steps = 0
     out = {
         "metric": "µs/chunk + active-weight HBM GB/s (%% peak) at k=%d; speedup vs dense FFN" % k,
         "value": active_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -184,10 +206,11 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights, f32 activations and accumulation" if w.wdtype == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: d=%d E=%d d_e=%d %s experts, k=%d x %d chunks, sigma=%.2f, %d weight sets (%.2f GB)"
+        "config": {"workload": "%s: d=%d E=%d d_e=%d %s experts, k=%d x %d chunks, sigma=%.2f, %d weight sets (%.2f GB)%s"
                                % (w.name, w.d, w.E, w.d_e, "gated" if w.gated else "swish", k, C, w.sigma, R,
-                                  R * w.E * w.expert_bytes / 1e9),
-                   "replicas": R},
+                                  R * w.E * w.expert_bytes / 1e9,
+                                  ", chunks enqueued one after the other" if args.sequential else ""),
+                   "replicas": R, "sequential": args.sequential},
         "us_per_chunk": ms_per_step * 1e3 / C,
         "tokens_per_s": w.n_tok / (ms_per_step * 1e-3),
         "pct_hbm_peak": 100.0 * active_bytes / (ms_per_step * 1e-3) / HBM_PEAK,
