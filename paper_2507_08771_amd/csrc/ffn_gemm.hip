@@ -29,18 +29,18 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int kTileK = 64;   // contraction elements per stage (two MFMA K-steps)
 
 // Workgroup tile: TM weight rows x TN tokens, WR x WC waves.  The chip's L2 delivers about
 // 10-15 TB/s to the CUs (measured), the matrix cores want 2.5 PFLOP/s: a tile has to reuse every
 // byte it pulls from L2 for > 100 flop, which takes 256 x 256 (128 flop per byte); 128 x 128
 // (64 flop per byte) is kept for chunks too short to fill 256 token columns.
-template <int TM_, int TN_, int WR_, int WC_>
+template <int TM_, int TN_, int WR_, int WC_, int KS_>
 struct Tile {
   static constexpr int TM = TM_, TN = TN_, WR = WR_, WC = WC_;
+  static constexpr int KS = KS_;                           // MFMA K-steps (32 elements) per stage
+  static constexpr int TK = 32 * KS;                       // contraction elements per stage
   static constexpr int WAVES = WR * WC, THREADS = WAVES * 64;
   static constexpr int FA = TM / 16, FB = TN / 16;        // operand fragments per K-step
-  static constexpr int KS = kTileK / 32;                   // K-steps per stage
   static constexpr int FI = FA / WR, FJ = FB / WC;         // a wave's tile, in fragments
   static constexpr int NL = (FA + FB) * KS / WAVES;        // fragment loads per wave and stage
   static constexpr int STAGE_VEC = (FA + FB) * KS * 64;    // uint4 per stage
@@ -49,8 +49,10 @@ struct Tile {
   static_assert(FA * KS % NL == 0 && (FA + FB) * KS % WAVES == 0, "loads must split evenly over the waves");
   static_assert(NL % KS == 0 && (FA / 2) % (NL / KS) == 0, "a wave's A fragments must not straddle W_up / W_gate");
 };
-using TileSmall = Tile<128, 128, 2, 2>;   // 4 waves, 64 KiB LDS, 2 workgroups per CU
-using TileBig = Tile<256, 256, 2, 4>;     // 8 waves, 128 KiB LDS, 1 workgroup per CU
+// (A 4-wave variant of the 256-wide tile with 128 x 128 per wave, which halves the LDS reads per
+// MFMA, was slower: one wave per SIMD leaves nothing to cover LDS and memory latency with.)
+using TileSmall = Tile<128, 128, 2, 2, 2>;   // 4 waves, 64 KiB LDS, 2 workgroups per CU
+using TileBig = Tile<256, 256, 2, 4, 2>;     // 8 waves, 128 KiB LDS, 1 workgroup per CU
 
 __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   }
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
   const uint16_t *base0 = is_a ? wsel : xb + (size_t)c * k * d;
-  auto base = [&](int st) { return base0 + (size_t)st * kTileK; };
+  auto base = [&](int st) { return base0 + (size_t)st * T::TK; };
 
   f32x4 acc[T::FI][T::FJ];
 #pragma unroll
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // this wave's A fragments: gated: FI/2 up fragments and the FI/2 matching gate fragments
   const int a_lo = NM == 2 ? wr * (T::FI / 2) : wr * T::FI;
   const int a_hi = NM == 2 ? T::FA / 2 + wr * (T::FI / 2) : wr * T::FI + T::FI / 2;
-  gemm_mainloop<T>(lds, d / kTileK, base, off, acc, a_lo, a_hi, wc);
+  gemm_mainloop<T>(lds, d / T::TK, base, off, acc, a_lo, a_hi, wc);
 
   // D[i = neuron 4g + q of the fragment][j = token n of the fragment]
   const int n = lane & 15;
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   const int s_lo = (int)((int64_t)n_act * sp / splits), s_hi = (int)((int64_t)n_act * (sp + 1) / splits);
   const int t0 = tt * T::TN, col0 = tc * T::TM;
   const int wr = wave % T::WR, wc = wave / T::WR;
-  const int st_per_slot = d_e / kTileK;
+  const int st_per_slot = d_e / T::TK;
 
   // A fragment f: W_down rows col0 + 16 f of the stage's expert; B fragment f: mid rows of tokens
   // t0 + 16 f (clamped as in the up kernel) of the stage's slot.
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   }
   auto base = [&](int st) -> const uint16_t * {
     const int s = s_lo + st / st_per_slot;
-    const size_t koff = (size_t)(st % st_per_slot) * kTileK;
+    const size_t koff = (size_t)(st % st_per_slot) * T::TK;
     if (is_a) {
       int e = active_idx ? active_idx[c * E + s] : s;
       e = min(max(e, 0), E - 1);
