@@ -109,10 +109,11 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
                               const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
                               hipStream_t s);
 
-// Flat (chunk, slot) list of the active experts: items[i] = chunk * E + slot, *total = its length
-// (n_active == nullptr: every chunk has E slots).  items needs n_chunks * E entries.
-hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int32_t *items, int32_t *total,
-                           hipStream_t s);
+// Flat list of the active experts in groups of `group` consecutive slots: items[i] = chunk * E +
+// first slot of the group, *total = its length (n_active == nullptr: every chunk has E slots).
+// items needs n_chunks * E entries.
+hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int group, int32_t *items,
+                           int32_t *total, hipStream_t s);
 
 // Matrix-core grouped contraction for large chunks (bf16 weights, 32 < k <= 512).
 bool gemm_supported(const LayerView &L, int wdtype, int k, bool gated);

@@ -398,7 +398,7 @@ hipError_t launch_up_gemm(const LayerView &L, bool gated, const int32_t *chunk_l
                      dim3(kThreads), 0, s, x, w.xb, n8);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  err = launch_worklist(n_active, n_chunks, L.E, w.items, w.total, s);
+  err = launch_worklist(n_active, n_chunks, L.E, 1, w.items, w.total, s);
   if (err != hipSuccess) return err;
   if (big_up(L, k, gated))
     return launch_up_tile<TileBig>(L, gated, chunk_layer, scores, token_mask, active_idx, w, n_chunks, k, s);

@@ -60,9 +60,11 @@ constexpr int acc_tiles(int NB) { return NB == 4 ? 2 : 1; }
 constexpr int acc_of(int NB, int bf) { return NB == 4 ? bf / 2 : 0; }
 constexpr int tokens_of(int NB) { return NB == 1 ? 8 : (NB == 2 ? 16 : 32); }
 
-// Flat (chunk, slot) work list: items[i] = chunk * E + slot for every slot below n_active[chunk].
+// Flat work list: items[i] = chunk * E + slot for every `group`-th slot below n_active[chunk]
+// (an item stands for up to `group` consecutive slots of one chunk).
 __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restrict__ n_active, int64_t n_chunks, int E,
-                                                        int32_t *__restrict__ items, int32_t *__restrict__ total) {
+                                                        int group, int32_t *__restrict__ items,
+                                                        int32_t *__restrict__ total) {
   __shared__ int wave_tot[16];
   __shared__ int carry;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restric
   for (int64_t c0 = 0; c0 < n_chunks; c0 += 1024) {
     const int64_t c = c0 + tid;
     int n = 0;
-    if (c < n_chunks) n = n_active ? min(max(n_active[c], 0), E) : E;
+    if (c < n_chunks) n = ((n_active ? min(max(n_active[c], 0), E) : E) + group - 1) / group;
     int incl = n;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restric
     int base = carry;
     for (int w = 0; w < wave; ++w) base += wave_tot[w];
     const int start = base + incl - n;
-    for (int s = 0; s < n; ++s) items[start + s] = (int32_t)(c * E + s);
+    for (int s = 0; s < n; ++s) items[start + s] = (int32_t)(c * E + s * group);
     __syncthreads();
     if (tid == 1023) carry = base + incl;
     __syncthreads();
@@ -99,7 +101,8 @@ template <int NB, int NM, int RT>
 __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, int k, uint16_t *__restrict__ midB) {
+    const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
+    int group, int k, uint16_t *__restrict__ midB) {
   extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
   constexpr int KC = 2048 / NB;   // contraction elements per LDS fill
   constexpr int NA = acc_tiles(NB);
@@ -110,12 +113,18 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   const int total = *total_ptr;
   const size_t row_bytes = (size_t)d * 2;
 
-  auto item_expert = [&](int item, int64_t &c, int &s, int &e) {
-    const int code = items[item];   // chunk * E + slot
+  auto slot_expert = [&](int64_t c, int s) {
+    const int e = active_idx ? active_idx[c * E + s] : s;
+    return min(max(e, 0), E - 1);
+  };
+  // an item is up to `group` consecutive slots of one chunk: the chunk's split x is written to
+  // LDS once per item and serves all of them
+  auto item_decode = [&](int item, int64_t &c, int &s, int &ns) {
+    const int code = items[item];   // chunk * E + first slot
     c = code / E;
     s = code - (int)c * E;
-    e = active_idx ? active_idx[c * E + s] : s;
-    e = min(max(e, 0), E - 1);
+    const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
+    ns = max(1, min(group, n_act - s));
   };
   // per-lane byte pointer to the first fragment of (layer, expert, tile rr, matrix m)
   auto tile_ptr = [&](int layer, int e, int rr, int m) -> const char * {
@@ -128,9 +137,12 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   int item = blockIdx.x;
   if (item >= total) return;
   int64_t c;
-  int s, e;
-  item_expert(item, c, s, e);
+  int s, ns;        // current slot and slots left in the item (this one included)
+  item_decode(item, c, s, ns);
+  int e = slot_expert(c, s);
   int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  int64_t c_loaded = -1;   // chunk and K-chunk whose split x is in LDS
+  int kc_loaded = -1;
   {
     const char *p = tile_ptr(layer, e, 0, 0);
 #pragma unroll
@@ -138,14 +150,20 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   }
 
   while (true) {
-    const int next_item = item + gridDim.x;
-    const bool has_next = next_item < total;
-    int64_t c_n = 0;
-    int s_n = 0, e_n = 0, layer_n = 0;
-    if (has_next) {
-      item_expert(next_item, c_n, s_n, e_n);
-      layer_n = clamp_layer(chunk_layer, c_n, L.n_layers);
+    // what comes after this slot: the item's next slot, or the first slot of the next item
+    bool has_next = true;
+    int next_item = item;
+    int64_t c_n = c;
+    int s_n = s + 1, ns_n = ns - 1, e_n = 0, layer_n = layer;
+    if (ns_n == 0) {
+      next_item = item + gridDim.x;
+      has_next = next_item < total;
+      if (has_next) {
+        item_decode(next_item, c_n, s_n, ns_n);
+        layer_n = clamp_layer(chunk_layer, c_n, L.n_layers);
+      }
     }
+    if (has_next) e_n = slot_expert(c_n, s_n);
 
     f32x4 acc[RT][NM][NA];
 #pragma unroll
@@ -158,9 +176,10 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     for (int kc0 = 0; kc0 < d; kc0 += KC) {
       const int kc_len = min(KC, d - kc0);
       const int nkb = kc_len / 512;
-      __syncthreads();   // every wave is done with the previous contents of xB
+      const bool refill = c != c_loaded || kc0 != kc_loaded;   // uniform over the workgroup
+      if (refill) __syncthreads();   // every wave is done with the previous contents of xB
       // split x[c*k + tok][kc0 .. kc0 + kc_len) into hi/lo bf16 in B-operand order
-      for (int it = tid; it < (kc_len / 8) * TOK; it += kThreads) {
+      for (int it = tid; refill && it < (kc_len / 8) * TOK; it += kThreads) {
         const int tok = it % TOK, cg = it / TOK;   // cg: group of 8 columns
         const int kstep = cg >> 2, gg = cg & 3;
         uint32_t hi[8], lo[8];
@@ -187,7 +206,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
           dst[64] = vlo;
         }
       }
-      __syncthreads();
+      if (refill) __syncthreads();
+      c_loaded = c;
+      kc_loaded = kc0;
       const bool last_kc = kc0 + KC >= d;
 #pragma unroll
       for (int rr = 0; rr < RT; ++rr) {
@@ -267,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 
     if (!has_next) break;
     item = next_item;
-    c = c_n; s = s_n; e = e_n; layer = layer_n;
+    c = c_n; s = s_n; ns = ns_n; e = e_n; layer = layer_n;
   }
 }
 
@@ -514,8 +535,9 @@ int num_cus() {
 
 template <int NB, int NM, int RT>
 hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float *x, const float *scores,
-                     const uint64_t *token_mask, const int32_t *active_idx, const int32_t *items,
-                     const int32_t *total, int64_t max_items, int k, uint16_t *midB, hipStream_t s) {
+                     const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
+                     const int32_t *items, const int32_t *total, int group, int64_t max_items, int k, uint16_t *midB,
+                     hipStream_t s) {
   static bool attr_set = false;
   auto kern = up_stream_kernel<NB, NM, RT>;
   if (!attr_set) {
@@ -526,7 +548,7 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float
   }
   const int64_t grid = std::min<int64_t>(max_items, (int64_t)num_cus() * 2);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, x, scores, token_mask,
-                     active_idx, items, total, k, midB);
+                     active_idx, n_active, items, total, group, k, midB);
   return hipGetLastError();
 }
 
@@ -609,9 +631,9 @@ StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
 
 }  // namespace
 
-hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int32_t *items, int32_t *total,
-                           hipStream_t s) {
-  hipLaunchKernelGGL(worklist_kernel, dim3(1), dim3(1024), 0, s, n_active, n_chunks, E, items, total);
+hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int group, int32_t *items,
+                           int32_t *total, hipStream_t s) {
+  hipLaunchKernelGGL(worklist_kernel, dim3(1), dim3(1024), 0, s, n_active, n_chunks, E, group, items, total);
   return hipGetLastError();
 }
 
@@ -647,12 +669,15 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
 #undef BLOCKFFN_SPLIT
     return hipGetLastError();
   }
-  hipError_t err = launch_worklist(n_active, n_chunks, L.E, w.items, w.total, s);
+  // Two slots per item when the whole contraction of x fits in LDS: the 64 KiB of x are then
+  // fetched and split once per 2 experts.  (With more K-chunks LDS is refilled per K-chunk anyway.)
+  const int group = (L.d <= 2048 / NB) ? 2 : 1;
+  hipError_t err = launch_worklist(n_active, n_chunks, L.E, group, w.items, w.total, s);
   if (err != hipSuccess) return err;
 #define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
   if (NB == nb && (gated ? 2 : 1) == nm && RT == rt)                                                      \
-    return launch_up<nb, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, w.items, w.total, max_items, k, \
-                                 w.midB, s);
+    return launch_up<nb, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, n_active, w.items, w.total, \
+                                 group, max_items, k, w.midB, s);
   BLOCKFFN_CASE(1, 1, 1) BLOCKFFN_CASE(1, 1, 2) BLOCKFFN_CASE(1, 1, 4)
   BLOCKFFN_CASE(1, 2, 1) BLOCKFFN_CASE(1, 2, 2) BLOCKFFN_CASE(1, 2, 4)
   BLOCKFFN_CASE(2, 1, 1) BLOCKFFN_CASE(2, 1, 2) BLOCKFFN_CASE(2, 1, 4)
