@@ -41,7 +41,9 @@ def parse():
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="spec_k8")
-    p.add_argument("--replicas", type=int, default=32, help="distinct weight sets the chunks rotate through")
+    p.add_argument("--replicas", type=int, default=0,
+                   help="distinct weight sets the chunks rotate through (0: 32, or more where 32 sets stay "
+                        "below 3 GiB, so that the rotation cannot live in the 256 MiB last-level cache)")
     p.add_argument("--chunks", type=int, default=0, help="override the number of chunks")
     p.add_argument("--swish", action="store_true", help="non-gated experts (Eq. 2) instead of the gated ones")
     p.add_argument("--sequential", action="store_true",
@@ -119,7 +121,9 @@ def main():
         w = w.replace(n_chunks=args.chunks)
     if args.swish:
         w = w.replace(gated=False)
-    R = max(1, min(args.replicas, w.n_chunks))
+    set_bytes = w.E * w.expert_bytes
+    R = args.replicas if args.replicas > 0 else max(32, -(-(3 << 30) // set_bytes))
+    R = max(1, min(R, w.n_chunks))
 
     layers = wl.make_layers(w, R, device=dev)
     chunk_layer = wl.make_chunk_layer(w, R, device=dev)

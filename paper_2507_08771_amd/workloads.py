@@ -56,6 +56,7 @@ class Workload:
     independent: bool = False   # tokens i.i.d. N(0, I) instead of centre + noise
     group: int = 0    # tokens sharing one centre (0: the whole chunk)
     seed: int = 0
+    p_active: float = 0.2   # probability that a router pre-activation is positive (1 - TLS)
 
     @property
     def n_tok(self) -> int:
@@ -95,6 +96,13 @@ WORKLOADS: Dict[str, Workload] = {
                                   gated=True, k=512, n_chunks=1, sigma=0.3, group=8),
     "paper_k32": Workload("paper_k32", d=2048, E=128, d_e=128, wdtype="bf16", gated=False,
                           k=32, n_chunks=512, sigma=0.3),
+    # The 2.8B shape at the sparsity levels of Table 11: 12.45 % of the experts active per
+    # token, and 30.86 % active in the union of a 32-token draft tree (sigma solves the closed
+    # form of expected_sparsity for that union ratio).
+    "paper_ar_k1": Workload("paper_ar_k1", d=2048, E=128, d_e=128, wdtype="bf16", gated=False,
+                            k=1, n_chunks=4096, sigma=0.0, independent=True, p_active=0.1245),
+    "paper_tree_k32": Workload("paper_tree_k32", d=2048, E=128, d_e=128, wdtype="bf16", gated=False,
+                               k=32, n_chunks=1024, sigma=0.3443161, p_active=0.1245),
 }
 
 
@@ -110,7 +118,7 @@ def _weight(shape, wdtype: str, gen: torch.Generator, device) -> torch.Tensor:
 
 
 def make_layers(w: Workload, n_layers: int = 1, device="cpu", seed: Optional[int] = None,
-                p_active: float = 0.2, bias: bool = True, gain: bool = False) -> Dict[str, torch.Tensor]:
+                p_active: Optional[float] = None, bias: bool = True, gain: bool = False) -> Dict[str, torch.Tensor]:
     """Weights of ``n_layers`` stacked layers.
 
     Returns tensors laid out as the library expects them: ``w_router [L][E][d]``,
@@ -119,6 +127,7 @@ def make_layers(w: Workload, n_layers: int = 1, device="cpu", seed: Optional[int
     ``gain``, then drawn from U(0.5, 1.5)).
     """
     seed = w.seed if seed is None else seed
+    p_active = w.p_active if p_active is None else p_active
     out: Dict[str, list] = {n: [] for n in ("w_router", "w_up", "w_gate", "w_down", "b_router", "g_rms")}
     z = -float(torch.distributions.Normal(0.0, 1.0).icdf(torch.tensor(p_active, dtype=torch.float64)))
     sig_eff = 0.0 if w.independent else w.sigma

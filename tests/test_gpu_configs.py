@@ -36,7 +36,7 @@ def full_size_case(name, n_layers, chunks, dense_sampled=True):
     np.testing.assert_array_equal(np.bitwise_or.reduce(tm, axis=1), gpu["union_mask"])
     assert gpu["stats"][1] == C * E - gpu["n_active"].sum()
     assert gpu["stats"][0] == w.n_tok * E - popcount_rows(gpu["token_mask"]).sum()
-    e_tls, e_cls = wl.expected_sparsity(w.k, w.sigma, independent=w.independent)
+    e_tls, e_cls = wl.expected_sparsity(w.k, w.sigma, w.p_active, independent=w.independent)
     assert abs(gpu["stats"][0] / (w.n_tok * E) - e_tls) < 0.01
     assert abs(gpu["stats"][1] / (C * E) - e_cls) < 0.02
     assert np.isfinite(gpu["y"]).all()
@@ -59,6 +59,16 @@ def test_tree_k32_full_size():
 def test_paper_shape_two_mask_words():
     """The paper's 2.8B shape: Eq. 2 experts, N_e = 128 (two mask words), d_e = 128, k = 32."""
     full_size_case("paper_k32", 2, [0, 1, 255, 511], dense_sampled=False)
+
+
+def test_paper_shape_table11_sparsity_levels():
+    """The 2.8B shape at Table 11's levels: 12.45 % of the experts active per token (k = 1) and
+    30.86 % active in the union of a 32-token tree (checked against the generator's closed form
+    inside full_size_case)."""
+    full_size_case("paper_ar_k1", 4, [0, 1, 63, 64, 2049, 4095] + list(range(700, 716)))
+    full_size_case("paper_tree_k32", 2, [0, 1, 511, 1023], dense_sampled=False)
+    w = wl.WORKLOADS["paper_tree_k32"]
+    assert abs((1 - wl.expected_sparsity(w.k, w.sigma, w.p_active)[1]) - 0.3086) < 1e-4
 
 
 def test_stack_decode_24_layers_chained():
