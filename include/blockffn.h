@@ -125,6 +125,30 @@ int blockffn_sparse_ffn_down(const blockffn_layer *layer, const int32_t *chunk_l
                              int64_t n_chunks, int32_t k, float *y, void *workspace,
                              size_t workspace_bytes, void *stream);
 
+/* Sec. 2.1, the curve of Fig. 1(a): CLS_L for every window length L = 1 .. l_max at once, from
+ * the token masks blockffn_router wrote.  The n_tok tokens are n_tok / seq_len sequences of
+ * seq_len tokens (n_tok must be a multiple of seq_len); no window crosses a sequence boundary.
+ * Row 0 of each output is for disjoint windows [j*L, (j+1)*L) (floor(seq_len / L) per sequence,
+ * a shorter tail is left out), row 1 for sliding windows (every start s with s + L <= seq_len).
+ *   inactive [2][l_max] int64   sum over the windows of (N_e - experts active in the window)
+ *   windows  [2][l_max] int64   number of windows
+ *   cls      [2][l_max] double  inactive / (windows * N_e); 0 where there is no window
+ * All three are overwritten.  CLS_1 is TLS; disjoint L = k gives the CLS_k of
+ * blockffn_chunk_union.  1 <= l_max <= 64 (larger: BLOCKFFN_ERR_UNSUPPORTED). */
+int blockffn_cls_sweep(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int32_t n_experts,
+                       int32_t l_max, int64_t *inactive, int64_t *windows, double *cls, void *stream);
+
+/* Sec. 4.1.2 (Table 4), expert selection stability: with S_i the experts token i activates,
+ * the mean of |S_i & S_{i+1}| / |S_i| over neighbouring tokens of the same sequence.  A pair
+ * whose S_i is empty has no ratio and is left out of the mean; all pairs of all sequences are
+ * pooled.  Outputs (overwritten), indexed by c = |S_i|:
+ *   num [N_e + 1] int64   sum of |S_i & S_{i+1}| over the pairs with |S_i| = c
+ *   cnt [N_e + 1] int64   number of such pairs (entry 0 stays 0)
+ *   ratio [1] double      (sum_c num[c] / c) / sum_c cnt[c], added in ascending c; 0 with no pair
+ * The integer outputs are exact; ratio is their fp64 evaluation. */
+int blockffn_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int32_t n_experts,
+                         int64_t *num, int64_t *cnt, double *ratio, void *stream);
+
 /* Bytes of workspace the two FFN entry points need for this shape (0 on invalid arguments). */
 size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k);
 

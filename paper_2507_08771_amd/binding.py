@@ -23,7 +23,7 @@ OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
            "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_workspace_bytes", "blockffn_strerror",
-           "blockffn_version")
+           "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -62,13 +62,16 @@ def lib() -> ctypes.CDLL:
         L.blockffn_dense_ffn.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
         L.blockffn_sparse_ffn_up.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
         L.blockffn_sparse_ffn_down.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
+        L.blockffn_cls_sweep.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
+        L.blockffn_reuse_ratio.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.blockffn_workspace_bytes.argtypes = [lp, i64, i32]
         L.blockffn_workspace_bytes.restype = sz
         L.blockffn_strerror.argtypes = [ctypes.c_int]
         L.blockffn_strerror.restype = ctypes.c_char_p
         L.blockffn_version.restype = ctypes.c_int
         for n in ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
-                  "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down"):
+                  "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_cls_sweep",
+                  "blockffn_reuse_ratio"):
             getattr(L, n).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -141,6 +144,18 @@ def blockffn_chunk_union(token_mask: torch.Tensor, n_chunks: int, k: int, n_expe
                          stream=None):
     _check(lib().blockffn_chunk_union(_p(token_mask), n_chunks, k, n_experts, _p(union_mask), _p(active_idx),
                                       _p(n_active), _p(stats), _stream(stream)), "blockffn_chunk_union")
+
+
+def blockffn_cls_sweep(token_mask: torch.Tensor, n_tok: int, seq_len: int, n_experts: int, l_max: int,
+                       inactive: torch.Tensor, windows: torch.Tensor, cls: torch.Tensor, stream=None):
+    _check(lib().blockffn_cls_sweep(_p(token_mask), n_tok, seq_len, n_experts, l_max, _p(inactive), _p(windows),
+                                    _p(cls), _stream(stream)), "blockffn_cls_sweep")
+
+
+def blockffn_reuse_ratio(token_mask: torch.Tensor, n_tok: int, seq_len: int, n_experts: int, num: torch.Tensor,
+                         cnt: torch.Tensor, ratio: torch.Tensor, stream=None):
+    _check(lib().blockffn_reuse_ratio(_p(token_mask), n_tok, seq_len, n_experts, _p(num), _p(cnt), _p(ratio),
+                                      _stream(stream)), "blockffn_reuse_ratio")
 
 
 def blockffn_sparse_ffn(layer: Layer, x, scores, token_mask, active_idx, n_active, n_chunks: int, k: int, y,

@@ -118,6 +118,17 @@ int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_lay
   return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
 }
 
+
+// a stream of n_tok token masks cut into sequences of seq_len tokens
+int check_stream_of_masks(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int32_t n_experts) {
+  if (n_experts < 1 || n_tok < 0 || seq_len < 1) return BLOCKFFN_ERR_INVALID;
+  if (n_tok % seq_len != 0) return BLOCKFFN_ERR_INVALID;
+  if (n_experts > kMaxExperts) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (token_mask == nullptr && n_tok > 0) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(token_mask, 8)) return BLOCKFFN_ERR_INVALID;
+  return BLOCKFFN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -151,6 +162,30 @@ int blockffn_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int32_t k
     return BLOCKFFN_ERR_INVALID;
   if (n_chunks == 0) return BLOCKFFN_OK;
   hipError_t err = launch_chunk_union(token_mask, n_chunks, k, n_experts, union_mask, active_idx, n_active, stats,
+                                      static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
+int blockffn_cls_sweep(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int32_t n_experts, int32_t l_max,
+                       int64_t *inactive, int64_t *windows, double *cls, void *stream) {
+  int rc = check_stream_of_masks(token_mask, n_tok, seq_len, n_experts);
+  if (rc != BLOCKFFN_OK) return rc;
+  if (l_max < 1) return BLOCKFFN_ERR_INVALID;
+  if (l_max > stats_max_window()) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (inactive == nullptr || windows == nullptr || cls == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(inactive, 8) || !aligned(windows, 8) || !aligned(cls, 8)) return BLOCKFFN_ERR_INVALID;
+  hipError_t err = launch_cls_sweep(token_mask, n_tok, seq_len, n_experts, l_max, inactive, windows, cls,
+                                    static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
+int blockffn_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int32_t n_experts, int64_t *num,
+                         int64_t *cnt, double *ratio, void *stream) {
+  int rc = check_stream_of_masks(token_mask, n_tok, seq_len, n_experts);
+  if (rc != BLOCKFFN_OK) return rc;
+  if (num == nullptr || cnt == nullptr || ratio == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(num, 8) || !aligned(cnt, 8) || !aligned(ratio, 8)) return BLOCKFFN_ERR_INVALID;
+  hipError_t err = launch_reuse_ratio(token_mask, n_tok, seq_len, n_experts, num, cnt, ratio,
                                       static_cast<hipStream_t>(stream));
   return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
 }

@@ -89,6 +89,15 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
 hipError_t launch_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int k, int E,
                               uint64_t *union_mask, int32_t *active_idx, int32_t *n_active,
                               int64_t *stats, hipStream_t s);
+
+// CLS_L for L = 1 .. L_max over disjoint (row 0) and sliding (row 1) windows that stay inside
+// sequences of seq_len tokens; inactive / windows / cls are [2][L_max].  L_max <= stats_max_window().
+int stats_max_window();
+hipError_t launch_cls_sweep(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int E, int L_max,
+                            int64_t *inactive, int64_t *windows, double *cls, hipStream_t s);
+// Reuse ratio of neighbouring tokens: num / cnt are [E + 1] (indexed by |S_i|), ratio is [1].
+hipError_t launch_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int E, int64_t *num,
+                              int64_t *cnt, double *ratio, hipStream_t s);
 // Shape-generic FFN kernels.  active_idx == nullptr selects the dense path (every expert, no
 // masking).  mid is fp32 [chunk][slot][token][neuron] with E slots per chunk.
 hipError_t launch_up_generic(const LayerView &L, int wdtype, bool gated, const int32_t *chunk_layer, const float *x,

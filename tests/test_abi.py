@@ -105,6 +105,28 @@ def test_union_and_ffn_argument_checks():
     assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 0, 8, FAKE, None, 0, None) == B.OK
 
 
+def test_statistics_argument_checks():
+    lib = B.lib()
+    sweep = lambda mask=FAKE, n_tok=64, seq=16, E=64, l_max=8, a=FAKE, b=FAKE, c=FAKE: lib.blockffn_cls_sweep(
+        mask, n_tok, seq, E, l_max, a, b, c, None)
+    assert sweep(mask=None) == B.ERR_INVALID
+    assert sweep(n_tok=-1) == B.ERR_INVALID
+    assert sweep(seq=0) == B.ERR_INVALID
+    assert sweep(n_tok=65) == B.ERR_INVALID            # not a whole number of sequences
+    assert sweep(E=0) == B.ERR_INVALID
+    assert sweep(E=257) == B.ERR_UNSUPPORTED
+    assert sweep(l_max=0) == B.ERR_INVALID
+    assert sweep(l_max=65) == B.ERR_UNSUPPORTED
+    assert sweep(a=None) == B.ERR_INVALID and sweep(b=None) == B.ERR_INVALID and sweep(c=None) == B.ERR_INVALID
+    assert sweep(a=ctypes.c_void_p(0x10004)) == B.ERR_INVALID
+    reuse = lambda mask=FAKE, n_tok=64, seq=16, E=64, a=FAKE, b=FAKE, c=FAKE: lib.blockffn_reuse_ratio(
+        mask, n_tok, seq, E, a, b, c, None)
+    assert reuse(mask=None) == B.ERR_INVALID
+    assert reuse(n_tok=60) == B.ERR_INVALID
+    assert reuse(E=300) == B.ERR_UNSUPPORTED
+    assert reuse(a=None) == B.ERR_INVALID and reuse(b=None) == B.ERR_INVALID and reuse(c=None) == B.ERR_INVALID
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libblockffn.so"))

@@ -1,0 +1,133 @@
+"""GPU parity of the sparsity-statistics kernels (CLS_L sweep, reuse ratio) against the oracle:
+integer outputs bit-exact, the fp64 ratios to rounding."""
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_08771_amd import binding as B
+from paper_2507_08771_amd import workloads as wl
+from oracle import sparsity_stats as ss
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def random_masks(seed, n_tok, E, p, empty_every=0):
+    rng = np.random.default_rng(seed)
+    W = (E + 63) // 64
+    bits = rng.random((n_tok, W * 64)) < p
+    bits[:, E:] = False
+    if empty_every:
+        bits[::empty_every] = False
+    words = np.zeros((n_tok, W), dtype=np.uint64)
+    for w in range(W):
+        chunk = bits[:, w * 64:(w + 1) * 64]
+        words[:, w] = (chunk.astype(np.uint64) << np.arange(64, dtype=np.uint64)[None, :]).sum(axis=1, dtype=np.uint64)
+    return words
+
+
+def gpu_cls_sweep(mask_np, E, seq_len, l_max):
+    m = torch.from_numpy(mask_np.view(np.int64)).cuda()
+    inactive = torch.full((2, l_max), -7, dtype=torch.int64, device="cuda")   # must be overwritten
+    windows = torch.full((2, l_max), -7, dtype=torch.int64, device="cuda")
+    cls = torch.full((2, l_max), -7.0, dtype=torch.float64, device="cuda")
+    B.blockffn_cls_sweep(m, mask_np.shape[0], seq_len, E, l_max, inactive, windows, cls)
+    torch.cuda.synchronize()
+    return inactive.cpu().numpy(), windows.cpu().numpy(), cls.cpu().numpy()
+
+
+def gpu_reuse(mask_np, E, seq_len):
+    m = torch.from_numpy(mask_np.view(np.int64)).cuda()
+    num = torch.full((E + 1,), -7, dtype=torch.int64, device="cuda")
+    cnt = torch.full((E + 1,), -7, dtype=torch.int64, device="cuda")
+    ratio = torch.full((1,), -7.0, dtype=torch.float64, device="cuda")
+    B.blockffn_reuse_ratio(m, mask_np.shape[0], seq_len, E, num, cnt, ratio)
+    torch.cuda.synchronize()
+    return num.cpu().numpy(), cnt.cpu().numpy(), float(ratio.item())
+
+
+CASES = [
+    # E, seq_len, n_seq, l_max, p
+    (5, 7, 3, 9, 0.3),          # lengths beyond the sequence, one partial workgroup
+    (64, 16, 40, 16, 0.1),      # sequences shorter than a workgroup: boundaries inside it
+    (64, 1000, 2, 64, 0.05),    # windows reaching into the next workgroup's tokens, ragged tail
+    (70, 300, 3, 33, 0.08),     # two mask words
+    (130, 129, 5, 64, 0.03),    # three mask words, odd lengths
+    (256, 64, 9, 32, 0.02),     # the widest mask
+    (32, 1, 500, 4, 0.2),       # length-1 sequences: only L = 1 has windows, no pairs
+]
+
+
+@pytest.mark.parametrize("E,seq_len,n_seq,l_max,p", CASES)
+def test_cls_sweep_matches_oracle(E, seq_len, n_seq, l_max, p):
+    m = random_masks(E * 7 + seq_len, seq_len * n_seq, E, p, empty_every=5)
+    g_in, g_w, g_cls = gpu_cls_sweep(m, E, seq_len, l_max)
+    r_in, r_w, r_cls = ss.cls_sweep(m, E, seq_len, l_max)
+    np.testing.assert_array_equal(g_in, r_in)
+    np.testing.assert_array_equal(g_w, r_w)
+    np.testing.assert_allclose(g_cls, r_cls, rtol=1e-15, atol=0)
+
+
+@pytest.mark.parametrize("E,seq_len,n_seq,l_max,p", CASES)
+def test_reuse_ratio_matches_oracle(E, seq_len, n_seq, l_max, p):
+    m = random_masks(E * 11 + seq_len, seq_len * n_seq, E, max(p, 0.1), empty_every=7)
+    g_num, g_cnt, g_ratio = gpu_reuse(m, E, seq_len)
+    r_num, r_cnt, r_ratio = ss.reuse_ratio(m, E, seq_len)
+    np.testing.assert_array_equal(g_num, r_num)
+    np.testing.assert_array_equal(g_cnt, r_cnt)
+    assert g_ratio == pytest.approx(r_ratio, rel=1e-13, abs=0)
+
+
+def test_statistics_ignore_bits_at_or_above_E():
+    E = 10
+    m = random_masks(1, 64, 64, 0.5)          # garbage in bits 10..63
+    clean = m & np.uint64((1 << E) - 1)
+    np.testing.assert_array_equal(gpu_cls_sweep(m, E, 64, 8)[0], ss.cls_sweep(clean, E, 64, 8)[0])
+    np.testing.assert_array_equal(gpu_reuse(m, E, 64)[0], ss.reuse_ratio(clean, E, 64)[0])
+
+
+def test_empty_stream():
+    m = np.zeros((0, 1), dtype=np.uint64)
+    g_in, g_w, g_cls = gpu_cls_sweep(m, 64, 16, 8)
+    assert not g_in.any() and not g_w.any() and not g_cls.any()
+    num, cnt, ratio = gpu_reuse(m, 64, 16)
+    assert not num.any() and not cnt.any() and ratio == 0.0
+
+
+def test_statistics_of_the_router_masks_at_full_size():
+    """The benchmark's k = 8 workload: masks from the router kernel, the chunk's 8 tokens share a
+    centre.  The sweep on disjoint windows reproduces the counters of the union step at L = 1 and
+    L = 8, follows the generator's closed form for every L <= 8 (windows inside one chunk), and
+    matches the oracle on a prefix of the stream; neighbouring tokens of a chunk reuse far more
+    experts than the 20 % independent tokens would."""
+    w = wl.WORKLOADS["spec_k8"]
+    layers = wl.make_layers(w, 4, device="cuda")
+    cl = wl.make_chunk_layer(w, 4, device="cuda")
+    x = wl.make_tokens(w, layers, cl, device="cuda")
+    gpu = pu.run_gpu(layers, x, w.k, cl, dense=False)
+    m = gpu["token_mask"]
+    n_tok = m.shape[0]
+    # sequences = chunks: every window and pair stays among tokens sharing a centre
+    g_in, g_w, g_cls = gpu_cls_sweep(m, w.E, w.k, w.k)
+    assert g_in[0, 0] == g_in[1, 0] == gpu["stats"][0]
+    assert g_in[0, w.k - 1] == gpu["stats"][1] and g_w[0, w.k - 1] == w.n_chunks
+    for L in range(1, w.k + 1):
+        want = wl.expected_sparsity(L, w.sigma, w.p_active)[1]
+        assert abs(g_cls[1, L - 1] - want) < 0.01, (L, g_cls[1, L - 1], want)
+    num, cnt, ratio = gpu_reuse(m, w.E, w.k)
+    assert cnt.sum() + cnt[0] <= n_tok - w.n_chunks and 0.5 < ratio < 1.0
+    # the whole stream as one sequence, long windows: oracle on a prefix that ends on a workgroup edge
+    pre = 256 * 8
+    r = ss.cls_sweep(m[:pre], w.E, pre, 32)
+    g = gpu_cls_sweep(m[:pre].copy(), w.E, pre, 32)
+    np.testing.assert_array_equal(g[0], r[0])
+    np.testing.assert_array_equal(g[1], r[1])
+    full = gpu_cls_sweep(m, w.E, n_tok, 64)
+    assert np.all(np.diff(full[2][1]) <= 5e-4)    # sliding CLS_L falls with L (up to edge effects of the mean)
+    rr = ss.reuse_ratio(m[:pre], w.E, pre)
+    gg = gpu_reuse(m[:pre].copy(), w.E, pre)
+    np.testing.assert_array_equal(gg[0], rr[0])
+    np.testing.assert_array_equal(gg[1], rr[1])
+    assert gg[2] == pytest.approx(rr[2], rel=1e-13)
