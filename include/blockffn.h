@@ -125,6 +125,33 @@ int blockffn_sparse_ffn_down(const blockffn_layer *layer, const int32_t *chunk_l
                              int64_t n_chunks, int32_t k, float *y, void *workspace,
                              size_t workspace_bytes, void *stream);
 
+/* blockffn_router that also writes the pre-activations A^0 = W_router^T x (+ b) of Eq. 3 to
+ * preact [n_chunks*k][E] fp32 (NULL: not written).  scores and token_mask exactly as
+ * blockffn_router writes them; preact holds the values whose sign decided the mask bits. */
+int blockffn_router_preact(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                           int64_t n_chunks, int32_t k, float *scores, uint64_t *token_mask,
+                           float *preact, void *stream);
+
+/* Forward values of the CLS-aware training objectives (Sec. 3.2) on the pre-activations of a
+ * stream of n_tok tokens cut into sequences of seq_len tokens (n_tok a multiple of seq_len),
+ * evaluated in fp64:
+ *   losses[0] = L_al, Eq. 4: binary cross entropy with input sigmoid(alpha * A^0[t, i]) and
+ *     target sigmoid(alpha * A^0[t+1, i]) (the sequence shifted left by one token), averaged
+ *     over all (t, i) whose token has a successor in its sequence; the logarithms are the exact
+ *     log-sigmoids (no clamping).  0 when seq_len = 1.
+ *   losses[1] = L_cs, Eq. 5, for chunks of chunk_len consecutive tokens: p_ik = the L1
+ *     normalisation over experts of ReLU(A^0) for token k (all zero for a token with no active
+ *     expert), P^i_act = 1 - exp(sum_k ln(1 - p_ik)), averaged over experts and over the
+ *     disjoint chunks [j*chunk_len, (j+1)*chunk_len) of every sequence (a shorter tail is left
+ *     out).  0 when there is no chunk.
+ * alpha >= 0 finite.  workspace: blockffn_losses_workspace_bytes() bytes, 8-byte aligned,
+ * contents undefined on entry and on return.  The result does not depend on scheduling: partial
+ * sums are combined in a fixed order. */
+size_t blockffn_losses_workspace_bytes(void);
+int blockffn_router_losses(const float *preact, int64_t n_tok, int64_t seq_len, int32_t n_experts,
+                           int32_t chunk_len, float alpha, double *losses, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
 /* Sec. 2.1, the curve of Fig. 1(a): CLS_L for every window length L = 1 .. l_max at once, from
  * the token masks blockffn_router wrote.  The n_tok tokens are n_tok / seq_len sequences of
  * seq_len tokens (n_tok must be a multiple of seq_len); no window crosses a sequence boundary.

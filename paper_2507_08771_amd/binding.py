@@ -23,7 +23,8 @@ OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
            "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_workspace_bytes", "blockffn_strerror",
-           "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio")
+           "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio", "blockffn_router_preact",
+           "blockffn_router_losses", "blockffn_losses_workspace_bytes")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -62,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.blockffn_dense_ffn.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
         L.blockffn_sparse_ffn_up.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
         L.blockffn_sparse_ffn_down.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
+        L.blockffn_router_preact.argtypes = [lp, vp, vp, i64, i32, vp, vp, vp, vp]
+        L.blockffn_router_losses.argtypes = [vp, i64, i64, i32, i32, ctypes.c_float, vp, vp, sz, vp]
+        L.blockffn_losses_workspace_bytes.argtypes = []
+        L.blockffn_losses_workspace_bytes.restype = sz
         L.blockffn_cls_sweep.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.blockffn_reuse_ratio.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.blockffn_workspace_bytes.argtypes = [lp, i64, i32]
@@ -71,7 +76,7 @@ def lib() -> ctypes.CDLL:
         L.blockffn_version.restype = ctypes.c_int
         for n in ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
                   "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_cls_sweep",
-                  "blockffn_reuse_ratio"):
+                  "blockffn_reuse_ratio", "blockffn_router_preact", "blockffn_router_losses"):
             getattr(L, n).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -144,6 +149,23 @@ def blockffn_chunk_union(token_mask: torch.Tensor, n_chunks: int, k: int, n_expe
                          stream=None):
     _check(lib().blockffn_chunk_union(_p(token_mask), n_chunks, k, n_experts, _p(union_mask), _p(active_idx),
                                       _p(n_active), _p(stats), _stream(stream)), "blockffn_chunk_union")
+
+
+def blockffn_router_preact(layer: Layer, x, n_chunks: int, k: int, scores, token_mask, preact, chunk_layer=None,
+                           stream=None):
+    _check(lib().blockffn_router_preact(layer.ref(), _p(chunk_layer), _p(x), n_chunks, k, _p(scores), _p(token_mask),
+                                        _p(preact), _stream(stream)), "blockffn_router_preact")
+
+
+def blockffn_losses_workspace_bytes() -> int:
+    return int(lib().blockffn_losses_workspace_bytes())
+
+
+def blockffn_router_losses(preact: torch.Tensor, n_tok: int, seq_len: int, n_experts: int, chunk_len: int,
+                           alpha: float, losses: torch.Tensor, workspace: torch.Tensor, stream=None):
+    _check(lib().blockffn_router_losses(_p(preact), n_tok, seq_len, n_experts, chunk_len, alpha, _p(losses),
+                                        _p(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream(stream)), "blockffn_router_losses")
 
 
 def blockffn_cls_sweep(token_mask: torch.Tensor, n_tok: int, seq_len: int, n_experts: int, l_max: int,

@@ -133,18 +133,41 @@ int check_stream_of_masks(const uint64_t *token_mask, int64_t n_tok, int64_t seq
 
 extern "C" {
 
-int blockffn_router(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, int64_t n_chunks,
-                    int32_t k, float *scores, uint64_t *token_mask, void *stream) {
+int blockffn_router_preact(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, int64_t n_chunks,
+                           int32_t k, float *scores, uint64_t *token_mask, float *preact, void *stream) {
   LayerView v;
   int rc = check_layer(layer, v);
   if (rc != BLOCKFFN_OK) return rc;
   rc = check_chunks(n_chunks, k);
   if (rc != BLOCKFFN_OK) return rc;
   if (x == nullptr || scores == nullptr || token_mask == nullptr) return BLOCKFFN_ERR_INVALID;
-  if (!aligned(x, 16) || !aligned(scores, 4) || !aligned(token_mask, 8)) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(x, 16) || !aligned(scores, 4) || !aligned(token_mask, 8) || !aligned(preact, 4))
+    return BLOCKFFN_ERR_INVALID;
   if (n_chunks == 0) return BLOCKFFN_OK;
-  hipError_t err = launch_router(v, layer->wdtype, chunk_layer, x, n_chunks, k, scores, token_mask,
+  hipError_t err = launch_router(v, layer->wdtype, chunk_layer, x, n_chunks, k, scores, token_mask, preact,
                                  static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
+int blockffn_router(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, int64_t n_chunks,
+                    int32_t k, float *scores, uint64_t *token_mask, void *stream) {
+  return blockffn_router_preact(layer, chunk_layer, x, n_chunks, k, scores, token_mask, nullptr, stream);
+}
+
+size_t blockffn_losses_workspace_bytes(void) { return losses_workspace_bytes(); }
+
+int blockffn_router_losses(const float *preact, int64_t n_tok, int64_t seq_len, int32_t n_experts, int32_t chunk_len,
+                           float alpha, double *losses, void *workspace, size_t workspace_bytes, void *stream) {
+  if (n_experts < 1 || n_tok < 0 || seq_len < 1 || chunk_len < 1) return BLOCKFFN_ERR_INVALID;
+  if (n_tok % seq_len != 0) return BLOCKFFN_ERR_INVALID;
+  if (!(alpha >= 0.0f) || !(alpha <= 3.0e38f)) return BLOCKFFN_ERR_INVALID;   // NaN and inf fail too
+  if (n_experts > kMaxExperts) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (preact == nullptr && n_tok > 0) return BLOCKFFN_ERR_INVALID;
+  if (losses == nullptr || workspace == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (!aligned(preact, 4) || !aligned(losses, 8) || !aligned(workspace, 8)) return BLOCKFFN_ERR_INVALID;
+  if (workspace_bytes < losses_workspace_bytes()) return BLOCKFFN_ERR_WORKSPACE;
+  hipError_t err = launch_router_losses(preact, n_tok, seq_len, n_experts, chunk_len, alpha, losses, workspace,
+                                        static_cast<hipStream_t>(stream));
   return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
 }
 

@@ -85,7 +85,8 @@ __device__ __forceinline__ int clamp_layer(const int32_t *chunk_layer, int64_t c
 
 // Launchers implemented in the .hip files (host side).  Each returns a hipError_t.
 hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
-                         int64_t n_chunks, int k, float *scores, uint64_t *token_mask, hipStream_t s);
+                         int64_t n_chunks, int k, float *scores, uint64_t *token_mask, float *preact,
+                         hipStream_t s);   // preact: A^0 [n_tok][E] as well, or nullptr
 hipError_t launch_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int k, int E,
                               uint64_t *union_mask, int32_t *active_idx, int32_t *n_active,
                               int64_t *stats, hipStream_t s);
@@ -95,6 +96,11 @@ hipError_t launch_chunk_union(const uint64_t *token_mask, int64_t n_chunks, int 
 int stats_max_window();
 hipError_t launch_cls_sweep(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int E, int L_max,
                             int64_t *inactive, int64_t *windows, double *cls, hipStream_t s);
+// Eq. 4 / Eq. 5 forward values: losses[0] = L_al, losses[1] = L_cs for chunks of L tokens.
+// workspace: losses_workspace_bytes() bytes, 8-byte aligned.
+size_t losses_workspace_bytes();
+hipError_t launch_router_losses(const float *a0, int64_t n_tok, int64_t seq_len, int E, int L, float alpha,
+                                double *losses, void *workspace, hipStream_t s);
 // Reuse ratio of neighbouring tokens: num / cnt are [E + 1] (indexed by |S_i|), ratio is [1].
 hipError_t launch_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int E, int64_t *num,
                               int64_t *cnt, double *ratio, hipStream_t s);

@@ -49,7 +49,8 @@ template <typename WT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                           const float *__restrict__ x, int k, int tiles_per_chunk,
                                                           float *__restrict__ scores,
-                                                          uint64_t *__restrict__ token_mask) {
+                                                          uint64_t *__restrict__ token_mask,
+                                                          float *__restrict__ preact) {
   // part[wave][expert][token]
   __shared__ float part[4][kMaxExperts][kTok];
 
@@ -137,6 +138,7 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
           a0 = L.b_router ? L.b_router[(size_t)layer * E + i] : 0.0f;
           a0 += (part[0][i][t] + part[1][i][t]) + (part[2][i][t] + part[3][i][t]);
         }
+        if (preact && i < E) preact[tok * E + i] = a0;
         const bool active = (i < E) && (a0 > 0.0f);
         const uint64_t word = __ballot(active);
         if (lane == 0) token_mask[tok * L.W + wd] = word;
@@ -163,7 +165,8 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
 // and the RMSNorm'ed scores, in place.
 __global__ __launch_bounds__(kThreads) void router_finish_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                                  int64_t n_tok, int k, float *__restrict__ scores,
-                                                                 uint64_t *__restrict__ token_mask) {
+                                                                 uint64_t *__restrict__ token_mask,
+                                                                 float *__restrict__ preact) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t tok = (int64_t)blockIdx.x * 4 + wave;
   if (tok >= n_tok) return;
@@ -177,6 +180,7 @@ __global__ __launch_bounds__(kThreads) void router_finish_kernel(LayerView L, co
     if (wd < L.W) {
       const int i = wd * 64 + lane;
       const float a0 = i < E ? scores[tok * E + i] : 0.0f;
+      if (preact && i < E) preact[tok * E + i] = a0;
       const bool active = (i < E) && (a0 > 0.0f);
       const uint64_t word = __ballot(active);
       if (lane == 0) token_mask[tok * L.W + wd] = word;
@@ -201,7 +205,8 @@ __global__ __launch_bounds__(kThreads) void router_finish_kernel(LayerView L, co
 }  // namespace
 
 hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
-                         int64_t n_chunks, int k, float *scores, uint64_t *token_mask, hipStream_t s) {
+                         int64_t n_chunks, int k, float *scores, uint64_t *token_mask, float *preact,
+                         hipStream_t s) {
   const int tiles = (k + kTok - 1) / kTok;
   const int64_t blocks = n_chunks * tiles;
   if (blocks <= 0) return hipSuccess;
@@ -212,21 +217,25 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
     // few token tiles: spread the expert groups over workgroups, then normalise
     dim3 grid((unsigned)blocks, (unsigned)n_groups);
     if (wdtype == BLOCKFFN_BF16)
-      hipLaunchKernelGGL((router_kernel<bf16_t, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+      hipLaunchKernelGGL((router_kernel<bf16_t, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
+                         preact);
     else
-      hipLaunchKernelGGL((router_kernel<float, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+      hipLaunchKernelGGL((router_kernel<float, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
+                         preact);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int64_t n_tok = n_chunks * k;
     hipLaunchKernelGGL(router_finish_kernel, dim3((unsigned)((n_tok + 3) / 4)), block, 0, s, L, chunk_layer, n_tok, k,
-                       scores, token_mask);
+                       scores, token_mask, preact);
     return hipGetLastError();
   }
   dim3 grid((unsigned)blocks);
   if (wdtype == BLOCKFFN_BF16)
-    hipLaunchKernelGGL((router_kernel<bf16_t, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+    hipLaunchKernelGGL((router_kernel<bf16_t, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
+                         preact);
   else
-    hipLaunchKernelGGL((router_kernel<float, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask);
+    hipLaunchKernelGGL((router_kernel<float, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
+                         preact);
   return hipGetLastError();
 }
 

@@ -127,6 +127,29 @@ def test_statistics_argument_checks():
     assert reuse(a=None) == B.ERR_INVALID and reuse(b=None) == B.ERR_INVALID and reuse(c=None) == B.ERR_INVALID
 
 
+def test_losses_argument_checks():
+    lib = B.lib()
+    need = lib.blockffn_losses_workspace_bytes()
+    assert need > 0 and need % 8 == 0
+    f = lambda a0=FAKE, n_tok=64, seq=16, E=64, L=8, alpha=1.0, out=FAKE, ws=FAKE, nbytes=need: \
+        lib.blockffn_router_losses(a0, n_tok, seq, E, L, alpha, out, ws, nbytes, None)
+    assert f(a0=None) == B.ERR_INVALID
+    assert f(n_tok=65) == B.ERR_INVALID
+    assert f(seq=0) == B.ERR_INVALID
+    assert f(L=0) == B.ERR_INVALID
+    assert f(E=0) == B.ERR_INVALID
+    assert f(E=257) == B.ERR_UNSUPPORTED
+    assert f(alpha=-1.0) == B.ERR_INVALID
+    assert f(alpha=float("nan")) == B.ERR_INVALID
+    assert f(alpha=float("inf")) == B.ERR_INVALID
+    assert f(out=None) == B.ERR_INVALID and f(ws=None) == B.ERR_INVALID
+    assert f(nbytes=need - 1) == B.ERR_WORKSPACE
+    lay = layer()
+    assert lib.blockffn_router_preact(ctypes.byref(lay), None, FAKE, 1, 8, FAKE, FAKE, ctypes.c_void_p(0x10002),
+                                      None) == B.ERR_INVALID     # misaligned pre-activation buffer
+    assert lib.blockffn_router_preact(ctypes.byref(lay), None, FAKE, 0, 8, FAKE, FAKE, None, None) == B.OK
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libblockffn.so"))
