@@ -15,7 +15,7 @@
  * Conventions common to every entry point
  * ---------------------------------------
  * - Every pointer is a DEVICE pointer owned by the caller, except `layer` (host struct, read
- *   during the call only) and `stream`.  The library never allocates, frees or keeps them.
+ *   during the call only), `stream`, and the arguments of blockffn_offload_sim (host memory).  The library never allocates, frees or keeps them.
  * - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
  *   work on it: no synchronisation, no host read-back.  Outputs of one call are valid inputs
  *   of the next call on the same stream.
@@ -151,6 +151,22 @@ size_t blockffn_losses_workspace_bytes(void);
 int blockffn_router_losses(const float *preact, int64_t n_tok, int64_t seq_len, int32_t n_experts,
                            int32_t chunk_len, float alpha, double *losses, void *workspace,
                            size_t workspace_bytes, void *stream);
+
+/* Expert-cache simulation for offloading (Sec. 1 and Sec. 4.1.2 name the saving of expert IO as
+ * the second use of chunk-level sparsity and of a high reuse ratio; no mechanism is given, this
+ * is the textbook one).  HOST code on HOST pointers, nothing is launched: active_idx
+ * [n_chunks][N_e] and n_active [n_chunks] are one layer's union lists copied back from
+ * blockffn_chunk_union.  A cache of `capacity` experts with least-recently-used replacement,
+ * empty at the start, is driven by the lists: the experts of a chunk are touched in list order;
+ * touching a resident expert is a hit and makes it the most recently used; touching any other
+ * is a load, which first evicts the least recently used resident expert when the cache is full.
+ *   loads_per_chunk [n_chunks] int64, or NULL   loads caused by each chunk
+ *   totals [3] int64                            touches, loads, evictions
+ * Bytes moved = loads * bytes of one expert.  An entry of a list outside [0, N_e), or an
+ * n_active outside [0, N_e], returns BLOCKFFN_ERR_INVALID (outputs then undefined). */
+int blockffn_offload_sim(const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
+                         int32_t n_experts, int32_t capacity, int64_t *loads_per_chunk,
+                         int64_t *totals);
 
 /* Sec. 2.1, the curve of Fig. 1(a): CLS_L for every window length L = 1 .. l_max at once, from
  * the token masks blockffn_router wrote.  The n_tok tokens are n_tok / seq_len sequences of

@@ -24,7 +24,7 @@ OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
            "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_workspace_bytes", "blockffn_strerror",
            "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio", "blockffn_router_preact",
-           "blockffn_router_losses", "blockffn_losses_workspace_bytes")
+           "blockffn_router_losses", "blockffn_losses_workspace_bytes", "blockffn_offload_sim")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.blockffn_router_losses.argtypes = [vp, i64, i64, i32, i32, ctypes.c_float, vp, vp, sz, vp]
         L.blockffn_losses_workspace_bytes.argtypes = []
         L.blockffn_losses_workspace_bytes.restype = sz
+        L.blockffn_offload_sim.argtypes = [vp, vp, i64, i32, i32, vp, vp]
+        L.blockffn_offload_sim.restype = ctypes.c_int
         L.blockffn_cls_sweep.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.blockffn_reuse_ratio.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
         L.blockffn_workspace_bytes.argtypes = [lp, i64, i32]
@@ -166,6 +168,16 @@ def blockffn_router_losses(preact: torch.Tensor, n_tok: int, seq_len: int, n_exp
     _check(lib().blockffn_router_losses(_p(preact), n_tok, seq_len, n_experts, chunk_len, alpha, _p(losses),
                                         _p(workspace), workspace.numel() * workspace.element_size(),
                                         _stream(stream)), "blockffn_router_losses")
+
+
+def blockffn_offload_sim(active_idx: torch.Tensor, n_active: torch.Tensor, n_experts: int, capacity: int,
+                         loads_per_chunk: Optional[torch.Tensor], totals: torch.Tensor):
+    """HOST tensors (int32 lists, int64 outputs): the simulation runs on the CPU."""
+    for t in (active_idx, n_active, loads_per_chunk, totals):
+        if t is not None and (t.is_cuda or not t.is_contiguous()):
+            raise ValueError("blockffn_offload_sim takes contiguous host tensors")
+    _check(lib().blockffn_offload_sim(_p(active_idx), _p(n_active), n_active.numel(), n_experts, capacity,
+                                      _p(loads_per_chunk), _p(totals)), "blockffn_offload_sim")
 
 
 def blockffn_cls_sweep(token_mask: torch.Tensor, n_tok: int, seq_len: int, n_experts: int, l_max: int,

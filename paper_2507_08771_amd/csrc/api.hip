@@ -154,6 +154,15 @@ int blockffn_router(const blockffn_layer *layer, const int32_t *chunk_layer, con
   return blockffn_router_preact(layer, chunk_layer, x, n_chunks, k, scores, token_mask, nullptr, stream);
 }
 
+int blockffn_offload_sim(const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks, int32_t n_experts,
+                         int32_t capacity, int64_t *loads_per_chunk, int64_t *totals) {
+  if (n_experts < 1 || n_chunks < 0 || capacity < 0) return BLOCKFFN_ERR_INVALID;
+  if (n_experts > kMaxExperts) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (totals == nullptr) return BLOCKFFN_ERR_INVALID;
+  if (n_chunks > 0 && (active_idx == nullptr || n_active == nullptr)) return BLOCKFFN_ERR_INVALID;
+  return offload_sim(active_idx, n_active, n_chunks, n_experts, capacity, loads_per_chunk, totals);
+}
+
 size_t blockffn_losses_workspace_bytes(void) { return losses_workspace_bytes(); }
 
 int blockffn_router_losses(const float *preact, int64_t n_tok, int64_t seq_len, int32_t n_experts, int32_t chunk_len,

@@ -101,6 +101,9 @@ hipError_t launch_cls_sweep(const uint64_t *token_mask, int64_t n_tok, int64_t s
 size_t losses_workspace_bytes();
 hipError_t launch_router_losses(const float *a0, int64_t n_tok, int64_t seq_len, int E, int L, float alpha,
                                 double *losses, void *workspace, hipStream_t s);
+// LRU expert-cache simulation on HOST lists; returns a BLOCKFFN_* code.
+int offload_sim(const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks, int E, int capacity,
+                int64_t *loads_per_chunk, int64_t *totals);
 // Reuse ratio of neighbouring tokens: num / cnt are [E + 1] (indexed by |S_i|), ratio is [1].
 hipError_t launch_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int E, int64_t *num,
                               int64_t *cnt, double *ratio, hipStream_t s);
