@@ -51,12 +51,80 @@ def parse():
                         "with --workload stack_decode_k8 --chunks 24 --replicas 24 a step is a 24-layer decode step")
     p.add_argument("--dense-steps", type=int, default=3)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--extras", action="store_true",
+                   help="also time the sparsity statistics (CLS_L sweep, reuse ratio), the training-objective forward "
+                        "values and the expert-cache simulation on this workload's router outputs")
     p.add_argument("--cpu-sample-chunks", type=int, default=512)
     p.add_argument("--calibrate-copy", action="store_true",
                    help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
     p.add_argument("--traffic-bytes", type=float, default=None,
                    help="HBM bytes per launch of the dominant kernel from rocprofv3 counters, if known")
     return p.parse_args()
+
+
+def timed_us(fn, reps=5):
+    import torch
+
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e3
+
+
+def extras(w, L, x, buf, chunk_layer):
+    """Statistics and objectives on the router outputs of the timed workload.  The token stream is
+    read as sequences of k tokens (the chunks: tokens that share a centre), and the CLS_L sweep
+    also as one long sequence."""
+    import torch
+
+    from paper_2507_08771_amd import binding as B
+
+    dev = x.device
+    C, k, E, n_tok = w.n_chunks, w.k, w.E, w.n_tok
+    l_max = 32
+    inactive = torch.empty((2, l_max), dtype=torch.int64, device=dev)
+    windows = torch.empty_like(inactive)
+    cls = torch.empty((2, l_max), dtype=torch.float64, device=dev)
+    num = torch.empty((E + 1,), dtype=torch.int64, device=dev)
+    cnt = torch.empty_like(num)
+    ratio = torch.empty((1,), dtype=torch.float64, device=dev)
+    pre = torch.empty((n_tok, E), dtype=torch.float32, device=dev)
+    losses = torch.empty((2,), dtype=torch.float64, device=dev)
+    ws = torch.empty(B.blockffn_losses_workspace_bytes(), dtype=torch.uint8, device=dev)
+    out = {}
+    out["cls_sweep_us"] = timed_us(lambda: B.blockffn_cls_sweep(buf.token_mask, n_tok, n_tok, E, l_max, inactive,
+                                                                windows, cls))
+    out["cls_sliding_one_stream"] = {str(Lw): float(cls[1, Lw - 1]) for Lw in (1, 2, 4, 8, 16, 32)}
+    B.blockffn_cls_sweep(buf.token_mask, n_tok, k, E, min(k, l_max), inactive, windows, cls)
+    torch.cuda.synchronize()
+    out["cls_disjoint_within_chunks"] = {str(Lw): float(cls[0, Lw - 1]) for Lw in (1, 2, 4, 8, 16, 32) if Lw <= k}
+    out["reuse_ratio_us"] = timed_us(lambda: B.blockffn_reuse_ratio(buf.token_mask, n_tok, k, E, num, cnt, ratio))
+    out["reuse_ratio_within_chunks"] = float(ratio.item())
+    out["router_preact_us"] = timed_us(lambda: B.blockffn_router_preact(L, x, C, k, buf.scores, buf.token_mask, pre,
+                                                                        chunk_layer))
+    alpha = 16.0
+    out["losses_us"] = timed_us(lambda: B.blockffn_router_losses(pre, n_tok, k, E, k, alpha, losses, ws))
+    out["L_al(alpha=%g)" % alpha], out["L_cs(L=%d)" % k] = float(losses[0]), float(losses[1])
+    # offloading: the chunks that read weight set 0, in order, are one layer's stream of unions
+    sel = (chunk_layer == 0).nonzero().flatten() if chunk_layer is not None else torch.arange(C, device=dev)
+    idx = buf.active_idx[sel].cpu().contiguous()
+    n_act = buf.n_active[sel].cpu().contiguous()
+    totals = torch.zeros(3, dtype=torch.int64)
+    sim = {}
+    for cap in (E // 4, E // 2, (3 * E) // 4, E):
+        t0 = time.perf_counter()
+        B.blockffn_offload_sim(idx, n_act, E, cap, None, totals)
+        sim[str(cap)] = {"loads_per_chunk": float(totals[1]) / max(1, n_act.numel()),
+                         "MB_per_chunk": float(totals[1]) * w.expert_bytes / max(1, n_act.numel()) / 1e6,
+                         "hit_rate": 1.0 - float(totals[1]) / max(1, int(totals[0])),
+                         "host_us": (time.perf_counter() - t0) * 1e6}
+    out["offload_lru_by_capacity"] = sim
+    return out
 
 
 def cpu_baseline(w, layers, x, chunk_layer, n_sample, expert_bytes):
@@ -233,6 +301,8 @@ def main():
                      "algorithmic_bytes": up_bytes,
                      "avg_launch_us": stage_us["up"]},
     }
+    if args.extras:
+        out["extras"] = extras(w, L, x, buf, chunk_layer)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, layers, x, chunk_layer, min(args.cpu_sample_chunks, C), w.expert_bytes)
     print(json.dumps(out))
