@@ -93,13 +93,50 @@ __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restric
   if (tid == 0) *total = carry;
 }
 
+// ------------------------------------------------------------------------------------------------ x split
+
+// x of every chunk split into bf16 hi/lo, stored in the B-operand order the up kernel reads from
+// LDS: xS [chunk][K-step = d / 32][NB][64 lanes] of 8 bf16, lane = gg * 16 + n holding the 8
+// contraction elements 8 * gg .. 8 * gg + 7 of the K-step for column n of the fragment.
+// NB = 1: columns 0-7 are the hi parts of tokens 0-7, columns 8-15 their lo parts.
+// NB = 2, 4: fragment 2 * grp is the hi part of tokens 16 * grp .. 16 * grp + 15, fragment
+// 2 * grp + 1 their lo part.  Tokens at or above k are zero.  One thread per 16-byte entry.
+template <int NB>
+__global__ __launch_bounds__(kThreads) void split_x_kernel(const float *__restrict__ x, int64_t n_chunks, int k, int d,
+                                                           uint4 *__restrict__ xS) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t per_chunk = (int64_t)(d / 32) * NB * 64;
+  if (idx >= n_chunks * per_chunk) return;
+  const int64_t c = idx / per_chunk;
+  const int rem = (int)(idx - c * per_chunk);
+  const int kstep = rem / (NB * 64), bf = (rem >> 6) % NB, lane = rem & 63;
+  const int gg = lane >> 4, n = lane & 15;
+  const int tok = NB == 1 ? (n & 7) : (bf >> 1) * 16 + n;
+  const bool want_lo = NB == 1 ? n >= 8 : (bf & 1);
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (tok < k) {
+    const float4 *p = reinterpret_cast<const float4 *>(x + (c * k + tok) * d + kstep * 32 + gg * 8);
+    const float4 a = p[0], b = p[1];
+    const float xv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    uint32_t h[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      uint32_t hi, lo;
+      split_bf16(xv[q], hi, lo);
+      h[q] = want_lo ? lo : hi;
+    }
+    v = make_uint4(h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16);
+  }
+  xS[idx] = v;
+}
+
 // ------------------------------------------------------------------------------------------------ up
 
 // NB: B fragments per K-step (see the top of the file); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
 // groups of the expert (d_e = 64 * RT).  Wave w owns row tiles rr*4 + w.
 template <int NB, int NM, int RT>
 __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
-    LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
+    LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
     int group, int k, uint16_t *__restrict__ midB) {
@@ -143,6 +180,12 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   int layer = clamp_layer(chunk_layer, c, L.n_layers);
   int64_t c_loaded = -1;   // chunk and K-chunk whose split x is in LDS
   int kc_loaded = -1;
+  // The first PF entries per lane of the NEXT LDS fill are loaded during the last block of the
+  // current K-chunk, ahead of that block's weight prefetches: loads return in issue order, so a
+  // fill issued after them would wait for a full HBM round trip with the matrix cores idle.
+  constexpr int PF = RT * NM * NA >= 16 ? 4 : (RT * NM * NA >= 8 ? 8 : 16);
+  uint4 pf[PF];
+  bool pf_valid = false;
   {
     const char *p = tile_ptr(layer, e, 0, 0);
 #pragma unroll
@@ -178,38 +221,36 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       const int nkb = kc_len / 512;
       const bool refill = c != c_loaded || kc0 != kc_loaded;   // uniform over the workgroup
       if (refill) __syncthreads();   // every wave is done with the previous contents of xB
-      // split x[c*k + tok][kc0 .. kc0 + kc_len) into hi/lo bf16 in B-operand order
-      for (int it = tid; refill && it < (kc_len / 8) * TOK; it += kThreads) {
-        const int tok = it % TOK, cg = it / TOK;   // cg: group of 8 columns
-        const int kstep = cg >> 2, gg = cg & 3;
-        uint32_t hi[8], lo[8];
-        if (tok < k) {
-          const float4 *p = reinterpret_cast<const float4 *>(x + (c * k + tok) * d + kc0 + cg * 8);
-          const float4 a = p[0], b = p[1];
-          const float xv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      // copy the K-chunk's slice of the chunk's split x into LDS, 8 loads in flight per lane
+      if (refill) {
+        const int n16 = (kc_len / 32) * NB * 64;
+        const uint4 *src = xS + ((size_t)c * (d / 32) + kc0 / 32) * NB * 64;
+        for (int base = 0; base < n16; base += PF * kThreads) {
+          if (base > 0 || !pf_valid) {   // the first batch may have been loaded ahead
 #pragma unroll
-          for (int q = 0; q < 8; ++q) split_bf16(xv[q], hi[q], lo[q]);
-        } else {
+            for (int j = 0; j < PF; ++j) {
+              const int idx = base + j * kThreads + tid;
+              pf[j] = idx < n16 ? src[idx] : make_uint4(0, 0, 0, 0);
+            }
+          }
 #pragma unroll
-          for (int q = 0; q < 8; ++q) hi[q] = lo[q] = 0;
-        }
-        const uint4 vhi = make_uint4(hi[0] | hi[1] << 16, hi[2] | hi[3] << 16, hi[4] | hi[5] << 16, hi[6] | hi[7] << 16);
-        const uint4 vlo = make_uint4(lo[0] | lo[1] << 16, lo[2] | lo[3] << 16, lo[4] | lo[5] << 16, lo[6] | lo[7] << 16);
-        if (NB == 1) {
-          uint4 *dst = xB + (size_t)kstep * 64 + gg * 16 + tok;
-          dst[0] = vhi;
-          dst[8] = vlo;
-        } else {
-          const int grp = tok >> 4, n = tok & 15;
-          uint4 *dst = xB + (size_t)(kstep * NB + grp * 2) * 64 + gg * 16 + n;
-          dst[0] = vhi;
-          dst[64] = vlo;
+          for (int j = 0; j < PF; ++j) {
+            const int idx = base + j * kThreads + tid;
+            if (idx < n16) xB[idx] = pf[j];
+          }
         }
       }
       if (refill) __syncthreads();
       c_loaded = c;
       kc_loaded = kc0;
+      pf_valid = false;
       const bool last_kc = kc0 + KC >= d;
+      // the LDS fill that follows this K-chunk: the slot's next K-chunk, else the next slot's first
+      const int64_t c_f = last_kc ? c_n : c;
+      const int k_f = last_kc ? 0 : kc0 + KC;
+      const bool need_f = last_kc ? (has_next && (c_n != c || kc0 != 0)) : true;
+      const int n16_f = (min(KC, d - k_f) / 32) * NB * 64;
+      const uint4 *src_f = xS + ((size_t)c_f * (d / 32) + k_f / 32) * NB * 64;
 #pragma unroll
       for (int rr = 0; rr < RT; ++rr) {
 #pragma unroll
@@ -229,6 +270,14 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
             const bool tail = kb + 1 == nkb;
             const char *nxt = tail ? nxt_tile : cur + (size_t)(kb + 1) * 1024;
             const bool ok = tail ? nxt_ok : true;
+            if (rr == RT - 1 && m == NM - 1 && tail && need_f) {
+#pragma unroll
+              for (int j = 0; j < PF; ++j) {
+                const int idx = j * kThreads + tid;
+                pf[j] = idx < n16_f ? src_f[idx] : make_uint4(0, 0, 0, 0);
+              }
+              pf_valid = true;
+            }
 #pragma unroll
             for (int i = 0; i < kRing; ++i) {
 #pragma unroll
@@ -534,7 +583,7 @@ int num_cus() {
 }
 
 template <int NB, int NM, int RT>
-hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float *x, const float *scores,
+hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                      const int32_t *items, const int32_t *total, int group, int64_t max_items, int k, uint16_t *midB,
                      hipStream_t s) {
@@ -547,7 +596,7 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const float
     attr_set = true;
   }
   const int64_t grid = std::min<int64_t>(max_items, (int64_t)num_cus() * 2);
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, x, scores, token_mask,
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
                      active_idx, n_active, items, total, group, k, midB);
   return hipGetLastError();
 }
@@ -608,8 +657,13 @@ int b_frags(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
 struct StreamWs {
   uint16_t *midB;
   int32_t *items, *total;
+  uint4 *xS;     // the chunks' x split into bf16 hi/lo in B-operand order
   float *part;   // partial sums of the split down projection (few chunks only)
 };
+
+size_t xs_bytes(const LayerView &L, int64_t n_chunks, int k) {
+  return (size_t)n_chunks * (L.d / 32) * b_frags(k) * 64 * sizeof(uint4);   // a multiple of 1024
+}
 
 size_t mid_bytes(const LayerView &L, int64_t n_chunks, int k) {
   return ((size_t)n_chunks * L.E * b_frags(k) * 16 * L.d_e * 2 + 255) & ~(size_t)255;
@@ -625,7 +679,8 @@ StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
   w.midB = reinterpret_cast<uint16_t *>(p);
   w.total = reinterpret_cast<int32_t *>(p + mid_bytes(L, n_chunks, k));
   w.items = w.total + 64;
-  w.part = reinterpret_cast<float *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks));
+  w.xS = reinterpret_cast<uint4 *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks));
+  w.part = reinterpret_cast<float *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks) + xs_bytes(L, n_chunks, k));
   return w;
 }
 
@@ -644,7 +699,7 @@ bool stream_supported(const LayerView &L, int wdtype, int k) {
 
 size_t stream_workspace_bytes(const LayerView &L, int64_t n_chunks, int k) {
   // mid as bf16 hi/lo fragments [chunk][slot][NB][16][d_e], then the item count and the item list
-  size_t b = mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks);
+  size_t b = mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks) + xs_bytes(L, n_chunks, k);
   const int splits = down_splits(L, n_chunks);
   if (splits > 1) b += ((size_t)splits * n_chunks * k * L.d * sizeof(float) + 255) & ~(size_t)255;
   return b;
@@ -674,9 +729,22 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   const int group = (L.d <= 2048 / NB) ? 2 : 1;
   hipError_t err = launch_worklist(n_active, n_chunks, L.E, group, w.items, w.total, s);
   if (err != hipSuccess) return err;
+  {
+    const int64_t entries = n_chunks * (int64_t)(L.d / 32) * NB * 64;
+    const int64_t blocks = (entries + kThreads - 1) / kThreads;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (NB == 1)
+      hipLaunchKernelGGL(split_x_kernel<1>, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, n_chunks, k, L.d, w.xS);
+    else if (NB == 2)
+      hipLaunchKernelGGL(split_x_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, n_chunks, k, L.d, w.xS);
+    else
+      hipLaunchKernelGGL(split_x_kernel<4>, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, n_chunks, k, L.d, w.xS);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
 #define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
   if (NB == nb && (gated ? 2 : 1) == nm && RT == rt)                                                      \
-    return launch_up<nb, nm, rt>(L, chunk_layer, x, scores, token_mask, active_idx, n_active, w.items, w.total, \
+    return launch_up<nb, nm, rt>(L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, \
                                  group, max_items, k, w.midB, s);
   BLOCKFFN_CASE(1, 1, 1) BLOCKFFN_CASE(1, 1, 2) BLOCKFFN_CASE(1, 1, 4)
   BLOCKFFN_CASE(1, 2, 1) BLOCKFFN_CASE(1, 2, 2) BLOCKFFN_CASE(1, 2, 4)
