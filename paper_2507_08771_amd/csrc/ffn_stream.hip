@@ -380,26 +380,34 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
 #pragma unroll
     for (int i = 0; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row + i * 32);
   }
-  // keep every weight load of this wave in flight before anything waits on x
+  // x of this wave's quarter of the contraction.  Fragment column n carries token n & 7, its hi
+  // part for n < 8 and its lo part for n >= 8, so lanes n and n + 8 need the same 8 floats: each
+  // loads one half (4 floats), splits it, and the two exchange what the other needs.
+  const int tok = n & 7, half = n >> 3;
+  const float *xrow = x + (c * k + min(tok, k - 1)) * d + kq0 + g * 8 + half * 4;
+  float4 xv[FW];
+#pragma unroll
+  for (int i = 0; i < FW; ++i) xv[i] = *reinterpret_cast<const float4 *>(xrow + i * 32);
+  // every load of this wave is in flight before anything waits
   __builtin_amdgcn_sched_barrier(0);
   f32x4 acc[NM];
 #pragma unroll
   for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int tok = n & 7;
-  const float *xrow = x + (c * k + min(tok, k - 1)) * d + kq0 + g * 8;
 #pragma unroll
   for (int i = 0; i < FW; ++i) {
-    const float4 *p = reinterpret_cast<const float4 *>(xrow + i * 32);
-    const float4 v0 = p[0], v1 = p[1];
-    const float xv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-    uint32_t h[8];
+    const float v[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+    uint32_t hi[4], lo[4];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      uint32_t hi, lo;
-      split_bf16(xv[q], hi, lo);
-      h[q] = (tok < k) ? (n < 8 ? hi : lo) : 0u;
+    for (int q = 0; q < 4; ++q) {
+      split_bf16(v[q], hi[q], lo[q]);
+      if (tok >= k) hi[q] = lo[q] = 0u;
     }
-    const uint4 b = make_uint4(h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16);
+    const uint32_t hw0 = hi[0] | hi[1] << 16, hw1 = hi[2] | hi[3] << 16;
+    const uint32_t lw0 = lo[0] | lo[1] << 16, lw1 = lo[2] | lo[3] << 16;
+    // lane n < 8 keeps its hi words and sends its lo words; lane n + 8 does the opposite
+    const uint32_t r0 = __shfl_xor(half ? hw0 : lw0, 8, kWave);
+    const uint32_t r1 = __shfl_xor(half ? hw1 : lw1, 8, kWave);
+    const uint4 b = half ? make_uint4(r0, r1, lw0, lw1) : make_uint4(hw0, hw1, r0, r1);
 #pragma unroll
     for (int m = 0; m < NM; ++m) acc[m] = mfma16(a[m][i], b, acc[m]);
   }
