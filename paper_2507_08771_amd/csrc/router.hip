@@ -1,12 +1,18 @@
 // Router of the BlockFFN layer (Eq. 3): A^0 = W_router^T x + b, A^1 = ReLU(A^0),
 // A = RMSNorm(A^1), plus the per-token activation mask (bit set iff A^0 > 0).
 //
-// One workgroup (4 waves) takes a tile of up to 8 consecutive tokens of one chunk.  Each lane
-// keeps its 8 columns of the 8 tokens in registers (64 VGPRs) and walks over all experts: one
-// 128-bit load of a W_router row segment feeds 64 fp32 FMAs.  Partial sums of 8 experts x 8
-// tokens are reduced across the wave with a 63-step reduce-scatter (lane q ends with entry q),
-// the four waves' column quarters are combined in LDS.  Everything is fp32 on the vector ALUs:
-// the sign of A^0 decides a mask bit, so no reduced-precision product is used here.
+// One workgroup (4 waves) takes a tile of up to 8 consecutive tokens of one chunk.  The sign of
+// A^0 decides a mask bit, so every product is an exact fp32 product and every sum is fp32.
+//
+// router_mfma_kernel (bf16 weights, enough token tiles to fill the chip): x is carried as three
+// bf16 pieces that add up to the fp32 value exactly, and the matrix cores do the contraction.
+// router_kernel (fp32 weights, and launches of a few tiles, where blockIdx.y spreads the expert
+// groups over workgroups): vector ALUs.  Each lane keeps its 8 columns of the 8 tokens in
+// registers (64 VGPRs) and walks over the experts: one 128-bit load of a W_router row segment
+// feeds 64 fp32 FMAs; partial sums of 8 experts x 8 tokens are reduced across the wave with a
+// 63-step reduce-scatter (lane q ends with entry q).
+// Both leave the four waves' partial sums in LDS for the same finishing step (bias, mask ballot,
+// RMSNorm, gain).
 #include "common.hpp"
 
 namespace blockffn {
@@ -41,10 +47,56 @@ __device__ __forceinline__ float reduce_scatter64(float (&v)[64], int lane) {
   return v[0];
 }
 
+// The four waves' partial sums part[wave][expert][token] of a tile of nt tokens starting at
+// token tok0 become A^0 (+ bias), the mask words and the RMSNorm'ed scores.  Each wave finishes
+// tokens wave, wave + 4: lanes run over experts, one mask word at a time.
+template <int ROWS>
+__device__ __forceinline__ void finish_tile(const LayerView &L, int layer, const float (&part)[4][ROWS][kTok],
+                                            int64_t tok0, int nt, float *__restrict__ scores,
+                                            uint64_t *__restrict__ token_mask, float *__restrict__ preact) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int E = L.E;
+  for (int t = wave; t < nt; t += 4) {
+    const int64_t tok = tok0 + t;
+    float a1[kMaxMaskWords];
+    float sumsq = 0.0f;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      a1[wd] = 0.0f;
+      if (wd < L.W) {
+        const int i = wd * 64 + lane;
+        float a0 = 0.0f;
+        if (i < E) {
+          a0 = L.b_router ? L.b_router[(size_t)layer * E + i] : 0.0f;
+          a0 += (part[0][i][t] + part[1][i][t]) + (part[2][i][t] + part[3][i][t]);
+        }
+        if (preact && i < E) preact[tok * E + i] = a0;
+        const bool active = (i < E) && (a0 > 0.0f);
+        const uint64_t word = __ballot(active);
+        if (lane == 0) token_mask[tok * L.W + wd] = word;
+        a1[wd] = active ? a0 : 0.0f;
+        sumsq = fmaf(a1[wd], a1[wd], sumsq);
+      }
+    }
+    const float ms = wave_sum(sumsq) / (float)E;
+    const float rms = sqrtf(ms + L.eps);
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      if (wd < L.W) {
+        const int i = wd * 64 + lane;
+        if (i < E) {
+          const float g = L.g_rms ? L.g_rms[(size_t)layer * E + i] : 1.0f;
+          scores[tok * E + i] = a1[wd] > 0.0f ? g * a1[wd] / rms : 0.0f;
+        }
+      }
+    }
+  }
+}
+
 // SPLIT = false: one workgroup runs all experts of its token tile and finishes the tokens.
 // SPLIT = true (few tokens in the launch): blockIdx.y selects one group of 8 experts; the
 // workgroup writes that group's pre-activations A^0 into `scores` and router_finish_kernel
-// normalises in place.  Both give the same bits: the summation order of A^0 is the same.
+// normalises in place.
 template <typename WT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                           const float *__restrict__ x, int k, int tiles_per_chunk,
@@ -123,42 +175,105 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
     return;
   }
 
-  // Each wave finishes tokens wave, wave+4: lanes run over experts, one mask word at a time.
-  for (int t = wave; t < nt; t += 4) {
-    const int64_t tok = tok0 + t;
-    float a1[kMaxMaskWords];
-    float sumsq = 0.0f;
+  finish_tile(L, layer, part, tok0, nt, scores, token_mask, preact);
+}
+
+// bf16 weights, many token tiles: the same contraction on the matrix cores without giving up
+// fp32 products.  An fp32 x is the exact sum of three bf16 numbers (24 significant bits in
+// three pieces of 8: h = bf16(x), m = bf16(x - h), l = x - h - m), and a bf16 piece times a bf16
+// weight is exact in fp32, so three MFMA columns per token accumulate in fp32 exactly the
+// products the vector ALUs would: only the order of the fp32 additions differs.  The sign of A^0
+// still decides the mask bit, and it is still backed by full fp32 products.
+//
+// One workgroup = one tile of up to 8 tokens of one chunk; its four waves take the K-steps
+// (32 contraction elements) w, w + 4, ... .  Per K-step a wave loads RT fragments of W_router
+// (16 experts x 32 elements each), builds two B fragments from x in registers (columns 0-7: h of
+// tokens 0-7, 8-15: m, 16-23: l, 24-31: zero) and issues 2 * RT MFMAs.  KB K-steps are loaded
+// together so that their memory latency is paid once.  At the end h + m + l columns are added
+// inside the wave and the four waves meet in the LDS layout the finishing step reads.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t bf16_bits_of(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
+
+template <int RT, int KB>
+__global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
+                                                               const float *__restrict__ x, int k,
+                                                               int tiles_per_chunk, float *__restrict__ scores,
+                                                               uint64_t *__restrict__ token_mask,
+                                                               float *__restrict__ preact) {
+  __shared__ float part[4][RT * 16][kTok];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, g = lane >> 4;
+  const int64_t c = blockIdx.x / tiles_per_chunk;
+  const int t0 = (int)(blockIdx.x % tiles_per_chunk) * kTok;
+  const int nt = min(kTok, k - t0);
+  const int64_t tok0 = c * (int64_t)k + t0;
+  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  const int d = L.d, E = L.E;
+  const uint16_t *wr = static_cast<const uint16_t *>(L.w_router) + (size_t)layer * E * d;
+  const int tok = n & 7;
+  const bool tok_ok = tok < nt;
+  const float *xrow = x + (tok0 + (tok_ok ? tok : 0)) * d;
+  const int n_ksteps = (d + 31) / 32;
+
+  f32x4_t acc[RT][2];
 #pragma unroll
-    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
-      a1[wd] = 0.0f;
-      if (wd < L.W) {
-        const int i = wd * 64 + lane;
-        float a0 = 0.0f;
-        if (i < E) {
-          a0 = L.b_router ? L.b_router[(size_t)layer * E + i] : 0.0f;
-          a0 += (part[0][i][t] + part[1][i][t]) + (part[2][i][t] + part[3][i][t]);
-        }
-        if (preact && i < E) preact[tok * E + i] = a0;
-        const bool active = (i < E) && (a0 > 0.0f);
-        const uint64_t word = __ballot(active);
-        if (lane == 0) token_mask[tok * L.W + wd] = word;
-        a1[wd] = active ? a0 : 0.0f;
-        sumsq = fmaf(a1[wd], a1[wd], sumsq);
+  for (int rt = 0; rt < RT; ++rt) acc[rt][0] = acc[rt][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  for (int ks0 = wave; ks0 < n_ksteps; ks0 += 4 * KB) {
+    uint4 a[KB][RT];
+    float4 xa[KB], xb[KB];
+#pragma unroll
+    for (int u = 0; u < KB; ++u) {
+      const int col = (ks0 + 4 * u) * 32 + g * 8;   // d is a multiple of 8: a lane's 8 elements are all in or all out
+      const bool ok = col < d;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        const int row = min(rt * 16 + n, E - 1);   // rows at or above E repeat the last one; never read back
+        a[u][rt] = ok ? *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + col) : make_uint4(0, 0, 0, 0);
       }
+      const float4 *px = reinterpret_cast<const float4 *>(xrow + col);
+      xa[u] = ok ? px[0] : make_float4(0.f, 0.f, 0.f, 0.f);
+      xb[u] = ok ? px[1] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    const float ms = wave_sum(sumsq) / (float)E;
-    const float rms = sqrtf(ms + L.eps);
 #pragma unroll
-    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
-      if (wd < L.W) {
-        const int i = wd * 64 + lane;
-        if (i < E) {
-          const float g = L.g_rms ? L.g_rms[(size_t)layer * E + i] : 1.0f;
-          scores[tok * E + i] = a1[wd] > 0.0f ? g * a1[wd] / rms : 0.0f;
-        }
+    for (int u = 0; u < KB; ++u) {
+      const float xv[8] = {xa[u].x, xa[u].y, xa[u].z, xa[u].w, xb[u].x, xb[u].y, xb[u].z, xb[u].w};
+      uint32_t p0[8], p1[8];   // this lane's piece for the first and for the second B fragment
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t h = bf16_bits_of(xv[q]);
+        const float r1 = xv[q] - __uint_as_float(h << 16);
+        const uint32_t m = bf16_bits_of(r1);
+        const float r2 = r1 - __uint_as_float(m << 16);
+        const uint32_t l = bf16_bits_of(r2);
+        p0[q] = tok_ok ? (n < 8 ? h : m) : 0u;
+        p1[q] = (tok_ok && n < 8) ? l : 0u;
+      }
+      const uint4 b0 = make_uint4(p0[0] | p0[1] << 16, p0[2] | p0[3] << 16, p0[4] | p0[5] << 16, p0[6] | p0[7] << 16);
+      const uint4 b1 = make_uint4(p1[0] | p1[1] << 16, p1[2] | p1[3] << 16, p1[4] | p1[5] << 16, p1[6] | p1[7] << 16);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        acc[rt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u][rt]),
+                                                             __builtin_bit_cast(bf16x8_t, b0), acc[rt][0], 0, 0, 0);
+        acc[rt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u][rt]),
+                                                             __builtin_bit_cast(bf16x8_t, b1), acc[rt][1], 0, 0, 0);
       }
     }
   }
+  // accumulator element q of lane (n, g) is expert rt * 16 + 4 * g + q, column n: token n & 7,
+  // piece h (n < 8) or m (n >= 8) in the first fragment, l (n < 8) in the second
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float hm = acc[rt][0][q] + __shfl_xor(acc[rt][0][q], 8, kWave);
+      const int i = rt * 16 + 4 * g + q;
+      if (n < 8) part[wave][i][n] = hm + acc[rt][1][q];
+    }
+  __syncthreads();
+  finish_tile(L, layer, part, tok0, nt, scores, token_mask, preact);
 }
 
 // Second half of the split router: one wave per token turns A^0 (in `scores`) into the mask word(s)
@@ -230,10 +345,18 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
     return hipGetLastError();
   }
   dim3 grid((unsigned)blocks);
-  if (wdtype == BLOCKFFN_BF16)
-    hipLaunchKernelGGL((router_kernel<bf16_t, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
-                         preact);
-  else
+  if (wdtype == BLOCKFFN_BF16) {
+    const int rt = (L.E + 15) / 16;
+#define BLOCKFFN_ROUTER(RT, KB)                                                                               \
+  hipLaunchKernelGGL((router_mfma_kernel<RT, KB>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, \
+                     token_mask, preact)
+    if (rt <= 1) BLOCKFFN_ROUTER(1, 4);
+    else if (rt <= 2) BLOCKFFN_ROUTER(2, 2);
+    else if (rt <= 4) BLOCKFFN_ROUTER(4, 2);
+    else if (rt <= 8) BLOCKFFN_ROUTER(8, 2);
+    else BLOCKFFN_ROUTER(16, 1);
+#undef BLOCKFFN_ROUTER
+  } else
     hipLaunchKernelGGL((router_kernel<float, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
                          preact);
   return hipGetLastError();
