@@ -6,8 +6,8 @@
 //   up    one workgroup = (item of the (chunk, slot) list, TN tokens, TM/2 neurons): a
 //         TM x TN x d contraction (TM/2 W_up rows and the matching W_gate rows against TN
 //         tokens; TM = TN = 256, or 128 for short chunks), both operands staged through
-//         double-buffered LDS in MFMA fragment order (global loads use the lane pattern of the
-//         operand, so LDS writes and reads are linear in the lane id and conflict free).
+//         double-buffered LDS in MFMA fragment order (global loads take whole 128-byte lines,
+//         8 lanes per row; an XOR swizzle of the slots keeps LDS writes and reads conflict free).
 //         Swish/gating, score and mask are applied on the accumulators; mid is written as
 //         bf16 [chunk][slot][token][neuron].
 //   down  one workgroup = (chunk, TM output columns, TN tokens, split): the contraction runs
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restr
 }
 
 // One stage in LDS: fragment id = (operand fragment) * KS + K-step, A fragments first; a fragment
-// is 64 lanes x 16 bytes in lane order.  Wave w loads ids [w * NL, (w + 1) * NL): the first
+// is 64 slots of 16 bytes (slot order: see the swizzle below).  Wave w loads ids [w * NL, (w + 1) * NL): the first
 // A_WAVES waves the A operand, the others the B operand, so a wave's loads of a stage share one
 // base pointer (base(stage), uniform over the wave) and differ only by the lane offsets off[]
 // (elements), fixed for the whole loop: no divergent control flow around the loads.  Loads for
@@ -96,10 +96,21 @@ __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseFn b
   r2 = *reinterpret_cast<const uint4 *>((ptr) + off[2]); r3 = *reinterpret_cast<const uint4 *>((ptr) + off[3]); \
   r4 = *reinterpret_cast<const uint4 *>((ptr) + off[4]); r5 = *reinterpret_cast<const uint4 *>((ptr) + off[5]); \
   r6 = *reinterpret_cast<const uint4 *>((ptr) + off[6]); r7 = *reinterpret_cast<const uint4 *>((ptr) + off[7]);
+  // load 2p + h of a wave covers rows 8h .. 8h + 7 of its p-th fragment, both K-steps: 8 lanes
+  // per row read one whole 128-byte line.  In LDS, entry (column group kg = 4 * ks + g, row n)
+  // of a fragment sits at slot g * 16 + (n ^ kg) of K-step ks: the 8 lanes that hold one row
+  // write 8 different bank groups, and a K-step's 64 entries still fill its 64 slots, so the
+  // fragment reads (one slot per lane) stay conflict free.
+  static_assert(T::KS == 2, "a stage row is one 128-byte line");
+  const int kg = lane & 7;
+  const int s0 = (kg >> 2) * 64 + (kg & 3) * 16 + ((lane >> 3) ^ kg);
+  const int s1 = (kg >> 2) * 64 + (kg & 3) * 16 + ((8 + (lane >> 3)) ^ kg);
 #define BLOCKFFN_STORE8(dst)                                                                     \
-  (dst)[0 * 64] = r0; (dst)[1 * 64] = r1; (dst)[2 * 64] = r2; (dst)[3 * 64] = r3;                \
-  (dst)[4 * 64] = r4; (dst)[5 * 64] = r5; (dst)[6 * 64] = r6; (dst)[7 * 64] = r7;
-  const int my = wave * T::NL * 64 + lane;   // this lane's slot in the first of its 8 fragments
+  (dst)[0 * 128 + s0] = r0; (dst)[0 * 128 + s1] = r1; (dst)[1 * 128 + s0] = r2; (dst)[1 * 128 + s1] = r3; \
+  (dst)[2 * 128 + s0] = r4; (dst)[2 * 128 + s1] = r5; (dst)[3 * 128 + s0] = r6; (dst)[3 * 128 + s1] = r7;
+  const int my = wave * T::NL * 64;   // first slot of this wave's 4 fragments (2 K-steps each)
+  const int rd0 = (lane >> 4) * 16 + ((lane & 15) ^ (lane >> 4));         // this lane's slot when reading K-step 0
+  const int rd1 = (lane >> 4) * 16 + ((lane & 15) ^ (4 + (lane >> 4)));   // and K-step 1
   {
     const uint16_t *b0 = base(0);
     BLOCKFFN_LOAD8(b0)
@@ -115,9 +126,10 @@ __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseFn b
       uint4 a[T::FI], b[T::FJ];
 #pragma unroll
       for (int i = 0; i < T::FI; ++i)
-        a[i] = cur[((i < T::FI / 2 ? a_lo + i : a_hi + i - T::FI / 2) * T::KS + ks) * 64 + lane];
+        a[i] = cur[((i < T::FI / 2 ? a_lo + i : a_hi + i - T::FI / 2) * T::KS + ks) * 64 + (ks ? rd1 : rd0)];
 #pragma unroll
-      for (int j = 0; j < T::FJ; ++j) b[j] = cur[((T::FA + wc * T::FJ + j) * T::KS + ks) * 64 + lane];
+      for (int j = 0; j < T::FJ; ++j)
+        b[j] = cur[((T::FA + wc * T::FJ + j) * T::KS + ks) * 64 + (ks ? rd1 : rd0)];
 #pragma unroll
       for (int i = 0; i < T::FI; ++i)
 #pragma unroll
@@ -141,7 +153,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
     uint16_t *__restrict__ H) {
   extern __shared__ uint4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, g = lane >> 4;
+  const int g = lane >> 4;
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int per_item = tiles_t * tiles_j;
   const int item = blockIdx.x / per_item;
@@ -168,11 +180,11 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   int off[T::NL];
 #pragma unroll
   for (int i = 0; i < T::NL; ++i) {
-    const int f = f0 + i / T::KS, ks = i % T::KS;
+    const int f = f0 + i / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
     int row;
-    if (is_a) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + r;
-    else row = min(t0 + f * 16 + r, k - 1);
-    off[i] = row * d + ks * 32 + g * 8;
+    if (is_a) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
+    else row = min(t0 + f * 16 + rf, k - 1);
+    off[i] = row * d + (lane & 7) * 8;
   }
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
   const uint16_t *base0 = is_a ? wsel : xb + (size_t)c * k * d;
@@ -223,7 +235,7 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
     const uint16_t *__restrict__ H, float *__restrict__ out, size_t split_stride) {
   extern __shared__ uint4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, g = lane >> 4;
+  const int g = lane >> 4;
   const int E = L.E, d = L.d, d_e = L.d_e;
   int b = blockIdx.x;
   const int sp = b % splits; b /= splits;
@@ -244,9 +256,9 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   int off[T::NL];
 #pragma unroll
   for (int i = 0; i < T::NL; ++i) {
-    const int f = f0 + i / T::KS, ks = i % T::KS;
-    const int row = is_a ? col0 + f * 16 + r : min(t0 + f * 16 + r, k - 1);
-    off[i] = row * d_e + ks * 32 + g * 8;
+    const int f = f0 + i / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
+    const int row = is_a ? col0 + f * 16 + rf : min(t0 + f * 16 + rf, k - 1);
+    off[i] = row * d_e + (lane & 7) * 8;
   }
   auto base = [&](int st) -> const uint16_t * {
     const int s = s_lo + st / st_per_slot;

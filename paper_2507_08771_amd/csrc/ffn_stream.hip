@@ -143,7 +143,6 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
   constexpr int KC = 2048 / NB;   // contraction elements per LDS fill
   constexpr int NA = acc_tiles(NB);
-  constexpr int TOK = tokens_of(NB);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int E = L.E, d = L.d, d_e = L.d_e;
