@@ -58,6 +58,9 @@ def impl(request, monkeypatch):
     (4096, 40, 256, 5, 3),    # two K-chunks of the streaming up kernel
     (1536, 64, 64, 16, 5),    # two token tiles
     (512, 130, 128, 20, 4),   # four token tiles with a ragged last one, three mask words
+    (512, 256, 64, 8, 5),     # the most experts: four full mask words, 16 router row tiles
+    (256, 8, 1024, 4, 2),     # the widest expert
+    (16384, 4, 8, 2, 2),      # the longest hidden size
 ])
 def test_shapes(d, E, d_e, k, C, wdtype, gated, impl):
     if impl == "generic" and wdtype == "f32":
@@ -209,3 +212,44 @@ def test_full_size_spec_k8_sampled_chunks():
     assert abs(gpu["stats"][1] / (C * E) - e_cls) < 0.02
     y = gpu["y"]
     assert np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("E", [5, 16, 31, 64, 100, 128, 130, 256])
+@pytest.mark.parametrize("k", [1, 8, 11])
+def test_router_with_many_token_tiles(E, k):
+    """Enough token tiles that the router takes its many-tile kernel (the matrix-core one for bf16
+    weights), every count of 16-expert row tiles, a hidden size that ends in a partial K-step
+    (520 = 16 * 32 + 8), gain and three weight sets; scores, masks and pre-activations against the
+    oracle's router."""
+    import oracle
+    d, C, n_layers = 520, 300, 3
+    w = wl.Workload("t", d=d, E=E, d_e=8, wdtype="bf16", gated=False, k=k, n_chunks=C, sigma=0.3, seed=E * 31 + k)
+    layers = wl.make_layers(w, n_layers, gain=True)
+    cl = wl.make_chunk_layer(w, n_layers)
+    x = wl.make_tokens(w, layers, cl)
+    dev = pu.to_device(layers)
+    L = B.Layer(dev["w_router"], dev["w_up"], dev["w_down"], None, dev["b_router"], dev["g_rms"], 1e-6)
+    scores = torch.empty((w.n_tok, E), dtype=torch.float32, device="cuda")
+    mask = torch.empty((w.n_tok, w.mask_words), dtype=torch.int64, device="cuda")
+    pre = torch.empty((w.n_tok, E), dtype=torch.float32, device="cuda")
+    B.blockffn_router_preact(L, x.cuda(), C, k, scores, mask, pre, cl.cuda().to(torch.int32))
+    torch.cuda.synchronize()
+    g_scores, g_mask, g_pre = scores.cpu().numpy(), mask.cpu().numpy().view(np.uint64), pre.cpu().numpy()
+    xs, cls = x.numpy(), cl.numpy()
+    for l in range(n_layers):
+        OL = pu.oracle_layer(layers, l, use_gain=True)
+        tok = np.nonzero(np.repeat(cls == l, k))[0]
+        r_scores, r_mask, a0 = oracle.router(OL, xs[tok], return_a0=True)
+        np.testing.assert_array_equal(g_mask[tok], r_mask)
+        mag = np.abs(xs[tok]).astype(np.float64) @ np.abs(layers["w_router"][l].double().numpy()).T + 1.0
+        delta = 1e-6 * mag                      # fp32 summation error allowed on a pre-activation
+        assert np.all(np.abs(g_pre[tok] - a0) <= delta)
+        # scores: 1e-5 of the row's rms, plus what the allowed error of the pre-activations becomes
+        # behind the normalisation (a token whose only active expert is barely active has
+        # sqrt(mean square + eps) close to sqrt(eps), which magnifies it)
+        a1 = np.maximum(a0, 0.0)
+        scale = np.sqrt((a1 * a1).mean(axis=1) + 1e-6)
+        gmax = float(layers["g_rms"][l].max())
+        rms = np.sqrt((r_scores.astype(np.float64) ** 2).mean(axis=1))
+        allowed = 1e-5 * np.maximum(rms, 1e-30) + 2.0 * gmax * delta.max(axis=1) / scale
+        assert np.all(np.abs(g_scores[tok] - r_scores).max(axis=1) <= allowed)
