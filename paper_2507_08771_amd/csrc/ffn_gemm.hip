@@ -6,8 +6,8 @@
 //   up    one workgroup = (item of the (chunk, slot) list, TN tokens, TM/2 neurons): a
 //         TM x TN x d contraction (TM/2 W_up rows and the matching W_gate rows against TN
 //         tokens; TM = TN = 256, or 128 for short chunks), both operands staged through
-//         double-buffered LDS in MFMA fragment order (global loads take whole 128-byte lines,
-//         8 lanes per row; an XOR swizzle of the slots keeps LDS writes and reads conflict free).
+//         double-buffered LDS (LDS-direct global loads of whole 128-byte lines, 8 lanes per
+//         row; an XOR swizzle of the pieces keeps the fragment reads conflict free).
 //         Swish/gating, score and mask are applied on the accumulators; mid is written as
 //         bf16 [chunk][slot][token][neuron].
 //   down  one workgroup = (chunk, TM output columns, TN tokens, split): the contraction runs
@@ -42,12 +42,12 @@ struct Tile {
   static constexpr int WAVES = WR * WC, THREADS = WAVES * 64;
   static constexpr int FA = TM / 16, FB = TN / 16;        // operand fragments per K-step
   static constexpr int FI = FA / WR, FJ = FB / WC;         // a wave's tile, in fragments
-  static constexpr int NL = (FA + FB) * KS / WAVES;        // fragment loads per wave and stage
+  static constexpr int NL = (FA + FB) * KS / WAVES;        // 1 KiB block loads per wave and stage
   static constexpr int STAGE_VEC = (FA + FB) * KS * 64;    // uint4 per stage
   static constexpr int LDS_BYTES = 2 * STAGE_VEC * 16;
-  static constexpr int A_WAVES = FA * KS / NL;             // waves [0, A_WAVES) load the A operand
-  static_assert(FA * KS % NL == 0 && (FA + FB) * KS % WAVES == 0, "loads must split evenly over the waves");
-  static_assert(NL % KS == 0 && (FA / 2) % (NL / KS) == 0, "a wave's A fragments must not straddle W_up / W_gate");
+  static constexpr int WF = FA / WAVES;                    // A fragments (and B fragments) a wave loads
+  static_assert(FA == FB && FA % WAVES == 0 && NL == 4 * WF, "every wave loads WF fragments of each operand");
+  static_assert((FA / 2) % WF == 0, "a wave's A fragments must not straddle W_up / W_gate");
 };
 // (A 4-wave variant of the 256-wide tile with 128 x 128 per wave, which halves the LDS reads per
 // MFMA, was slower: one wave per SIMD leaves nothing to cover LDS and memory latency with.)
@@ -76,71 +76,68 @@ __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restr
   }
 }
 
-// One stage in LDS: fragment id = (operand fragment) * KS + K-step, A fragments first; a fragment
-// is 64 slots of 16 bytes (slot order: see the swizzle below).  Wave w loads ids [w * NL, (w + 1) * NL): the first
-// A_WAVES waves the A operand, the others the B operand, so a wave's loads of a stage share one
-// base pointer (base(stage), uniform over the wave) and differ only by the lane offsets off[]
-// (elements), fixed for the whole loop: no divergent control flow around the loads.  Loads for
-// stage st+1 are issued before stage st is computed and written to the other LDS buffer after.
-template <typename T, typename BaseFn>
-__device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseFn base, const int (&off)[T::NL],
+// One stage in LDS: operand fragment F (A fragments first, then B) owns 2 KiB: block h (1 KiB)
+// holds rows 8h .. 8h + 7 of the fragment, both K-steps: a whole 128-byte line per row.  The
+// stage is filled by LDS-direct loads (global_load_lds_dwordx4: lane j's 16 bytes land at the
+// block's base + 16 j, no staging registers and no LDS store instructions): lane j loads piece
+// (j & 7) XOR (j >> 3) of row j >> 3, so the 8 lanes of a row together request the row's whole
+// line, and the 16-byte piece p of row r sits at slot 8 r + (p XOR r) of its block.  A fragment
+// read for K-step ks takes piece 4 ks + g of row n for lane (n, g): 8 neighbouring lanes hit 8
+// different bank groups, so the reads are conflict free.  Wave w fills A fragments and B
+// fragments [WF w, WF w + WF) (half of its loads each: the two operands come back at different
+// speeds, and waves that loaded only the slow one kept the others waiting at the barrier).  The
+// loads of one operand share a base pointer (base_a(stage) / base_b(stage), uniform over the
+// wave) and differ only by the lane offsets off[] (elements; A blocks first), fixed for the whole
+// loop.  The loads for stage st + 1 are issued while stage st is computed and awaited before the
+// barrier that ends it.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
+
+template <typename T, typename BaseA, typename BaseB>
+__device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseA base_a, BaseB base_b,
+                                              const int (&off)[T::NL],
                                               f32x4 (&acc)[T::FI][T::FJ], int a_lo, int a_hi, int wc) {
   // this wave's A fragments: a_lo + i for the first FI/2, a_hi + (i - FI/2) for the rest
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (n_stages <= 0) return;   // uniform over the workgroup
-  static_assert(T::NL == 8, "the staging registers below are written out for 8 loads per wave");
-  // eight named staging registers (an array here was left in scratch memory by the compiler)
-  uint4 r0, r1, r2, r3, r4, r5, r6, r7;
-#define BLOCKFFN_LOAD8(ptr)                                                                      \
-  r0 = *reinterpret_cast<const uint4 *>((ptr) + off[0]); r1 = *reinterpret_cast<const uint4 *>((ptr) + off[1]); \
-  r2 = *reinterpret_cast<const uint4 *>((ptr) + off[2]); r3 = *reinterpret_cast<const uint4 *>((ptr) + off[3]); \
-  r4 = *reinterpret_cast<const uint4 *>((ptr) + off[4]); r5 = *reinterpret_cast<const uint4 *>((ptr) + off[5]); \
-  r6 = *reinterpret_cast<const uint4 *>((ptr) + off[6]); r7 = *reinterpret_cast<const uint4 *>((ptr) + off[7]);
-  // load 2p + h of a wave covers rows 8h .. 8h + 7 of its p-th fragment, both K-steps: 8 lanes
-  // per row read one whole 128-byte line.  In LDS, entry (column group kg = 4 * ks + g, row n)
-  // of a fragment sits at slot g * 16 + (n ^ kg) of K-step ks: the 8 lanes that hold one row
-  // write 8 different bank groups, and a K-step's 64 entries still fill its 64 slots, so the
-  // fragment reads (one slot per lane) stay conflict free.
   static_assert(T::KS == 2, "a stage row is one 128-byte line");
-  const int kg = lane & 7;
-  const int s0 = (kg >> 2) * 64 + (kg & 3) * 16 + ((lane >> 3) ^ kg);
-  const int s1 = (kg >> 2) * 64 + (kg & 3) * 16 + ((8 + (lane >> 3)) ^ kg);
-#define BLOCKFFN_STORE8(dst)                                                                     \
-  (dst)[0 * 128 + s0] = r0; (dst)[0 * 128 + s1] = r1; (dst)[1 * 128 + s0] = r2; (dst)[1 * 128 + s1] = r3; \
-  (dst)[2 * 128 + s0] = r4; (dst)[2 * 128 + s1] = r5; (dst)[3 * 128 + s0] = r6; (dst)[3 * 128 + s1] = r7;
-  const int my = wave * T::NL * 64;   // first slot of this wave's 4 fragments (2 K-steps each)
-  const int rd0 = (lane >> 4) * 16 + ((lane & 15) ^ (lane >> 4));         // this lane's slot when reading K-step 0
-  const int rd1 = (lane >> 4) * 16 + ((lane & 15) ^ (4 + (lane >> 4)));   // and K-step 1
-  {
-    const uint16_t *b0 = base(0);
-    BLOCKFFN_LOAD8(b0)
-    BLOCKFFN_STORE8(lds + my)
-  }
+  const int my_a = wave * T::WF * 128, my_b = (T::FA + wave * T::WF) * 128;   // first slots of this wave's blocks
+  const int n = lane & 15, g = lane >> 4;
+  const int rd0 = (n >> 3) * 64 + (n & 7) * 8 + (g ^ (n & 7));         // this lane's slot when reading K-step 0
+  const int rd1 = (n >> 3) * 64 + (n & 7) * 8 + ((4 + g) ^ (n & 7));   // and K-step 1
+  auto fill = [&](int st, uint4 *buf) {
+    const uint16_t *pa = base_a(st), *pb = base_b(st);
+#pragma unroll
+    for (int i = 0; i < T::NL / 2; ++i) {
+      __builtin_amdgcn_global_load_lds((global_void_t *)(pa + off[i]), (lds_void_t *)(buf + my_a + i * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_void_t *)(pb + off[T::NL / 2 + i]), (lds_void_t *)(buf + my_b + i * 64),
+                                       16, 0, 0);
+    }
+  };
+  fill(0, lds);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   for (int st = 0; st < n_stages; ++st) {
-    const uint16_t *bn = base(min(st + 1, n_stages - 1));   // past the end: a harmless reload
-    BLOCKFFN_LOAD8(bn)
     const uint4 *cur = lds + (st & 1) * T::STAGE_VEC;
 #pragma unroll
     for (int ks = 0; ks < T::KS; ++ks) {
+      // the next stage's loads go out between the two K-steps: the matrix cores have the first
+      // K-step's work queued while the memory pipeline takes the requests
+      if (ks == 1 && st + 1 < n_stages) fill(st + 1, lds + ((st + 1) & 1) * T::STAGE_VEC);   // uniform branch
       uint4 a[T::FI], b[T::FJ];
 #pragma unroll
       for (int i = 0; i < T::FI; ++i)
-        a[i] = cur[((i < T::FI / 2 ? a_lo + i : a_hi + i - T::FI / 2) * T::KS + ks) * 64 + (ks ? rd1 : rd0)];
+        a[i] = cur[(i < T::FI / 2 ? a_lo + i : a_hi + i - T::FI / 2) * 128 + (ks ? rd1 : rd0)];
 #pragma unroll
-      for (int j = 0; j < T::FJ; ++j)
-        b[j] = cur[((T::FA + wc * T::FJ + j) * T::KS + ks) * 64 + (ks ? rd1 : rd0)];
+      for (int j = 0; j < T::FJ; ++j) b[j] = cur[(T::FA + wc * T::FJ + j) * 128 + (ks ? rd1 : rd0)];
 #pragma unroll
       for (int i = 0; i < T::FI; ++i)
 #pragma unroll
         for (int j = 0; j < T::FJ; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
     }
-    uint4 *nxt = lds + ((st + 1) & 1) * T::STAGE_VEC + my;
-    BLOCKFFN_STORE8(nxt)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the next stage is in LDS
     __syncthreads();
   }
-#undef BLOCKFFN_LOAD8
-#undef BLOCKFFN_STORE8
 }
 
 // ------------------------------------------------------------------------------------------------ up
@@ -155,10 +152,14 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4;
   const int E = L.E, d = L.d, d_e = L.d_e;
+  // Workgroups go to the 8 XCDs round robin (workgroup v runs on XCD v mod 8) and each XCD has
+  // its own L2: the tiles of one item share the expert's weight rows, so they are given ids that
+  // differ by multiples of 8 and meet in one L2; the weights cross the fabric once per item.
   const int per_item = tiles_t * tiles_j;
-  const int item = blockIdx.x / per_item;
+  const int q = blockIdx.x >> 3, within = q % per_item;
+  const int item = (q / per_item) * 8 + (blockIdx.x & 7);
   if (item >= *total_ptr) return;
-  const int tt = (blockIdx.x % per_item) / tiles_j, tj = blockIdx.x % tiles_j;
+  const int tt = within / tiles_j, tj = within % tiles_j;
   const int code = items[item];
   const int64_t c = code / E;
   const int s = code - (int)c * E;
@@ -174,21 +175,21 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // A fragment f: gated: f < FA/2 -> W_up rows j0 + 16 f, else W_gate rows j0 + 16 (f - FA/2);
   // Eq. 2: W_up rows j0 + 16 f.  B fragment f: tokens t0 + 16 f.  A token index past the chunk
   // is clamped: its column of the product comes from a valid row and is never stored.
-  const bool is_a = wave < T::A_WAVES;
-  const int f0 = (is_a ? wave : wave - T::A_WAVES) * (T::NL / T::KS);   // first fragment this wave loads
-  const bool gate_wave = NM == 2 && is_a && f0 >= T::FA / 2;
+  const int f0 = wave * T::WF;   // first fragment of each operand this wave loads
+  const bool gate_wave = NM == 2 && f0 >= T::FA / 2;
   int off[T::NL];
 #pragma unroll
   for (int i = 0; i < T::NL; ++i) {
-    const int f = f0 + i / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
+    const int f = f0 + (i % (T::NL / 2)) / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
     int row;
-    if (is_a) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
+    if (i < T::NL / 2) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
     else row = min(t0 + f * 16 + rf, k - 1);
-    off[i] = row * d + (lane & 7) * 8;
+    off[i] = row * d + ((lane & 7) ^ (lane >> 3)) * 8;   // piece (j & 7) XOR (j >> 3) of the row's line
   }
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
-  const uint16_t *base0 = is_a ? wsel : xb + (size_t)c * k * d;
-  auto base = [&](int st) { return base0 + (size_t)st * T::TK; };
+  const uint16_t *xsel = xb + (size_t)c * k * d;
+  auto base_a = [&](int st) { return wsel + (size_t)st * T::TK; };
+  auto base_b = [&](int st) { return xsel + (size_t)st * T::TK; };
 
   f32x4 acc[T::FI][T::FJ];
 #pragma unroll
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // this wave's A fragments: gated: FI/2 up fragments and the FI/2 matching gate fragments
   const int a_lo = NM == 2 ? wr * (T::FI / 2) : wr * T::FI;
   const int a_hi = NM == 2 ? T::FA / 2 + wr * (T::FI / 2) : wr * T::FI + T::FI / 2;
-  gemm_mainloop<T>(lds, d / T::TK, base, off, acc, a_lo, a_hi, wc);
+  gemm_mainloop<T>(lds, d / T::TK, base_a, base_b, off, acc, a_lo, a_hi, wc);
 
   // D[i = neuron 4g + q of the fragment][j = token n of the fragment]
   const int n = lane & 15;
@@ -231,17 +232,21 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
 template <typename T>
 __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ n_active, int k, int tiles_t, int tiles_c, int splits,
+    const int32_t *__restrict__ n_active, int k, int tiles_t, int tiles_c, int splits, int64_t n_groups,
     const uint16_t *__restrict__ H, float *__restrict__ out, size_t split_stride) {
   extern __shared__ uint4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4;
   const int E = L.E, d = L.d, d_e = L.d_e;
-  int b = blockIdx.x;
-  const int sp = b % splits; b /= splits;
-  const int tc = b % tiles_c; b /= tiles_c;
-  const int tt = b % tiles_t;
-  const int64_t c = b / tiles_t;
+  // all tiles of one (chunk, split) on one XCD (ids differing by multiples of 8): they share the
+  // split's W_down rows (the token tiles) and its mid rows (the column tiles) in that XCD's L2
+  const int per_group = tiles_t * tiles_c;
+  const int q = blockIdx.x >> 3, within = q % per_group;
+  const int64_t grp = (int64_t)(q / per_group) * 8 + (blockIdx.x & 7);
+  if (grp >= n_groups) return;   // uniform over the workgroup
+  const int sp = (int)(grp % splits);
+  const int64_t c = grp / splits;
+  const int tc = within % tiles_c, tt = within / tiles_c;
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
   const int s_lo = (int)((int64_t)n_act * sp / splits), s_hi = (int)((int64_t)n_act * (sp + 1) / splits);
@@ -251,24 +256,24 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
 
   // A fragment f: W_down rows col0 + 16 f of the stage's expert; B fragment f: mid rows of tokens
   // t0 + 16 f (clamped as in the up kernel) of the stage's slot.
-  const bool is_a = wave < T::A_WAVES;
-  const int f0 = (is_a ? wave : wave - T::A_WAVES) * (T::NL / T::KS);
+  const int f0 = wave * T::WF;   // first fragment of each operand this wave loads
   int off[T::NL];
 #pragma unroll
   for (int i = 0; i < T::NL; ++i) {
-    const int f = f0 + i / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
-    const int row = is_a ? col0 + f * 16 + rf : min(t0 + f * 16 + rf, k - 1);
-    off[i] = row * d_e + (lane & 7) * 8;
+    const int f = f0 + (i % (T::NL / 2)) / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
+    const int row = i < T::NL / 2 ? col0 + f * 16 + rf : min(t0 + f * 16 + rf, k - 1);
+    off[i] = row * d_e + ((lane & 7) ^ (lane >> 3)) * 8;
   }
-  auto base = [&](int st) -> const uint16_t * {
+  auto base_a = [&](int st) -> const uint16_t * {
     const int s = s_lo + st / st_per_slot;
-    const size_t koff = (size_t)(st % st_per_slot) * T::TK;
-    if (is_a) {
-      int e = active_idx ? active_idx[c * E + s] : s;
-      e = min(max(e, 0), E - 1);
-      return static_cast<const uint16_t *>(L.w_down) + ((size_t)layer * E + e) * d * d_e + koff;
-    }
-    return H + ((size_t)c * E + s) * k * d_e + koff;
+    int e = active_idx ? active_idx[c * E + s] : s;
+    e = min(max(e, 0), E - 1);
+    return static_cast<const uint16_t *>(L.w_down) + ((size_t)layer * E + e) * d * d_e +
+           (size_t)(st % st_per_slot) * T::TK;
+  };
+  auto base_b = [&](int st) -> const uint16_t * {
+    const int s = s_lo + st / st_per_slot;
+    return H + ((size_t)c * E + s) * k * d_e + (size_t)(st % st_per_slot) * T::TK;
   };
 
   f32x4 acc[T::FI][T::FJ];
@@ -276,7 +281,7 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   for (int i = 0; i < T::FI; ++i)
 #pragma unroll
     for (int j = 0; j < T::FJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  gemm_mainloop<T>(lds, (s_hi - s_lo) * st_per_slot, base, off, acc, wr * T::FI, wr * T::FI + T::FI / 2, wc);
+  gemm_mainloop<T>(lds, (s_hi - s_lo) * st_per_slot, base_a, base_b, off, acc, wr * T::FI, wr * T::FI + T::FI / 2, wc);
 
   const int n = lane & 15;
   float *dst = out + (size_t)sp * split_stride;
@@ -347,7 +352,7 @@ hipError_t launch_up_tile(const LayerView &L, bool gated, const int32_t *chunk_l
                           const uint64_t *token_mask, const int32_t *active_idx, const GemmWs &w, int64_t n_chunks,
                           int k, hipStream_t s) {
   const int tiles_t = (k + T::TN - 1) / T::TN, tiles_j = L.d_e / (T::TM / (gated ? 2 : 1));
-  const int64_t grid = n_chunks * L.E * tiles_t * tiles_j;
+  const int64_t grid = (n_chunks * L.E + 7) / 8 * 8 * tiles_t * tiles_j;   // items rounded up to the 8 XCDs
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   static bool attr_set = false;
   if (!attr_set) {
@@ -372,7 +377,8 @@ hipError_t launch_down_tile(const LayerView &L, const int32_t *chunk_layer, cons
                             const int32_t *n_active, int64_t n_chunks, int k, int splits, const uint16_t *H,
                             float *out, size_t stride, hipStream_t s) {
   const int tiles_t = (k + T::TN - 1) / T::TN, tiles_c = L.d / T::TM;
-  const int64_t grid = n_chunks * tiles_t * tiles_c * splits;
+  const int64_t n_groups = n_chunks * splits;
+  const int64_t grid = (n_groups + 7) / 8 * 8 * tiles_t * tiles_c;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   static bool attr_set = false;
   if (!attr_set) {
@@ -382,7 +388,7 @@ hipError_t launch_down_tile(const LayerView &L, const int32_t *chunk_layer, cons
     attr_set = true;
   }
   hipLaunchKernelGGL((down_gemm_kernel<T>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
-                     active_idx, n_active, k, tiles_t, tiles_c, splits, H, out, stride);
+                     active_idx, n_active, k, tiles_t, tiles_c, splits, n_groups, H, out, stride);
   return hipGetLastError();
 }
 
