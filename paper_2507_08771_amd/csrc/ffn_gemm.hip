@@ -79,11 +79,13 @@ __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restr
 // One stage in LDS: operand fragment F (A fragments first, then B) owns 2 KiB: block h (1 KiB)
 // holds rows 8h .. 8h + 7 of the fragment, both K-steps: a whole 128-byte line per row.  The
 // stage is filled by LDS-direct loads (global_load_lds_dwordx4: lane j's 16 bytes land at the
-// block's base + 16 j, no staging registers and no LDS store instructions): lane j loads piece
-// (j & 7) XOR (j >> 3) of row j >> 3, so the 8 lanes of a row together request the row's whole
-// line, and the 16-byte piece p of row r sits at slot 8 r + (p XOR r) of its block.  A fragment
-// read for K-step ks takes piece 4 ks + g of row n for lane (n, g): 8 neighbouring lanes hit 8
-// different bank groups, so the reads are conflict free.  Wave w fills A fragments and B
+// block's base + 16 j, no staging registers and no LDS store instructions): lane j of block h
+// loads piece (j & 7) XOR r of row r = (j >> 3) XOR h, so the 8 lanes of a row together request
+// the row's whole line, and the 16-byte piece p of row r sits at slot 8 (r XOR h) + (p XOR r) of
+// its block.  A fragment read for K-step ks takes piece 4 ks + g of row n for lane (n, g): the 16
+// lanes of one g (two blocks) hit 16 different 16-byte bank groups of the 64-bank LDS, so the
+// reads are conflict free - without the row swap in odd blocks the two blocks collided and every
+// read took 8 instead of 4 cycles (SQ_LDS_BANK_CONFLICT was half of SQ_LDS_IDX_ACTIVE).  Wave w fills A fragments and B
 // fragments [WF w, WF w + WF) (half of its loads each: the two operands come back at different
 // speeds, and waves that loaded only the slow one kept the others waiting at the barrier).  The
 // loads of one operand share a base pointer (base_a(stage) / base_b(stage), uniform over the
@@ -103,8 +105,9 @@ __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseA ba
   static_assert(T::KS == 2, "a stage row is one 128-byte line");
   const int my_a = wave * T::WF * 128, my_b = (T::FA + wave * T::WF) * 128;   // first slots of this wave's blocks
   const int n = lane & 15, g = lane >> 4;
-  const int rd0 = (n >> 3) * 64 + (n & 7) * 8 + (g ^ (n & 7));         // this lane's slot when reading K-step 0
-  const int rd1 = (n >> 3) * 64 + (n & 7) * 8 + ((4 + g) ^ (n & 7));   // and K-step 1
+  const int xs = ((n & 7) ^ (n >> 3)) * 8;                             // rows of odd blocks are swapped in pairs
+  const int rd0 = (n >> 3) * 64 + xs + (g ^ (n & 7));         // this lane's slot when reading K-step 0
+  const int rd1 = (n >> 3) * 64 + xs + ((4 + g) ^ (n & 7));   // and K-step 1
   auto fill = [&](int st, uint4 *buf) {
     const uint16_t *pa = base_a(st), *pb = base_b(st);
 #pragma unroll
@@ -180,16 +183,21 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   int off[T::NL];
 #pragma unroll
   for (int i = 0; i < T::NL; ++i) {
-    const int f = f0 + (i % (T::NL / 2)) / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
+    const int h = i % 2, r = (lane >> 3) ^ h;                  // block of the fragment, row of the block
+    const int f = f0 + (i % (T::NL / 2)) / 2, rf = h * 8 + r;   // fragment, row of the fragment
     int row;
     if (i < T::NL / 2) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
     else row = min(t0 + f * 16 + rf, k - 1);
-    off[i] = row * d + ((lane & 7) ^ (lane >> 3)) * 8;   // piece (j & 7) XOR (j >> 3) of the row's line
+    off[i] = row * d + ((lane & 7) ^ r) * 8;   // piece (j & 7) XOR r of the row's line
   }
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
   const uint16_t *xsel = xb + (size_t)c * k * d;
-  auto base_a = [&](int st) { return wsel + (size_t)st * T::TK; };
-  auto base_b = [&](int st) { return xsel + (size_t)st * T::TK; };
+  // every tile of the launch reads the chunk's x: each starts at another stage of the
+  // contraction, so that they do not all ask the L2 for the same lines at the same moment
+  const int n_st = d / T::TK, rot = (int)((blockIdx.x * 5u) % (unsigned)n_st);
+  auto stage_of = [&](int st) { const int v = st + rot; return v >= n_st ? v - n_st : v; };
+  auto base_a = [&](int st) { return wsel + (size_t)stage_of(st) * T::TK; };
+  auto base_b = [&](int st) { return xsel + (size_t)stage_of(st) * T::TK; };
 
   f32x4 acc[T::FI][T::FJ];
 #pragma unroll
@@ -260,9 +268,10 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   int off[T::NL];
 #pragma unroll
   for (int i = 0; i < T::NL; ++i) {
-    const int f = f0 + (i % (T::NL / 2)) / 2, rf = (i % 2) * 8 + (lane >> 3);   // fragment, row of the fragment
+    const int h = i % 2, r = (lane >> 3) ^ h;                  // block of the fragment, row of the block
+    const int f = f0 + (i % (T::NL / 2)) / 2, rf = h * 8 + r;   // fragment, row of the fragment
     const int row = i < T::NL / 2 ? col0 + f * 16 + rf : min(t0 + f * 16 + rf, k - 1);
-    off[i] = row * d_e + ((lane & 7) ^ (lane >> 3)) * 8;
+    off[i] = row * d_e + ((lane & 7) ^ r) * 8;
   }
   auto base_a = [&](int st) -> const uint16_t * {
     const int s = s_lo + st / st_per_slot;
