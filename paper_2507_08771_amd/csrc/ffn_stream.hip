@@ -36,6 +36,8 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void global_void_t;
 
 constexpr int kThreads = 256;
 constexpr int kRing = 16;          // 128-bit loads in flight per lane
@@ -521,14 +523,17 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       const bool has_next = s + 1 < s_hi;
       const int e_n = has_next ? slot_expert(s + 1) : e;
       const char *nxt = slot_ptr(e_n);
-      // mid of the next slot (the last slot re-reads itself; the copy is harmless and keeps the
-      // staging registers unconditional)
+      // mid of the next slot goes straight into the other LDS buffer (LDS-direct loads: lane j's
+      // 16 bytes land at the wave's base + 16 j; no staging registers, no LDS stores).  The last
+      // slot re-reads itself: harmless, and it keeps the number of loads in flight the same.
       const int s_stage = has_next ? s + 1 : s;
-      uint4 stage[kPerThread];
+      uint4 *stage_dst = midS[(s - s_lo + 1) & 1];
 #pragma unroll
       for (int q = 0; q < kPerThread; ++q) {
         const int idx = tid + q * kThreads;
-        stage[q] = *stage_src(s_stage, idx < kStage ? idx : 0);
+        if (q * kThreads + wave * 64 < kStage)   // uniform over the wave (kStage is a multiple of 64)
+          __builtin_amdgcn_global_load_lds((global_void_t *)stage_src(s_stage, idx),
+                                           (lds_void_t *)(stage_dst + q * kThreads + wave * 64), 16, 0, 0);
       }
       const char *cur = slot_ptr(e);
       const uint4 *bS = midS[(s - s_lo) & 1];
@@ -546,11 +551,10 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
           else if (has_next) ring[f % RING] = *reinterpret_cast<const uint4 *>(nxt + frag_off(fn - kFrag));
         }
       }
-#pragma unroll
-      for (int q = 0; q < kPerThread; ++q) {
-        const int idx = tid + q * kThreads;
-        if (idx < kStage) midS[(s - s_lo + 1) & 1][idx] = stage[q];
-      }
+      // loads return in issue order: everything older than the weight loads issued since (at
+      // most RING are outstanding) has arrived, and with it the staged mid
+      static_assert(kFrag >= RING, "the ring is refilled at least once per slot after the staging loads");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(RING) : "memory");
       __syncthreads();
       e = e_n;
     }
@@ -638,7 +642,7 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
   const int splits = down_splits(L, n_chunks);
   const size_t stride = (size_t)n_chunks * k * L.d;
   if (splits == 0) {
-    constexpr int MW = (NB == 4 && KSD >= 4) ? 4 : 8;   // two accumulator tiles per row tile at NB = 4
+    constexpr int MW = (NB == 4 && KSD >= 8) ? 4 : 8;   // 8 row tiles x 2 accumulator tiles do not fit beside 64 fragments of addresses
     const int col_blocks = L.d / (4 * MW * 16);
     const int64_t grid = n_chunks * col_blocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
