@@ -58,6 +58,10 @@ def impl(request, monkeypatch):
     (4096, 40, 256, 5, 3),    # two K-chunks of the streaming up kernel
     (1536, 64, 64, 16, 5),    # two token tiles
     (512, 130, 128, 20, 4),   # four token tiles with a ragged last one, three mask words
+    (2048, 64, 256, 16, 3),   # two token tiles, two K-chunks of 1024
+    (3072, 40, 256, 12, 3),   # two token tiles, three K-chunks
+    (1024, 48, 256, 32, 3),   # four token tiles, two K-chunks of 512
+    (2560, 64, 256, 24, 2),   # four token tiles with a ragged last one, five K-chunks
     (512, 256, 64, 8, 5),     # the most experts: four full mask words, 16 router row tiles
     (256, 8, 1024, 4, 2),     # the widest expert
     (16384, 4, 8, 2, 2),      # the longest hidden size
