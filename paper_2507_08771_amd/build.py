@@ -23,7 +23,7 @@ FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option", "-Wno-unused-command-line-argument",
+    "-Wall", "-Wno-unused-function", "-Wno-inline-asm", "-Wno-unknown-warning-option", "-Wno-unused-command-line-argument",
 ]
 
 

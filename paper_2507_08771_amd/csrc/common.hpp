@@ -74,6 +74,23 @@ __device__ __forceinline__ long long wave_sum_i64(long long v) {
   return v;
 }
 
+// LDS-direct load: lane j's 16 bytes at `src` land in LDS at `dst` + 16 j (dst is uniform over
+// the wave; it goes through M0).  Written as inline assembly on purpose: the compiler's wait
+// insertion treats the builtin form as a store to LDS that any later LDS read may alias and puts
+// `s_waitcnt vmcnt(0)` in front of that read, which serialises the very loads this is meant to
+// keep in flight under the matrix work.  Issued this way the compiler does not count the load, so
+// the caller must wait for it itself (`s_waitcnt vmcnt(n)`: loads return in issue order) and put
+// a barrier between the wait and reads by other waves.
+__device__ __forceinline__ void load_to_lds16(const void *src, void *dst) {
+  typedef __attribute__((address_space(3))) void lds_void;
+  const uint32_t lds_addr =
+      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_addr), "v"(src)
+               : "memory", "m0");
+}
+
 // Swish with beta = 1 (SiLU), full-precision exponential.
 __device__ __forceinline__ float swish(float u) { return u / (1.0f + expf(-u)); }
 

@@ -34,9 +34,10 @@ constexpr int kThreads = 256;
 // 10-15 TB/s to the CUs (measured), the matrix cores want 2.5 PFLOP/s: a tile has to reuse every
 // byte it pulls from L2 for > 100 flop, which takes 256 x 256 (128 flop per byte); 128 x 128
 // (64 flop per byte) is kept for chunks too short to fill 256 token columns.
-template <int TM_, int TN_, int WR_, int WC_, int KS_>
+template <int TM_, int TN_, int WR_, int WC_, int KS_, bool RING_>
 struct Tile {
   static constexpr int TM = TM_, TN = TN_, WR = WR_, WC = WC_;
+  static constexpr bool RING = RING_;                      // five half-stage buffers (see gemm_mainloop_ring)
   static constexpr int KS = KS_;                           // MFMA K-steps (32 elements) per stage
   static constexpr int TK = 32 * KS;                       // contraction elements per stage
   static constexpr int WAVES = WR * WC, THREADS = WAVES * 64;
@@ -44,15 +45,17 @@ struct Tile {
   static constexpr int FI = FA / WR, FJ = FB / WC;         // a wave's tile, in fragments
   static constexpr int NL = (FA + FB) * KS / WAVES;        // 1 KiB block loads per wave and stage
   static constexpr int STAGE_VEC = (FA + FB) * KS * 64;    // uint4 per stage
-  static constexpr int LDS_BYTES = 2 * STAGE_VEC * 16;
+  static constexpr int HALF_VEC = (FA + FB) * 64;          // uint4 per half stage (one K-step) of the ring
+  static constexpr int LDS_BYTES = RING ? 5 * HALF_VEC * 16 : 2 * STAGE_VEC * 16;
   static constexpr int WF = FA / WAVES;                    // A fragments (and B fragments) a wave loads
+  static constexpr int NOFF = RING ? 2 * WF : NL;          // distinct lane offsets of a wave's loads
   static_assert(FA == FB && FA % WAVES == 0 && NL == 4 * WF, "every wave loads WF fragments of each operand");
   static_assert((FA / 2) % WF == 0, "a wave's A fragments must not straddle W_up / W_gate");
 };
 // (A 4-wave variant of the 256-wide tile with 128 x 128 per wave, which halves the LDS reads per
 // MFMA, was slower: one wave per SIMD leaves nothing to cover LDS and memory latency with.)
-using TileSmall = Tile<128, 128, 2, 2, 2>;   // 4 waves, 64 KiB LDS, 2 workgroups per CU
-using TileBig = Tile<256, 256, 2, 4, 2>;     // 8 waves, 128 KiB LDS, 1 workgroup per CU
+using TileSmall = Tile<128, 128, 2, 2, 2, false>;   // 4 waves, 64 KiB LDS, 2 workgroups per CU
+using TileBig = Tile<256, 256, 2, 4, 2, true>;       // 8 waves, 160 KiB LDS (5 x 32 KiB), 1 workgroup per CU
 
 __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
@@ -61,6 +64,12 @@ __device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
 
 __device__ __forceinline__ uint32_t bf16_bits(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
+}
+
+// Swish for a result that is rounded to bf16 right away: hardware exp2 and reciprocal (about
+// 1e-6 relative, against the 2^-9 of the rounding).  u -> -inf gives u * 0.
+__device__ __forceinline__ float swish_fast(float u) {
+  return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
 }
 
 __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restrict__ x, uint16_t *__restrict__ xb,
@@ -92,8 +101,6 @@ __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restr
 // wave) and differ only by the lane offsets off[] (elements; A blocks first), fixed for the whole
 // loop.  The loads for stage st + 1 are issued while stage st is computed and awaited before the
 // barrier that ends it.
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_void_t;
 
 template <typename T, typename BaseA, typename BaseB>
 __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseA base_a, BaseB base_b,
@@ -112,9 +119,8 @@ __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseA ba
     const uint16_t *pa = base_a(st), *pb = base_b(st);
 #pragma unroll
     for (int i = 0; i < T::NL / 2; ++i) {
-      __builtin_amdgcn_global_load_lds((global_void_t *)(pa + off[i]), (lds_void_t *)(buf + my_a + i * 64), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((global_void_t *)(pb + off[T::NL / 2 + i]), (lds_void_t *)(buf + my_b + i * 64),
-                                       16, 0, 0);
+      load_to_lds16(pa + off[i], buf + my_a + i * 64);
+      load_to_lds16(pb + off[T::NL / 2 + i], buf + my_b + i * 64);
     }
   };
   fill(0, lds);
@@ -124,9 +130,9 @@ __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseA ba
     const uint4 *cur = lds + (st & 1) * T::STAGE_VEC;
 #pragma unroll
     for (int ks = 0; ks < T::KS; ++ks) {
-      // the next stage's loads go out between the two K-steps: the matrix cores have the first
-      // K-step's work queued while the memory pipeline takes the requests
-      if (ks == 1 && st + 1 < n_stages) fill(st + 1, lds + ((st + 1) & 1) * T::STAGE_VEC);   // uniform branch
+      // the next stage's loads go out first (its buffer was released by the barrier that ended
+      // the previous stage) and have the whole stage's matrix work to arrive in
+      if (ks == 0 && st + 1 < n_stages) fill(st + 1, lds + ((st + 1) & 1) * T::STAGE_VEC);   // uniform branch
       uint4 a[T::FI], b[T::FJ];
 #pragma unroll
       for (int i = 0; i < T::FI; ++i)
@@ -141,6 +147,119 @@ __device__ __forceinline__ void gemm_mainloop(uint4 *lds, int n_stages, BaseA ba
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the next stage is in LDS
     __syncthreads();
   }
+}
+
+// Which piece of the tile lane `lane` fetches with its load i: operand (A or B), fragment
+// relative to the wave's first one, row of the fragment, 16-byte piece of the stage's row.
+template <typename T>
+__device__ __forceinline__ void load_role(int i, int lane, bool &is_b, int &f_rel, int &rf, int &piece) {
+  if constexpr (T::RING) {
+    is_b = i >= T::WF;
+    f_rel = i % T::WF;
+    rf = lane >> 2;
+    piece = (lane & 3) ^ ((rf >> 2) & 3);
+  } else {
+    const int h = i % 2, r = (lane >> 3) ^ h;   // block of the fragment, row of the block
+    is_b = i >= T::NL / 2;
+    f_rel = (i % (T::NL / 2)) / 2;
+    rf = h * 8 + r;
+    piece = (lane & 7) ^ r;   // piece (j & 7) XOR r of the row's line
+  }
+}
+
+// The 256 x 256 tile's pipeline.  With two 64 KiB stages a CU has one stage of loads in flight
+// for about half a stage of matrix work; a loaded round trip to L2 is far longer than that and
+// the matrix cores waited (stage period 2.2 us for 0.85 us of matrix work).  Here the 160 KiB of
+// LDS are five buffers of one K-step each (32 contraction elements of all 512 operand rows,
+// 32 KiB).  Loads are issued a pair of K-steps (one 128-byte line per row) at a time, the two
+// 64-byte halves of a line back to back by the same lanes, into two different buffers: pair j + 2
+// goes out in the middle of pair j, so every pair has one and a half pairs of matrix work to
+// arrive in and up to 128 KiB per CU are in flight.  Buffer of K-step h: h mod 5.
+//   fragment F of a buffer: 1 KiB = 16 rows x 64 bytes; lane j of the load fetches row j >> 2,
+//   piece (j & 3) XOR ((j >> 4) & 3), which lands at slot j; the fragment read of lane (n, g)
+//   takes slot 4 n + (g XOR (n >> 2)): for one g the 16 lanes touch 16 different 16-byte bank
+//   groups.
+// Loads return in issue order, so `s_waitcnt vmcnt(loads of one pair)` is "the older pair has
+// landed" while the newest stays in flight.
+template <typename T, typename BaseA, typename BaseB>
+__device__ __forceinline__ void gemm_mainloop_ring(uint4 *lds, int n_pairs, BaseA base_a, BaseB base_b,
+                                                   const int (&off)[T::NOFF], f32x4 (&acc)[T::FI][T::FJ], int a_lo,
+                                                   int a_hi, int wc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (n_pairs <= 0) return;   // uniform over the workgroup
+  constexpr int HV = T::HALF_VEC;
+  constexpr int kPairLoads = 4 * T::WF;   // loads a wave issues per pair
+  const int my_a = wave * T::WF * 64, my_b = (T::FA + wave * T::WF) * 64;
+  const int n = lane & 15, g = lane >> 4;
+  const int rd = n * 4 + (g ^ ((n >> 2) & 3));
+  auto issue = [&](int pair, int b0, int b1) {
+    const uint16_t *pa = base_a(pair), *pb = base_b(pair);
+    uint4 *d0 = lds + b0 * HV, *d1 = lds + b1 * HV;
+#pragma unroll
+    for (int i = 0; i < T::WF; ++i) {
+      load_to_lds16(pa + off[i], d0 + my_a + i * 64);
+      load_to_lds16(pa + off[i] + 32, d1 + my_a + i * 64);
+      load_to_lds16(pb + off[T::WF + i], d0 + my_b + i * 64);
+      load_to_lds16(pb + off[T::WF + i] + 32, d1 + my_b + i * 64);
+    }
+  };
+  // Fragment reads run one K-step ahead of the matrix work, into a second set of operand
+  // registers: the reads of K-step h + 1 are issued in the middle of K-step h, right after the
+  // barrier that says its buffer is complete, and their latency is covered by the second half of
+  // K-step h's MFMAs.  One barrier per K-step: it also tells that every wave has finished reading
+  // K-step h's buffer (each wave's reads completed before its first MFMA of the step), so the
+  // loads issued after it may overwrite that buffer and the one of K-step h - 1.
+  auto read = [&](uint4 (&a)[T::FI], uint4 (&b)[T::FJ], const uint4 *cur) {
+#pragma unroll
+    for (int j = 0; j < T::FJ; ++j) b[j] = cur[(T::FA + wc * T::FJ + j) * 64 + rd];
+#pragma unroll
+    for (int i = 0; i < T::FI; ++i) a[i] = cur[(i < T::FI / 2 ? a_lo + i : a_hi + i - T::FI / 2) * 64 + rd];
+  };
+  auto mma = [&](const uint4 (&a)[T::FI], const uint4 (&b)[T::FJ], int i_lo, int i_hi) {
+#pragma unroll
+    for (int i = i_lo; i < i_hi; ++i)
+#pragma unroll
+      for (int j = 0; j < T::FJ; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
+  };
+  auto buf = [&](int b) { return lds + (b >= 5 ? b - 5 : b) * HV; };
+  uint4 a0[T::FI], b0[T::FJ], a1[T::FI], b1[T::FJ];
+  issue(0, 0, 1);
+  if (n_pairs > 1) {
+    issue(1, 2, 3);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kPairLoads) : "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __syncthreads();
+  read(a0, b0, lds);
+  int b = 0;   // buffer of the pair's first K-step
+  for (int j = 0; j < n_pairs; ++j) {
+    // K-step 2 j: operands in (a0, b0)
+    mma(a0, b0, 0, T::FI / 2);
+    __syncthreads();
+    if (j + 2 < n_pairs) issue(j + 2, b + 4 >= 5 ? b - 1 : b + 4, b);   // uniform branch
+    read(a1, b1, buf(b + 1));
+    mma(a0, b0, T::FI / 2, T::FI);
+    // K-step 2 j + 1: operands in (a1, b1)
+    mma(a1, b1, 0, T::FI / 2);
+    if (j + 1 < n_pairs) {
+      // pair j + 1 has landed (the loads of pair j + 2, if any, stay in flight)
+      if (j + 2 < n_pairs) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kPairLoads) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      read(a0, b0, buf(b + 2));
+    }
+    mma(a1, b1, T::FI / 2, T::FI);
+    b = b + 2 >= 5 ? b - 3 : b + 2;
+  }
+}
+
+template <typename T, typename BaseA, typename BaseB>
+__device__ __forceinline__ void run_mainloop(uint4 *lds, int n_stages, BaseA base_a, BaseB base_b,
+                                             const int (&off)[T::NOFF], f32x4 (&acc)[T::FI][T::FJ], int a_lo, int a_hi,
+                                             int wc) {
+  if constexpr (T::RING) gemm_mainloop_ring<T>(lds, n_stages, base_a, base_b, off, acc, a_lo, a_hi, wc);
+  else gemm_mainloop<T>(lds, n_stages, base_a, base_b, off, acc, a_lo, a_hi, wc);
 }
 
 // ------------------------------------------------------------------------------------------------ up
@@ -180,21 +299,21 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // is clamped: its column of the product comes from a valid row and is never stored.
   const int f0 = wave * T::WF;   // first fragment of each operand this wave loads
   const bool gate_wave = NM == 2 && f0 >= T::FA / 2;
-  int off[T::NL];
+  int off[T::NOFF];
 #pragma unroll
-  for (int i = 0; i < T::NL; ++i) {
-    const int h = i % 2, r = (lane >> 3) ^ h;                  // block of the fragment, row of the block
-    const int f = f0 + (i % (T::NL / 2)) / 2, rf = h * 8 + r;   // fragment, row of the fragment
-    int row;
-    if (i < T::NL / 2) row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
-    else row = min(t0 + f * 16 + rf, k - 1);
-    off[i] = row * d + ((lane & 7) ^ r) * 8;   // piece (j & 7) XOR r of the row's line
+  for (int i = 0; i < T::NOFF; ++i) {
+    bool is_b;
+    int f_rel, rf, piece;
+    load_role<T>(i, lane, is_b, f_rel, rf, piece);
+    const int f = f0 + f_rel;
+    const int row = is_b ? min(t0 + f * 16 + rf, k - 1) : j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
+    off[i] = row * d + piece * 8;
   }
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
   const uint16_t *xsel = xb + (size_t)c * k * d;
   // every tile of the launch reads the chunk's x: each starts at another stage of the
   // contraction, so that they do not all ask the L2 for the same lines at the same moment
-  const int n_st = d / T::TK, rot = (int)((blockIdx.x * 5u) % (unsigned)n_st);
+  const int n_st = d / T::TK, rot = (int)(((unsigned)item * 5u) % (unsigned)n_st);
   auto stage_of = [&](int st) { const int v = st + rot; return v >= n_st ? v - n_st : v; };
   auto base_a = [&](int st) { return wsel + (size_t)stage_of(st) * T::TK; };
   auto base_b = [&](int st) { return xsel + (size_t)stage_of(st) * T::TK; };
@@ -207,17 +326,29 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // this wave's A fragments: gated: FI/2 up fragments and the FI/2 matching gate fragments
   const int a_lo = NM == 2 ? wr * (T::FI / 2) : wr * T::FI;
   const int a_hi = NM == 2 ? T::FA / 2 + wr * (T::FI / 2) : wr * T::FI + T::FI / 2;
-  gemm_mainloop<T>(lds, d / T::TK, base_a, base_b, off, acc, a_lo, a_hi, wc);
+  // score and mask bit of this lane's tokens: requested before the contraction so that the
+  // epilogue does not start with a round trip to memory
+  const int n = lane & 15;
+  float f_tok[T::FJ];
+#pragma unroll
+  for (int j = 0; j < T::FJ; ++j) {
+    const int t = t0 + (wc * T::FJ + j) * 16 + n;
+    f_tok[j] = 0.0f;
+    if (t < k) {
+      const int64_t tok = c * k + t;
+      const bool on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
+      f_tok[j] = on ? scores[tok * E + e] : 0.0f;
+    }
+  }
+  run_mainloop<T>(lds, d / T::TK, base_a, base_b, off, acc, a_lo, a_hi, wc);
 
   // D[i = neuron 4g + q of the fragment][j = token n of the fragment]
-  const int n = lane & 15;
 #pragma unroll
   for (int j = 0; j < T::FJ; ++j) {
     const int t = t0 + (wc * T::FJ + j) * 16 + n;
     if (t >= k) continue;
-    const int64_t tok = c * k + t;
-    const bool on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
-    const float f = scores[tok * E + e];
+    const bool on = f_tok[j] != 0.0f;   // a masked term, and one scaled by a zero score, store +0
+    const float f = f_tok[j];
     constexpr int kOut = T::FI / NM;
 #pragma unroll
     for (int i = 0; i < kOut; ++i) {
@@ -225,7 +356,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const float u = acc[i][j][q];
-        const float h = NM == 2 ? swish(acc[i + (NM - 1) * kOut][j][q]) * u : swish(u);
+        const float h = NM == 2 ? swish_fast(acc[i + (NM - 1) * kOut][j][q]) * u : swish_fast(u);
         p[q] = bf16_bits(on ? f * h : 0.0f);
       }
       const int neuron = j0 + (wr * kOut + i) * 16 + 4 * g;
@@ -265,13 +396,15 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   // A fragment f: W_down rows col0 + 16 f of the stage's expert; B fragment f: mid rows of tokens
   // t0 + 16 f (clamped as in the up kernel) of the stage's slot.
   const int f0 = wave * T::WF;   // first fragment of each operand this wave loads
-  int off[T::NL];
+  int off[T::NOFF];
 #pragma unroll
-  for (int i = 0; i < T::NL; ++i) {
-    const int h = i % 2, r = (lane >> 3) ^ h;                  // block of the fragment, row of the block
-    const int f = f0 + (i % (T::NL / 2)) / 2, rf = h * 8 + r;   // fragment, row of the fragment
-    const int row = i < T::NL / 2 ? col0 + f * 16 + rf : min(t0 + f * 16 + rf, k - 1);
-    off[i] = row * d_e + ((lane & 7) ^ r) * 8;
+  for (int i = 0; i < T::NOFF; ++i) {
+    bool is_b;
+    int f_rel, rf, piece;
+    load_role<T>(i, lane, is_b, f_rel, rf, piece);
+    const int f = f0 + f_rel;
+    const int row = is_b ? min(t0 + f * 16 + rf, k - 1) : col0 + f * 16 + rf;
+    off[i] = row * d_e + piece * 8;
   }
   auto base_a = [&](int st) -> const uint16_t * {
     const int s = s_lo + st / st_per_slot;
@@ -290,7 +423,7 @@ __global__ __launch_bounds__(T::THREADS) void down_gemm_kernel(
   for (int i = 0; i < T::FI; ++i)
 #pragma unroll
     for (int j = 0; j < T::FJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  gemm_mainloop<T>(lds, (s_hi - s_lo) * st_per_slot, base_a, base_b, off, acc, wr * T::FI, wr * T::FI + T::FI / 2, wc);
+  run_mainloop<T>(lds, (s_hi - s_lo) * st_per_slot, base_a, base_b, off, acc, wr * T::FI, wr * T::FI + T::FI / 2, wc);
 
   const int n = lane & 15;
   float *dst = out + (size_t)sp * split_stride;

@@ -36,8 +36,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void global_void_t;
 
 constexpr int kThreads = 256;
 constexpr int kRing = 16;          // 128-bit loads in flight per lane
@@ -532,8 +530,7 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       for (int q = 0; q < kPerThread; ++q) {
         const int idx = tid + q * kThreads;
         if (q * kThreads + wave * 64 < kStage)   // uniform over the wave (kStage is a multiple of 64)
-          __builtin_amdgcn_global_load_lds((global_void_t *)stage_src(s_stage, idx),
-                                           (lds_void_t *)(stage_dst + q * kThreads + wave * 64), 16, 0, 0);
+          load_to_lds16(stage_src(s_stage, idx), stage_dst + q * kThreads + wave * 64);
       }
       const char *cur = slot_ptr(e);
       const uint4 *bS = midS[(s - s_lo) & 1];
