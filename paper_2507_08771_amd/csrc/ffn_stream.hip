@@ -59,6 +59,12 @@ __device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) 
 constexpr int acc_tiles(int NB) { return NB == 4 ? 2 : 1; }
 constexpr int acc_of(int NB, int bf) { return NB == 4 ? bf / 2 : 0; }
 constexpr int tokens_of(int NB) { return NB == 1 ? 8 : (NB == 2 ? 16 : 32); }
+// Slots per item of the double-buffered up kernel: as many as keep the accumulators at 16 tiles
+// (NB = 4) or 8 tiles (more spilled), at most 4; with 1 the single-buffer kernel is used.
+constexpr int up_group(int NB, int RT, int NM) {
+  const int per_slot = RT * NM * acc_tiles(NB), cap = NB == 4 ? 16 : 8;
+  return cap / per_slot > 4 ? 4 : (cap / per_slot < 1 ? 1 : cap / per_slot);
+}
 
 // Flat work list: items[i] = chunk * E + slot for every `group`-th slot below n_active[chunk]
 // (an item stands for up to `group` consecutive slots of one chunk).
@@ -131,6 +137,82 @@ __global__ __launch_bounds__(kThreads) void split_x_kernel(const float *__restri
 }
 
 // ------------------------------------------------------------------------------------------------ up
+
+// Epilogue of one (chunk, slot), entirely inside the wave: lane (n = lane % 16, g) holds rows
+// 4g .. 4g + 3 of each tile.  Swish / gating, router score and mask bit; mid is written split into
+// bf16 hi/lo in the order the down kernel's B operand reads it.
+// Router score of this lane's token(s) for expert e, 0 where the mask bit is clear or the token is
+// past the chunk: what the epilogue multiplies with.
+template <int NB>
+__device__ __forceinline__ void up_scores(float (&f_tok)[acc_tiles(NB)], const LayerView &L,
+                                          const float *__restrict__ scores,
+                                          const uint64_t *__restrict__ token_mask, int64_t c, int e, int k, int lane) {
+  const int n = lane & 15;
+#pragma unroll
+  for (int q = 0; q < acc_tiles(NB); ++q) {
+    const int t = NB == 1 ? (n & 7) : q * 16 + n;
+    f_tok[q] = 0.0f;
+    if (t < k) {
+      const int64_t tok = c * k + t;
+      const bool on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
+      f_tok[q] = on ? scores[tok * L.E + e] : 0.0f;
+    }
+  }
+}
+
+template <int NB, int NM, int RT>
+__device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_tiles(NB)],
+                                              const float (&f_tok)[acc_tiles(NB)], const LayerView &L, int64_t c,
+                                              int s, int lane, int wave, uint16_t *__restrict__ midB) {
+  constexpr int NA = acc_tiles(NB);
+  const int E = L.E, d_e = L.d_e;
+  const int g = lane >> 4;
+  const int n = lane & 15;
+#pragma unroll
+  for (int q = 0; q < NA; ++q) {
+    const float f = f_tok[q];
+    const bool on = f != 0.0f;   // a masked term, and one with a zero score, store +0
+#pragma unroll
+    for (int rr = 0; rr < RT; ++rr) {
+      uint32_t phi[4], plo[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float u = acc[rr][0][q][j];
+        if (NB == 1) u += __shfl_xor(u, 8, kWave);
+        float h;
+        if (NM == 2) {
+          float gt = acc[rr][NM - 1][q][j];
+          if (NB == 1) gt += __shfl_xor(gt, 8, kWave);
+          h = swish(gt) * u;
+        } else {
+          h = swish(u);
+        }
+        split_bf16(on ? f * h : 0.0f, phi[j], plo[j]);
+      }
+      const uint2 vhi = make_uint2(phi[0] | phi[1] << 16, phi[2] | phi[3] << 16);
+      const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
+      const size_t col = (rr * 4 + wave) * 16 + 4 * g;
+      uint16_t *base = midB + ((size_t)c * E + s) * NB * 16 * d_e;
+      if (NB == 1) {
+        // fragment row n: hi for n < 8, lo of token n - 8 for n >= 8
+        *reinterpret_cast<uint2 *>(base + (size_t)n * d_e + col) = n < 8 ? vhi : vlo;
+      } else {
+        *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2) * 16 + n) * d_e + col) = vhi;
+        *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2 + 1) * 16 + n) * d_e + col) = vlo;
+      }
+    }
+  }
+}
+
+template <int NB, int NM, int RT>
+__device__ __forceinline__ void up_epilogue(const f32x4 (&acc)[RT][NM][acc_tiles(NB)], const LayerView &L,
+                                            const float *__restrict__ scores,
+                                            const uint64_t *__restrict__ token_mask, int64_t c, int s, int e, int k,
+                                            int lane, int wave, uint16_t *__restrict__ midB) {
+  float f_tok[acc_tiles(NB)];
+  up_scores<NB>(f_tok, L, scores, token_mask, c, e, k, lane);
+  up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB);
+}
 
 // NB: B fragments per K-step (see the top of the file); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
 // groups of the expert (d_e = 64 * RT).  Wave w owns row tiles rr*4 + w.
@@ -291,52 +373,216 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       }
     }
 
-    // epilogue, entirely inside the wave: lane (n = lane%16, g) holds rows 4g..4g+3 of each tile
-    const int n = lane & 15;
-#pragma unroll
-    for (int q = 0; q < NA; ++q) {
-      const int t = NB == 1 ? (n & 7) : q * 16 + n;
-      float f = 0.0f;
-      bool on = false;
-      if (t < k) {
-        const int64_t tok = c * k + t;
-        on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
-        f = scores[tok * E + e];
-      }
-#pragma unroll
-      for (int rr = 0; rr < RT; ++rr) {
-        uint32_t phi[4], plo[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float u = acc[rr][0][q][j];
-          if (NB == 1) u += __shfl_xor(u, 8, kWave);
-          float h;
-          if (NM == 2) {
-            float gt = acc[rr][NM - 1][q][j];
-            if (NB == 1) gt += __shfl_xor(gt, 8, kWave);
-            h = swish(gt) * u;
-          } else {
-            h = swish(u);
-          }
-          split_bf16(on ? f * h : 0.0f, phi[j], plo[j]);
-        }
-        const uint2 vhi = make_uint2(phi[0] | phi[1] << 16, phi[2] | phi[3] << 16);
-        const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
-        const size_t col = (rr * 4 + wave) * 16 + 4 * g;
-        uint16_t *base = midB + ((size_t)c * E + s) * NB * 16 * d_e;
-        if (NB == 1) {
-          // fragment row n: hi for n < 8, lo of token n - 8 for n >= 8
-          *reinterpret_cast<uint2 *>(base + (size_t)n * d_e + col) = n < 8 ? vhi : vlo;
-        } else {
-          *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2) * 16 + n) * d_e + col) = vhi;
-          *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2 + 1) * 16 + n) * d_e + col) = vlo;
-        }
-      }
-    }
+    up_epilogue<NB, NM, RT>(acc, L, scores, token_mask, c, s, e, k, lane, wave, midB);
 
     if (!has_next) break;
     item = next_item;
     c = c_n; s = s_n; ns = ns_n; e = e_n; layer = layer_n;
+  }
+}
+
+// Up projection for k > 8 with the chunk's split x double buffered in LDS.  A refill of the
+// single-buffer kernels costs two barriers at which the waves wait on memory while their weight
+// rings drain (about 5 us per refill, four refills per slot at d = 2048, k = 32).  Here LDS
+// holds two 32 KiB buffers of 1024 / NB contraction elements (FPT = 32 / NB K-steps); the buffer
+// of the next K-chunk is filled by LDS-direct loads issued when the current K-chunk starts, so
+// that at the K-chunk's end `s_waitcnt vmcnt(16)` (loads return in issue order, the 16 youngest
+// are the ring's) finds it landed, one barrier publishes it, and the ring never stops.
+// The weight stream's order is (item, K-chunk, slot, row tile, matrix, K-step); a cursor that
+// runs exactly 16 fragments (the ring) ahead of the consumer produces the prefetch addresses, so
+// it crosses tile, slot, K-chunk and item boundaries without special cases.  FPT is 8 or 16:
+// the cursor then changes tile exactly when the consumer does.  An item is up to G slots of one
+// chunk whose accumulators stay in registers across the K-chunks.
+template <int NB, int NM, int RT, int G>
+__global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
+    LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
+    const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
+    const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
+    int k, uint16_t *__restrict__ midB) {
+  static_assert(NB == 2 || NB == 4, "8 or 16 K-steps per buffer");
+  constexpr int FPT = 32 / NB;            // K-steps (fragments of one tile) per K-chunk
+  constexpr int KB = 32 * FPT;            // contraction elements per buffer
+  constexpr int kBuf = FPT * NB * 64;     // uint4 per buffer (2048 = 32 KiB)
+  constexpr int TPS = RT * NM;            // tiles per slot and K-chunk
+  static_assert(FPT == 16 || TPS % 2 == 0, "with 8 fragments per tile the ring half must follow from (rr, m)");
+  constexpr int NA = acc_tiles(NB);
+  extern __shared__ uint4 xB[];           // [2][K-step][NB][64 lanes]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int E = L.E, d = L.d, d_e = L.d_e;
+  const int total = *total_ptr;
+  const size_t row_bytes = (size_t)d * 2;
+  const int nkc = d / KB;
+
+  auto slot_expert = [&](int64_t c, int s) {
+    const int e = active_idx ? active_idx[c * E + s] : s;
+    return min(max(e, 0), E - 1);
+  };
+  auto item_decode = [&](int item, int64_t &c, int &s, int &ns) {
+    const int code = items[item];   // chunk * E + first slot
+    c = code / E;
+    s = code - (int)c * E;
+    const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
+    ns = max(1, min(G, n_act - s));
+  };
+  // per-lane byte pointer to fragment 0 of tile t = rr * NM + m of (layer, expert)
+  auto tile_ptr = [&](int layer, int e, int t) -> const char * {
+    const int rr = t / NM, m = t % NM;
+    const char *w = static_cast<const char *>(m == 0 ? L.w_up : L.w_gate);
+    const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + r;
+    return w + row * row_bytes + g * 16;
+  };
+  // The experts of an item's slots are kept as bytes of one word (E <= 256): indexed by a run-time
+  // slot, an array of them is moved to scratch memory by the compiler, and the load from there
+  // waits for every outstanding weight load.
+  static_assert(G <= 4 && kMaxExperts <= 256, "four expert ids in 32 bits");
+  auto pick = [&](uint32_t v, int sl) { return (int)((v >> (8 * sl)) & 0xffu); };
+  auto slots_experts = [&](int64_t c, int s0, int ns) {
+    uint32_t v = 0;
+#pragma unroll
+    for (int sl = 0; sl < G; ++sl) v |= (uint32_t)slot_expert(c, s0 + min(sl, ns - 1)) << (8 * sl);
+    return v;   // slots past ns repeat the last one and are never used
+  };
+  // LDS-direct fill of one buffer: 32 KiB, 8 loads per wave
+  auto fill = [&](int64_t c, int kc, int buf) {
+    const uint4 *src = xS + ((size_t)c * (d / 32) + (size_t)kc * FPT) * NB * 64 + wave * (kBuf / 4) + lane;
+    uint4 *dst = xB + buf * kBuf + wave * (kBuf / 4);
+#pragma unroll
+    for (int j = 0; j < kBuf / 4 / 64; ++j) load_to_lds16(src + j * 64, dst + j * 64);
+  };
+
+  // Workgroup b runs on XCD b mod 8 and each XCD has its own L2.  The items of a chunk all read
+  // the chunk's split x (256 KiB at k = 32), so consecutive items go to the workgroups of ONE XCD:
+  // step j of workgroup (xcd, w) takes item ((j * 8 + xcd) * per_xcd + w), and x is served by that
+  // L2 instead of crossing the fabric once per item.
+  const int per_xcd = gridDim.x / 8;   // the launcher makes the grid a multiple of 8
+  const int item_step = 8 * per_xcd;
+  int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (item >= total) return;
+  int64_t c;
+  int s0, ns;
+  item_decode(item, c, s0, ns);
+  int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  uint32_t es = slots_experts(c, s0, ns);
+
+  // next item (valid while has_next) and the prefetch cursor
+  bool has_next = false;
+  int64_t c_n = c;
+  int s0_n = 0, ns_n = 1, layer_n = layer;
+  uint32_t esn = es;
+  auto decode_next = [&](int next_item) {
+    has_next = next_item < total;
+    if (has_next) {
+      item_decode(next_item, c_n, s0_n, ns_n);
+      layer_n = clamp_layer(chunk_layer, c_n, L.n_layers);
+      esn = slots_experts(c_n, s0_n, ns_n);
+    }
+  };
+  decode_next(item + item_step);
+
+  bool cu_next = false;          // the cursor is in the next item
+  int cu_kc = 0, cu_sl = 0, cu_t = 0;
+  const char *cu_ptr = tile_ptr(layer, pick(es, 0), 0);
+  // To the next tile of the stream.  All of this is uniform over the wave and written without
+  // branches: control flow between two tiles makes the compiler's counted waits for the ring's
+  // loads collapse to "wait for everything" at the join.
+  auto cu_advance = [&]() {
+    const int nsl = cu_next ? ns_n : ns;
+    const bool wrap_t = cu_t + 1 == TPS;
+    const int t = wrap_t ? 0 : cu_t + 1;
+    const bool wrap_s = wrap_t && cu_sl + 1 == nsl;
+    const int sl = wrap_s ? 0 : cu_sl + (wrap_t ? 1 : 0);
+    const bool wrap_k = wrap_s && cu_kc + 1 == nkc;
+    const int kc = wrap_k ? 0 : cu_kc + (wrap_s ? 1 : 0);
+    const bool to_next = wrap_k && !cu_next && has_next;
+    const bool stay = wrap_k && !to_next;   // nothing follows: stay on the last tile (its loads are never used)
+    cu_kc = stay ? nkc - 1 : kc;
+    cu_sl = stay ? nsl - 1 : sl;
+    cu_t = stay ? TPS - 1 : t;
+    cu_next = cu_next || to_next;
+    cu_ptr = tile_ptr(cu_next ? layer_n : layer, cu_next ? pick(esn, cu_sl) : pick(es, cu_sl), cu_t) +
+             (size_t)cu_kc * (KB * 2);
+  };
+
+  // prologue: x of the first K-chunk, then the ring's first 16 fragments
+  fill(c, 0, 0);
+  uint4 ring[kRing];
+#pragma unroll
+  for (int h = 0; h < kRing / FPT; ++h) {
+#pragma unroll
+    for (int i = 0; i < FPT; ++i) ring[h * FPT + i] = *reinterpret_cast<const uint4 *>(cu_ptr + i * 64);
+    cu_advance();
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");   // the fill is older than the ring's loads
+  __syncthreads();
+  int par = 0;   // buffer of the current K-chunk
+
+  while (true) {
+    f32x4 acc[G][RT][NM][NA];
+#pragma unroll
+    for (int sl = 0; sl < G; ++sl)
+#pragma unroll
+      for (int a = 0; a < RT; ++a)
+#pragma unroll
+        for (int m = 0; m < NM; ++m)
+#pragma unroll
+          for (int q = 0; q < NA; ++q) acc[sl][a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the epilogue's scores are requested now: a load issued there would return behind the
+    // ring's and stop the stream for a memory round trip
+    float f_tok[G][NA];
+#pragma unroll
+    for (int sl = 0; sl < G; ++sl) {
+#pragma unroll
+      for (int q = 0; q < NA; ++q) f_tok[sl][q] = 0.0f;
+      if (sl < ns) up_scores<NB>(f_tok[sl], L, scores, token_mask, c, pick(es, sl), k, lane);
+    }
+
+    for (int kc = 0; kc < nkc; ++kc) {
+      // x of the K-chunk that follows goes into the other buffer (every wave left it at the last barrier)
+      const bool last_kc = kc + 1 == nkc;
+      if (!last_kc) fill(c, kc + 1, par ^ 1);
+      else if (has_next) fill(c_n, 0, par ^ 1);
+      const uint4 *xb = xB + par * kBuf;
+#pragma unroll
+      for (int sl = 0; sl < G; ++sl) {
+        if (sl >= ns) break;   // uniform over the workgroup
+#pragma unroll
+        for (int rr = 0; rr < RT; ++rr) {
+#pragma unroll
+          for (int m = 0; m < NM; ++m) {
+            constexpr int kHalves = kRing / FPT;   // tiles the ring holds
+            const int r0 = kHalves == 1 ? 0 : ((rr * NM + m) % kHalves) * FPT;
+#pragma unroll
+            for (int i = 0; i < FPT; ++i) {
+#pragma unroll
+              for (int bf = 0; bf < NB; ++bf) {
+                const uint4 b = xb[(i * NB + bf) * 64 + lane];
+                acc[sl][rr][m][acc_of(NB, bf)] = mfma16(ring[r0 + i], b, acc[sl][rr][m][acc_of(NB, bf)]);
+              }
+              ring[r0 + i] = *reinterpret_cast<const uint4 *>(cu_ptr + i * 64);
+              // keep the refill here: left alone, the scheduler sinks the loads to the end of the tile
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            cu_advance();
+          }
+        }
+      }
+      // the next buffer has landed (it is older than the ring's 16 outstanding loads); publish it
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");
+      __syncthreads();
+      par ^= 1;
+    }
+
+#pragma unroll
+    for (int sl = 0; sl < G; ++sl)
+      if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB);
+
+    if (!has_next) break;
+    item += item_step;
+    c = c_n; s0 = s0_n; ns = ns_n; layer = layer_n;
+    es = esn;
+    cu_next = false;   // the cursor was in this item already (an item is longer than the ring)
+    decode_next(item + item_step);
   }
 }
 
@@ -609,6 +855,25 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4
   return hipGetLastError();
 }
 
+template <int NB, int NM, int RT, int G>
+hipError_t launch_up_db(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
+                        const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
+                        const int32_t *items, const int32_t *total, int64_t max_items, int k, uint16_t *midB,
+                        hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = up_stream_db_kernel<NB, NM, RT, G>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kXBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
+                     active_idx, n_active, items, total, k, midB);
+  return hipGetLastError();
+}
+
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const float *__restrict__ part, int splits,
                                                                    size_t split_stride, size_t n4,
                                                                    float *__restrict__ y) {
@@ -734,7 +999,12 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   }
   // Two slots per item when the whole contraction of x fits in LDS: the 64 KiB of x are then
   // fetched and split once per 2 experts.  (With more K-chunks LDS is refilled per K-chunk anyway.)
-  const int group = (L.d <= 2048 / NB) ? 2 : 1;
+  // k > 8 with more than one LDS fill per slot: the double-buffered kernel, where the accumulators
+  // of more than one slot fit in registers (otherwise it has nothing over the single buffer).
+  // 8 fragments per tile (k > 16) need an even number of tiles per slot.
+  const int nm = gated ? 2 : 1;
+  const bool use_db = L.d > 2048 / NB && (NB == 2 || (NB == 4 && (RT * nm) % 2 == 0)) && up_group(NB, RT, nm) > 1;
+  const int group = use_db ? up_group(NB, RT, nm) : (L.d <= 2048 / NB ? 2 : 1);
   hipError_t err = launch_worklist(n_active, n_chunks, L.E, group, w.items, w.total, s);
   if (err != hipSuccess) return err;
   {
@@ -751,9 +1021,14 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
     if (err != hipSuccess) return err;
   }
 #define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
-  if (NB == nb && (gated ? 2 : 1) == nm && RT == rt)                                                      \
+  if (NB == nb && (gated ? 2 : 1) == nm && RT == rt) {                                                    \
+    if constexpr ((nb == 2 || (nb == 4 && (rt * nm) % 2 == 0)) && up_group(nb, rt, nm) > 1)               \
+      if (use_db)                                                                                         \
+        return launch_up_db<nb, nm, rt, up_group(nb, rt, nm)>(L, chunk_layer, w.xS, scores, token_mask, active_idx, \
+                                                              n_active, w.items, w.total, max_items, k, w.midB, s); \
     return launch_up<nb, nm, rt>(L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, \
-                                 group, max_items, k, w.midB, s);
+                                 group, max_items, k, w.midB, s);                                         \
+  }
   BLOCKFFN_CASE(1, 1, 1) BLOCKFFN_CASE(1, 1, 2) BLOCKFFN_CASE(1, 1, 4)
   BLOCKFFN_CASE(1, 2, 1) BLOCKFFN_CASE(1, 2, 2) BLOCKFFN_CASE(1, 2, 4)
   BLOCKFFN_CASE(2, 1, 1) BLOCKFFN_CASE(2, 1, 2) BLOCKFFN_CASE(2, 1, 4)
