@@ -204,16 +204,6 @@ __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_til
   }
 }
 
-template <int NB, int NM, int RT>
-__device__ __forceinline__ void up_epilogue(const f32x4 (&acc)[RT][NM][acc_tiles(NB)], const LayerView &L,
-                                            const float *__restrict__ scores,
-                                            const uint64_t *__restrict__ token_mask, int64_t c, int s, int e, int k,
-                                            int lane, int wave, uint16_t *__restrict__ midB) {
-  float f_tok[acc_tiles(NB)];
-  up_scores<NB>(f_tok, L, scores, token_mask, c, e, k, lane);
-  up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB);
-}
-
 // NB: B fragments per K-step (see the top of the file); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
 // groups of the expert (d_e = 64 * RT).  Wave w owns row tiles rr*4 + w.
 template <int NB, int NM, int RT>
@@ -296,6 +286,10 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       for (int m = 0; m < NM; ++m)
 #pragma unroll
         for (int q = 0; q < NA; ++q) acc[a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the epilogue's scores are requested now: a load issued there would return behind the
+    // ring's and stop the stream for a memory round trip
+    float f_tok[NA];
+    up_scores<NB>(f_tok, L, scores, token_mask, c, e, k, lane);
 
     for (int kc0 = 0; kc0 < d; kc0 += KC) {
       const int kc_len = min(KC, d - kc0);
@@ -373,7 +367,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       }
     }
 
-    up_epilogue<NB, NM, RT>(acc, L, scores, token_mask, c, s, e, k, lane, wave, midB);
+    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB);
 
     if (!has_next) break;
     item = next_item;
@@ -560,7 +554,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
                 acc[sl][rr][m][acc_of(NB, bf)] = mfma16(ring[r0 + i], b, acc[sl][rr][m][acc_of(NB, bf)]);
               }
               ring[r0 + i] = *reinterpret_cast<const uint4 *>(cu_ptr + i * 64);
-              // keep the refill here: left alone, the scheduler sinks the loads to the end of the tile
+              // keep the refill here: left alone, the scheduler moves the loads of a tile together and
+              // this kernel loses 10 % (the single-buffer kernel, oddly, is 1-5 % better left alone)
               __builtin_amdgcn_sched_barrier(0);
             }
             cu_advance();

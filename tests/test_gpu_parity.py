@@ -62,6 +62,9 @@ def impl(request, monkeypatch):
     (3072, 40, 256, 12, 3),   # two token tiles, three K-chunks
     (1024, 48, 256, 32, 3),   # four token tiles, two K-chunks of 512
     (2560, 64, 256, 24, 2),   # four token tiles with a ragged last one, five K-chunks
+    (2048, 64, 128, 32, 3),   # k = 32 at d_e = 128: double-buffered x, items of 2 (gated) or 4 slots
+    (2048, 64, 64, 24, 3),    # d_e = 64: one row tile per wave (gated: two tiles per slot, items of 4)
+    (2048, 48, 128, 16, 3),   # k = 16 at d_e = 128: 16 fragments per tile and buffer
     (512, 256, 64, 8, 5),     # the most experts: four full mask words, 16 router row tiles
     (256, 8, 1024, 4, 2),     # the widest expert
     (16384, 4, 8, 2, 2),      # the longest hidden size
