@@ -254,22 +254,34 @@ def main():
 
     # dense FFN of equal parameter count: same kernels, every expert, no masks
     dense_ms = None
-    if args.dense_steps > 0 and not args.sequential:
-        B.blockffn_dense_ffn(L, x, buf.scores, C, k, y_dense, buf.workspace, chunk_layer)
+
+    def dense_step():
+        if not args.sequential:
+            B.blockffn_dense_ffn(L, x, buf.scores, C, k, y_dense, buf.workspace, chunk_layer)
+            return
+        for c in range(C):   # the dense layer stack: router, then every expert of the layer
+            t0_, t1_ = c * k, (c + 1) * k
+            cl = chunk_layer[c:c + 1]
+            B.blockffn_router(L, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], cl)
+            B.blockffn_dense_ffn(L, x[t0_:t1_], buf.scores[t0_:t1_], 1, k, y_dense[t0_:t1_], buf.workspace, cl)
+
+    if args.dense_steps > 0:
+        dense_step()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(args.dense_steps):
-            B.blockffn_dense_ffn(L, x, buf.scores, C, k, y_dense, buf.workspace, chunk_layer)
+            dense_step()
         e1.record()
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1) / args.dense_steps
     ffn_ms = (stage_us["up"] + stage_us["down"]) / 1e3
+    if args.sequential:   # whole steps on both sides (router included): there is no per-kernel split here
+        ffn_ms = ms_per_step
 
     up_s = stage_us["up"] * 1e-6
     if args.sequential:   # no per-kernel split in this mode: price the whole step against all active bytes
         up_s, up_bytes = ms_per_step * 1e-3, active_bytes
-        args.dense_steps = 0
     out = {
         "metric": "µs/chunk + active-weight HBM GB/s (%% peak) at k=%d; speedup vs dense FFN" % k,
         "value": active_bytes / (ms_per_step * 1e-3) / 1e9,
