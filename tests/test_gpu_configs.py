@@ -71,6 +71,35 @@ def test_paper_shape_table11_sparsity_levels():
     assert abs((1 - wl.expected_sparsity(w.k, w.sigma, w.p_active)[1]) - 0.3086) < 1e-4
 
 
+def test_prefill_512_eight_chunks_through_eight_weight_sets():
+    """The 512-token prefill chunk in the launch configuration the benchmark times: 8 chunks, each
+    through its own weight set, on the matrix-core path (tiles that share an expert's weights
+    run side by side on one XCD, items rotate their start in the contraction).  Two chunks are
+    checked in full against the oracle; integers and union properties on all of them."""
+    w = wl.WORKLOADS["stack_prefill_512"].replace(n_chunks=8)
+    n_layers = 8
+    layers = wl.make_layers(w, n_layers, device="cuda")
+    cl = wl.make_chunk_layer(w, n_layers, device="cuda")
+    x = wl.make_tokens(w, layers, cl, device="cuda")
+    print("generated", flush=True)
+    gpu = pu.run_gpu(layers, x, w.k, cl, dense=False)
+    chunks = [0, 5]
+    layers_cpu = {n: (None if t is None else t.cpu()) for n, t in layers.items()}
+    ref = pu.run_oracle(layers_cpu, x.cpu(), w.k, cl.cpu(), dense=False, chunks=chunks)
+    pu.assert_integers_equal(gpu, ref, chunks=chunks, k=w.k)
+    rows = (np.asarray(chunks)[:, None] * w.k + np.arange(w.k)[None, :]).reshape(-1)
+    print(pu.assert_floats_close(gpu, ref, "bf16", rows=rows, bar=pu.GEMM_BAR, l2_bar=pu.GEMM_L2_BAR))
+    C, E, W = w.n_chunks, w.E, w.mask_words
+    np.testing.assert_array_equal(popcount_rows(gpu["union_mask"]), gpu["n_active"])
+    tm = gpu["token_mask"].reshape(C, w.k, W)
+    np.testing.assert_array_equal(np.bitwise_or.reduce(tm, axis=1), gpu["union_mask"])
+    assert gpu["n_active"].min() >= E - 2          # 64 groups of 8 tokens: the union is all but dense
+    assert np.isfinite(gpu["y"]).all()
+    none_active = popcount_rows(gpu["token_mask"]) == 0
+    assert np.all(gpu["y"][none_active] == 0)
+    assert np.all(np.abs(gpu["y"][~none_active]).max(axis=1) > 0)
+
+
 def test_stack_decode_24_layers_chained():
     """24 layers, one k = 8 chunk walking through them: x_{l+1} = (x_l + y_l) rescaled per token to
     the rms of x_0 (stands in for the attention and norms between FFNs).  Every layer is checked
