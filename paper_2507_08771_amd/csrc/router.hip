@@ -6,8 +6,9 @@
 //
 // router_mfma_kernel (bf16 weights, enough token tiles to fill the chip): x is carried as three
 // bf16 pieces that add up to the fp32 value exactly, and the matrix cores do the contraction.
-// router_kernel (fp32 weights, and launches of a few tiles, where blockIdx.y spreads the expert
-// groups over workgroups): vector ALUs.  Each lane keeps its 8 columns of the 8 tokens in
+// router_kernel (fp32 weights, and launches of tens of tiles, where blockIdx.y spreads the expert
+// groups over workgroups; a handful of tiles take router_expert_kernel, one workgroup per
+// expert): vector ALUs.  Each lane keeps its 8 columns of the 8 tokens in
 // registers (64 VGPRs) and walks over the experts: one 128-bit load of a W_router row segment
 // feeds 64 fp32 FMAs; partial sums of 8 experts x 8 tokens are reduced across the wave with a
 // 63-step reduce-scatter (lane q ends with entry q).
@@ -178,6 +179,57 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
   finish_tile(L, layer, part, tok0, nt, scores, token_mask, preact);
 }
 
+// A handful of token tiles (one chunk walking through a layer stack): one workgroup per (tile,
+// expert), so that E workgroups pull the router matrix instead of E / 8.  Each thread takes 8
+// columns of the expert's row and of the tile's tokens; the partial sums meet by wave reduction
+// and a four-entry LDS step.  Writes A^0 (+ bias) into `scores`; router_finish_kernel normalises.
+template <typename WT>
+__global__ __launch_bounds__(kThreads) void router_expert_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
+                                                                 const float *__restrict__ x, int k,
+                                                                 int tiles_per_chunk, float *__restrict__ scores) {
+  __shared__ float part[4][kTok];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t c = blockIdx.x / tiles_per_chunk;
+  const int t0 = (int)(blockIdx.x % tiles_per_chunk) * kTok;
+  const int nt = min(kTok, k - t0);
+  const int64_t tok0 = c * (int64_t)k + t0;
+  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  const int d = L.d, E = L.E, e = blockIdx.y;
+  const size_t w_row = ((size_t)layer * E + e) * d;
+  float acc[kTok];
+#pragma unroll
+  for (int t = 0; t < kTok; ++t) acc[t] = 0.0f;
+  for (int cb = 0; cb < d; cb += kColsPerBlock) {
+    const int col = cb + tid * 8;
+    if (col < d) {
+      float w[8];
+      load8<WT>(L.w_router, w_row + col, w);
+#pragma unroll
+      for (int t = 0; t < kTok; ++t) {
+        if (t < nt) {
+          const float4 *p = reinterpret_cast<const float4 *>(x + (tok0 + t) * d + col);
+          const float4 a = p[0], b = p[1];
+          float s = acc[t];
+          s = fmaf(w[0], a.x, s); s = fmaf(w[1], a.y, s); s = fmaf(w[2], a.z, s); s = fmaf(w[3], a.w, s);
+          s = fmaf(w[4], b.x, s); s = fmaf(w[5], b.y, s); s = fmaf(w[6], b.z, s); s = fmaf(w[7], b.w, s);
+          acc[t] = s;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < kTok; ++t) {
+    const float v = wave_sum(acc[t]);
+    if (lane == 0) part[wave][t] = v;
+  }
+  __syncthreads();
+  if (tid < nt) {
+    float a0 = L.b_router ? L.b_router[(size_t)layer * E + e] : 0.0f;
+    a0 += (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]);
+    scores[(tok0 + tid) * E + e] = a0;
+  }
+}
+
 // bf16 weights, many token tiles: the same contraction on the matrix cores without giving up
 // fp32 products.  An fp32 x is the exact sum of three bf16 numbers (24 significant bits in
 // three pieces of 8: h = bf16(x), m = bf16(x - h), l = x - h - m), and a bf16 piece times a bf16
@@ -329,14 +381,23 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
   dim3 block(kThreads);
   const int n_groups = (L.E + 7) / 8;
   if (blocks * 2 <= 256 && n_groups > 1) {
-    // few token tiles: spread the expert groups over workgroups, then normalise
-    dim3 grid((unsigned)blocks, (unsigned)n_groups);
-    if (wdtype == BLOCKFFN_BF16)
-      hipLaunchKernelGGL((router_kernel<bf16_t, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
-                         preact);
-    else
-      hipLaunchKernelGGL((router_kernel<float, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
-                         preact);
+    // few token tiles: spread the experts (or, with many tiles and experts, groups of 8 of them)
+    // over workgroups, then normalise
+    if (blocks * L.E <= 4096) {
+      dim3 grid((unsigned)blocks, (unsigned)L.E);
+      if (wdtype == BLOCKFFN_BF16)
+        hipLaunchKernelGGL((router_expert_kernel<bf16_t>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores);
+      else
+        hipLaunchKernelGGL((router_expert_kernel<float>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores);
+    } else {
+      dim3 grid((unsigned)blocks, (unsigned)n_groups);
+      if (wdtype == BLOCKFFN_BF16)
+        hipLaunchKernelGGL((router_kernel<bf16_t, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores,
+                           token_mask, preact);
+      else
+        hipLaunchKernelGGL((router_kernel<float, true>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores,
+                           token_mask, preact);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const int64_t n_tok = n_chunks * k;
