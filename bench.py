@@ -202,15 +202,21 @@ def main():
     C, k = w.n_chunks, w.k
     stages = ("router", "union", "up", "down")
 
+    # sequential mode: the way a model calls the library, one layer descriptor per layer (views
+    # of the stacked weights) and no per-chunk layer table for the kernels to look up
+    layer_of = chunk_layer.cpu().tolist()
+    views = ([B.Layer.from_dict({n: (None if t is None else t[r:r + 1]) for n, t in layers.items()}, gain=False)
+              for r in range(R)] if args.sequential else None)
+
     def step_sequential():
         for c in range(C):
             t0_, t1_ = c * k, (c + 1) * k
-            cl = chunk_layer[c:c + 1]
-            B.blockffn_router(L, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], cl)
+            Lc = views[layer_of[c]]
+            B.blockffn_router(Lc, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_])
             B.blockffn_chunk_union(buf.token_mask[t0_:t1_], 1, k, L.E, buf.union_mask[c:c + 1], buf.active_idx[c:c + 1],
                                    buf.n_active[c:c + 1], buf.stats)
-            B.blockffn_sparse_ffn(L, x[t0_:t1_], buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], buf.active_idx[c:c + 1],
-                                  buf.n_active[c:c + 1], 1, k, buf.y[t0_:t1_], buf.workspace, cl)
+            B.blockffn_sparse_ffn(Lc, x[t0_:t1_], buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], buf.active_idx[c:c + 1],
+                                  buf.n_active[c:c + 1], 1, k, buf.y[t0_:t1_], buf.workspace)
 
     def step(ev=None):
         if args.sequential:
@@ -261,9 +267,9 @@ def main():
             return
         for c in range(C):   # the dense layer stack: router, then every expert of the layer
             t0_, t1_ = c * k, (c + 1) * k
-            cl = chunk_layer[c:c + 1]
-            B.blockffn_router(L, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], cl)
-            B.blockffn_dense_ffn(L, x[t0_:t1_], buf.scores[t0_:t1_], 1, k, y_dense[t0_:t1_], buf.workspace, cl)
+            Lc = views[layer_of[c]]
+            B.blockffn_router(Lc, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_])
+            B.blockffn_dense_ffn(Lc, x[t0_:t1_], buf.scores[t0_:t1_], 1, k, y_dense[t0_:t1_], buf.workspace)
 
     if args.dense_steps > 0:
         dense_step()
