@@ -695,8 +695,8 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
 template <int NB, int KSD, int MW, int RING>
 __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ n_active, int k, int col_blocks, int splits, const uint16_t *__restrict__ midB,
-    float *__restrict__ out, size_t split_stride) {
+    const int32_t *__restrict__ n_active, int64_t n_chunks, int k, int col_blocks, int splits,
+    const uint16_t *__restrict__ midB, float *__restrict__ out, size_t split_stride) {
   constexpr int kFrag = KSD * MW;             // weight fragments per slot and wave
   static_assert(kFrag % RING == 0, "ring must divide the fragments of a slot");
   constexpr int kStage = KSD * NB * 64;       // uint4 of mid per slot
@@ -708,10 +708,18 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   const int r = lane & 15, g = lane >> 4;
   const int E = L.E, d = L.d;
   constexpr int d_e = KSD * 32;
-  const int sp = (int)(blockIdx.x % splits);
-  const int64_t cb = blockIdx.x / splits;
-  const int64_t c = cb / col_blocks;
-  const int col0 = (int)(cb % col_blocks) * (4 * MW * 16) + wave * (MW * 16);
+  // Every workgroup of a chunk stages the chunk's whole mid (16 NB rows of d_e per slot): spread
+  // over the XCDs, as consecutive block ids are, the col_blocks x splits workgroups of a chunk each
+  // pulled it through the fabric (at k = 32, d_e = 128: 64 KiB of mid per 512 KiB of W_down, 12 %
+  // on top of the weight bytes).  Block v runs on XCD v mod 8, so a chunk's workgroups get ids
+  // that differ by multiples of 8 and share the mid in one L2.
+  const int per_chunk = col_blocks * splits;
+  const int64_t q = blockIdx.x >> 3;
+  const int64_t c = (q / per_chunk) * 8 + (blockIdx.x & 7);
+  if (c >= n_chunks) return;   // the grid is rounded up to 8 chunks
+  const int within = (int)(q % per_chunk);
+  const int sp = within % splits;
+  const int col0 = (within / splits) * (4 * MW * 16) + wave * (MW * 16);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
   const int s_lo = (int)((int64_t)n_act * sp / splits), s_hi = (int)((int64_t)n_act * (sp + 1) / splits);
@@ -901,17 +909,17 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
   if (splits == 0) {
     constexpr int MW = (NB == 4 && KSD >= 8) ? 4 : 8;   // 8 row tiles x 2 accumulator tiles do not fit beside 64 fragments of addresses
     const int col_blocks = L.d / (4 * MW * 16);
-    const int64_t grid = n_chunks * col_blocks;
+    const int64_t grid = (n_chunks + 7) / 8 * 8 * col_blocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, kRing>), dim3((unsigned)grid), dim3(kThreads), 0, s, L,
-                       chunk_layer, active_idx, n_active, k, col_blocks, 1, midB, y, stride);
+                       chunk_layer, active_idx, n_active, n_chunks, k, col_blocks, 1, midB, y, stride);
     return hipGetLastError();
   }
   constexpr int MW = 8 / KSD;
   const int col_blocks = L.d / (4 * MW * 16);
-  const int64_t grid = n_chunks * col_blocks * splits;
+  const int64_t grid = (n_chunks + 7) / 8 * 8 * col_blocks * splits;
   hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
-                     active_idx, n_active, k, col_blocks, splits, midB, splits > 1 ? part : y, stride);
+                     active_idx, n_active, n_chunks, k, col_blocks, splits, midB, splits > 1 ? part : y, stride);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || splits == 1) return err;
   const size_t n4 = stride / 4;
