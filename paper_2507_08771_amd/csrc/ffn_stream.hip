@@ -151,28 +151,46 @@ __global__ __launch_bounds__(kThreads) void split_x_kernel(const float *__restri
 
 // ------------------------------------------------------------------------------------------------ up
 
-// Epilogue of one (chunk, slot), entirely inside the wave: lane (n = lane % 16, g) holds rows
-// 4g .. 4g + 3 of each tile.  Swish / gating, router score and mask bit; mid is written split into
-// bf16 hi/lo in the order the down kernel's B operand reads it.
 // Router score of this lane's token(s) for expert e, 0 where the mask bit is clear or the token is
-// past the chunk: what the epilogue multiplies with.
+// past the chunk: what the epilogue multiplies with.  Requested when the slot starts (a load issued
+// in the epilogue would return behind the ring's and stop the stream for a memory round trip).
+// The loads are unconditional (a token past the chunk reads the chunk's last token) and nothing
+// is done with what they return until up_scores_finish(), just before the epilogue: a use here
+// would wait for the load, and with it for every weight load of the ring that is in flight.
 template <int NB>
-__device__ __forceinline__ void up_scores(float (&f_tok)[acc_tiles(NB)], const LayerView &L,
-                                          const float *__restrict__ scores,
+struct ScoreRaw {
+  float score[acc_tiles(NB)];
+  uint64_t mask[acc_tiles(NB)];
+};
+
+template <int NB>
+__device__ __forceinline__ void up_scores(ScoreRaw<NB> &raw, const LayerView &L, const float *__restrict__ scores,
                                           const uint64_t *__restrict__ token_mask, int64_t c, int e, int k, int lane) {
   const int n = lane & 15;
 #pragma unroll
   for (int q = 0; q < acc_tiles(NB); ++q) {
-    const int t = NB == 1 ? (n & 7) : q * 16 + n;
-    f_tok[q] = 0.0f;
-    if (t < k) {
-      const int64_t tok = c * k + t;
-      const bool on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
-      f_tok[q] = on ? scores[tok * L.E + e] : 0.0f;
-    }
+    const int t = min(NB == 1 ? (n & 7) : q * 16 + n, k - 1);
+    const int64_t tok = c * k + t;
+    raw.mask[q] = token_mask ? token_mask[tok * L.W + (e >> 6)] : ~0ull;
+    raw.score[q] = scores[tok * L.E + e];
   }
 }
 
+template <int NB>
+__device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], const ScoreRaw<NB> &raw, int e, int k,
+                                                 int lane) {
+  const int n = lane & 15;
+#pragma unroll
+  for (int q = 0; q < acc_tiles(NB); ++q) {
+    const int t = NB == 1 ? (n & 7) : q * 16 + n;
+    const bool on = t < k && ((raw.mask[q] >> (e & 63)) & 1);
+    f_tok[q] = on ? raw.score[q] : 0.0f;
+  }
+}
+
+// Epilogue of one (chunk, slot), entirely inside the wave: lane (n = lane % 16, g) holds rows
+// 4g .. 4g + 3 of each tile.  Swish / gating, router score and mask bit; mid is written split into
+// bf16 hi/lo in the order the down kernel's B operand reads it.
 template <int NB, int NM, int RT>
 __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_tiles(NB)],
                                               const float (&f_tok)[acc_tiles(NB)], const LayerView &L, int64_t c,
@@ -301,8 +319,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
         for (int q = 0; q < NA; ++q) acc[a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the epilogue's scores are requested now: a load issued there would return behind the
     // ring's and stop the stream for a memory round trip
-    float f_tok[NA];
-    up_scores<NB>(f_tok, L, scores, token_mask, c, e, k, lane);
+    ScoreRaw<NB> raw;
+    up_scores<NB>(raw, L, scores, token_mask, c, e, k, lane);
 
     for (int kc0 = 0; kc0 < d; kc0 += KC) {
       const int kc_len = min(KC, d - kc0);
@@ -380,6 +398,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       }
     }
 
+    float f_tok[NA];
+    up_scores_finish<NB>(f_tok, raw, e, k, lane);
     up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB);
 
     if (!has_next) break;
@@ -536,13 +556,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
           for (int q = 0; q < NA; ++q) acc[sl][a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the epilogue's scores are requested now: a load issued there would return behind the
     // ring's and stop the stream for a memory round trip
-    float f_tok[G][NA];
+    ScoreRaw<NB> raw[G];   // slots past ns repeat the last one
 #pragma unroll
-    for (int sl = 0; sl < G; ++sl) {
-#pragma unroll
-      for (int q = 0; q < NA; ++q) f_tok[sl][q] = 0.0f;
-      if (sl < ns) up_scores<NB>(f_tok[sl], L, scores, token_mask, c, pick(es, sl), k, lane);
-    }
+    for (int sl = 0; sl < G; ++sl) up_scores<NB>(raw[sl], L, scores, token_mask, c, pick(es, sl), k, lane);
 
     for (int kc = 0; kc < nkc; ++kc) {
       // x of the K-chunk that follows goes into the other buffer (every wave left it at the last barrier)
@@ -581,6 +597,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
       par ^= 1;
     }
 
+    float f_tok[G][NA];
+#pragma unroll
+    for (int sl = 0; sl < G; ++sl) up_scores_finish<NB>(f_tok[sl], raw[sl], pick(es, sl), k, lane);
 #pragma unroll
     for (int sl = 0; sl < G; ++sl)
       if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB);
