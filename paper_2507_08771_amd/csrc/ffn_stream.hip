@@ -188,6 +188,19 @@ __device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], 
   }
 }
 
+// mid in memory is in the order the down kernel's B operand is read from LDS:
+// [chunk][slot][K-step = d_e / 32][NB fragments][64 lanes] of 8 bf16, lane gg * 16 + n holding the
+// expert's neurons 32 * K-step + 8 gg .. + 7 for fragment column n.  The up kernels hold, per lane
+// (n, g) of row tile T, the four neurons 16 T + 4 g .. + 3: half (g & 1) of the 16-byte entry of
+// lane (2 (T & 1) + g / 2) * 16 + n in K-step T / 2.  The 64 lanes of one store then cover 512
+// contiguous bytes (in a row-major [fragment row][d_e] layout they were 16 pieces of 32 bytes,
+// and the partial-line writes held the weight stream up for an eighth of the kernel's time).
+// Returns the address for fragment 0; fragment bf is 128 uint2 further.
+__device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int NB, int T, int g, int n) {
+  const size_t entry = ((kstep0 + (T >> 1)) * NB) * 64 + ((T & 1) * 2 + (g >> 1)) * 16 + n;
+  return reinterpret_cast<uint2 *>(midB) + entry * 2 + (g & 1);
+}
+
 // Epilogue of one (chunk, slot), entirely inside the wave: lane (n = lane % 16, g) holds rows
 // 4g .. 4g + 3 of each tile.  Swish / gating, router score and mask bit; mid is written split into
 // bf16 hi/lo in the order the down kernel's B operand reads it.
@@ -222,14 +235,13 @@ __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_til
       }
       const uint2 vhi = make_uint2(phi[0] | phi[1] << 16, phi[2] | phi[3] << 16);
       const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
-      const size_t col = (rr * 4 + wave) * 16 + 4 * g;
-      uint16_t *base = midB + ((size_t)c * E + s) * NB * 16 * d_e;
+      uint2 *base = mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), NB, rr * 4 + wave, g, n);
       if (NB == 1) {
-        // fragment row n: hi for n < 8, lo of token n - 8 for n >= 8
-        *reinterpret_cast<uint2 *>(base + (size_t)n * d_e + col) = n < 8 ? vhi : vlo;
+        // fragment column n: hi for n < 8, lo of token n - 8 for n >= 8
+        *base = n < 8 ? vhi : vlo;
       } else {
-        *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2) * 16 + n) * d_e + col) = vhi;
-        *reinterpret_cast<uint2 *>(base + ((size_t)(q * 2 + 1) * 16 + n) * d_e + col) = vlo;
+        base[(q * 2) * 128] = vhi;
+        base[(q * 2 + 1) * 128] = vlo;
       }
     }
   }
@@ -714,8 +726,8 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
     split_bf16(on ? f * h : 0.0f, hi, lo);
     packed[q] = n < 8 ? hi : lo;
   }
-  uint16_t *dst = midB + (((size_t)c * E + s) * 16 + n) * d_e + rt * 16 + 4 * g;
-  *reinterpret_cast<uint2 *>(dst) = make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+  *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), 1, rt, g, n) =
+      make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
 }
 
 // ------------------------------------------------------------------------------------------------ down
@@ -785,12 +797,8 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       for (int i = 0; i < RING; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + frag_off(i));
     }
     const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NB * 16) * d_e);
-    // mid of one slot is [NB][16][d_e] bf16; B-operand order is [K-step][NB][lane = g*16 + n]
-    auto stage_src = [&](int s, int idx) {
-      const int ln = idx & 63, bf = (idx >> 6) % NB, ks = idx / (64 * NB);
-      const int n = ln & 15, gg = ln >> 4;
-      return mid_c + (((size_t)s * NB + bf) * 16 + n) * (d_e / 8) + ks * 4 + gg;
-    };
+    // mid of one slot is stored as it is read: [K-step][NB][lane = gg * 16 + n] of 8 bf16
+    auto stage_src = [&](int s, int idx) { return mid_c + (size_t)s * kStage + idx; };
 #pragma unroll
     for (int q = 0; q < kPerThread; ++q) {
       const int idx = tid + q * kThreads;
