@@ -91,6 +91,17 @@ __device__ __forceinline__ void load_to_lds16(const void *src, void *dst) {
                : "memory", "m0");
 }
 
+// The same with 4 bytes per lane: lane j's dword lands at dst + 4 j.
+__device__ __forceinline__ void load_to_lds4(const void *src, void *dst) {
+  typedef __attribute__((address_space(3))) void lds_void;
+  const uint32_t lds_addr =
+      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void *)dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+               :
+               : "s"(lds_addr), "v"(src)
+               : "memory", "m0");
+}
+
 // Swish with beta = 1 (SiLU), full-precision exponential.
 __device__ __forceinline__ float swish(float u) { return u / (1.0f + expf(-u)); }
 

@@ -490,6 +490,37 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     for (int j = 0; j < kBuf / 4 / 64; ++j) load_to_lds16(src + j * 64, dst + j * 64);
   };
 
+  // Router scores and mask words of the item's tokens, [item parity][slot][score, mask lo, mask
+  // hi][token], also by LDS-direct loads: wave sl requests slot sl's when the item starts, the
+  // K-chunks' barriers publish them, the epilogue reads them from LDS.  Loaded into registers they
+  // made the epilogue wait for "every load so far" (the compiler cannot count across the K-chunk
+  // loop), which drained the ring; with the epilogue's stores, whose completion the ring's next
+  // counted wait includes, and the ring's restart that was three memory round trips per item in
+  // which the workgroup's four waves, tied together by the K-chunk barriers, requested nothing.
+  __shared__ uint32_t scoreS[2][G][3][64];
+  auto request_scores = [&](int ipar, int64_t c, uint32_t es, int k) {
+    if (wave < G) {   // uniform over the wave; a slot past ns repeats the last one
+      const int e = pick(es, wave);
+      const int64_t tok = c * k + min(lane & 31, k - 1);
+      load_to_lds4(scores + tok * E + e, &scoreS[ipar][wave][0][0]);
+      if (token_mask) {
+        const uint32_t *m = reinterpret_cast<const uint32_t *>(token_mask + tok * L.W + (e >> 6));
+        load_to_lds4(m, &scoreS[ipar][wave][1][0]);
+        load_to_lds4(m + 1, &scoreS[ipar][wave][2][0]);
+      }
+    }
+  };
+  auto read_scores = [&](float (&f_tok)[NA], int ipar, int sl, int e) {
+    const int n = lane & 15;
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+      const int t = q * 16 + n;   // NB = 2: one accumulator tile, tokens 0-15
+      const uint32_t word = token_mask ? scoreS[ipar][sl][1 + ((e >> 5) & 1)][t] : ~0u;
+      const bool on = t < k && ((word >> (e & 31)) & 1);
+      f_tok[q] = on ? __uint_as_float(scoreS[ipar][sl][0][t]) : 0.0f;
+    }
+  };
+
   // Workgroup b runs on XCD b mod 8 and each XCD has its own L2.  The items of a chunk all read
   // the chunk's split x (256 KiB at k = 32), so consecutive items go to the workgroups of ONE XCD:
   // step j of workgroup (xcd, w) takes item ((j * 8 + xcd) * per_xcd + w), and x is served by that
@@ -555,6 +586,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");   // the fill is older than the ring's loads
   __syncthreads();
   int par = 0;   // buffer of the current K-chunk
+  int ipar = 0;  // half of scoreS of the current item
 
   while (true) {
     f32x4 acc[G][RT][NM][NA];
@@ -568,9 +600,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
           for (int q = 0; q < NA; ++q) acc[sl][a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the epilogue's scores are requested now: a load issued there would return behind the
     // ring's and stop the stream for a memory round trip
-    ScoreRaw<NB> raw[G];   // slots past ns repeat the last one
-#pragma unroll
-    for (int sl = 0; sl < G; ++sl) up_scores<NB>(raw[sl], L, scores, token_mask, c, pick(es, sl), k, lane);
+    request_scores(ipar, c, es, k);
 
     for (int kc = 0; kc < nkc; ++kc) {
       // x of the K-chunk that follows goes into the other buffer (every wave left it at the last barrier)
@@ -611,10 +641,11 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 
     float f_tok[G][NA];
 #pragma unroll
-    for (int sl = 0; sl < G; ++sl) up_scores_finish<NB>(f_tok[sl], raw[sl], pick(es, sl), k, lane);
+    for (int sl = 0; sl < G; ++sl) read_scores(f_tok[sl], ipar, sl, pick(es, sl));
 #pragma unroll
     for (int sl = 0; sl < G; ++sl)
       if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB);
+    ipar ^= 1;   // the next item's scores go to the other half: a slower wave may still be reading this one
 
     if (!has_next) break;
     item += item_step;
