@@ -285,7 +285,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   };
 
   uint4 ring[kRing];
-  int item = blockIdx.x;
+  // workgroup b runs on XCD b mod 8: consecutive items (slots of one chunk, same split x) go to
+  // the workgroups of one XCD, which share an L2 (the launcher makes the grid a multiple of 8)
+  int item = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
   if (item >= total) return;
   int64_t c;
   int s, ns;        // current slot and slots left in the item (this one included)
@@ -923,7 +925,7 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int64_t grid = std::min<int64_t>(max_items, (int64_t)num_cus() * 2);
+  const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
                      active_idx, n_active, items, total, group, k, midB);
   return hipGetLastError();
