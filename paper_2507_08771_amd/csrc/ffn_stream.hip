@@ -769,6 +769,11 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
 // flight per lane.  With splits > 1 the union's slots are divided among `splits` workgroups per
 // (chunk, column block); each writes its partial sum to out + split * split_stride and a second
 // kernel adds them in a fixed order (used when a launch has too few chunks to fill the chip).
+__host__ __device__ inline bool down_by_xcd(int64_t n_chunks) { return n_chunks >= 64; }
+__host__ __device__ inline int64_t down_grid_chunks(int64_t n_chunks) {
+  return down_by_xcd(n_chunks) ? (n_chunks + 7) / 8 * 8 : n_chunks;
+}
+
 template <int NB, int KSD, int MW, int RING>
 __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
@@ -790,9 +795,11 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   // pulled it through the fabric (at k = 32, d_e = 128: 64 KiB of mid per 512 KiB of W_down, 12 %
   // on top of the weight bytes).  Block v runs on XCD v mod 8, so a chunk's workgroups get ids
   // that differ by multiples of 8 and share the mid in one L2.
+  // A handful of chunks keep the plain order: their few workgroups must spread over all XCDs.
   const int per_chunk = col_blocks * splits;
-  const int64_t q = blockIdx.x >> 3;
-  const int64_t c = (q / per_chunk) * 8 + (blockIdx.x & 7);
+  const bool by_xcd = down_by_xcd(n_chunks);
+  const int64_t q = by_xcd ? blockIdx.x >> 3 : blockIdx.x;
+  const int64_t c = by_xcd ? (q / per_chunk) * 8 + (blockIdx.x & 7) : q / per_chunk;
   if (c >= n_chunks) return;   // the grid is rounded up to 8 chunks
   const int within = (int)(q % per_chunk);
   const int sp = within % splits;
@@ -982,7 +989,7 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
   if (splits == 0) {
     constexpr int MW = (NB == 4 && KSD >= 8) ? 4 : 8;   // 8 row tiles x 2 accumulator tiles do not fit beside 64 fragments of addresses
     const int col_blocks = L.d / (4 * MW * 16);
-    const int64_t grid = (n_chunks + 7) / 8 * 8 * col_blocks;
+    const int64_t grid = down_grid_chunks(n_chunks) * col_blocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, kRing>), dim3((unsigned)grid), dim3(kThreads), 0, s, L,
                        chunk_layer, active_idx, n_active, n_chunks, k, col_blocks, 1, midB, y, stride);
@@ -990,7 +997,7 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
   }
   constexpr int MW = 8 / KSD;
   const int col_blocks = L.d / (4 * MW * 16);
-  const int64_t grid = (n_chunks + 7) / 8 * 8 * col_blocks * splits;
+  const int64_t grid = down_grid_chunks(n_chunks) * col_blocks * splits;
   hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
                      active_idx, n_active, n_chunks, k, col_blocks, splits, midB, splits > 1 ? part : y, stride);
   hipError_t err = hipGetLastError();
