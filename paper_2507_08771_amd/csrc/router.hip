@@ -248,34 +248,41 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t bf16_bits_of(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
 
-template <int RT, int KB>
+template <int RT, int KB, int T>
 __global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                                const float *__restrict__ x, int k,
                                                                int tiles_per_chunk, float *__restrict__ scores,
                                                                uint64_t *__restrict__ token_mask,
                                                                float *__restrict__ preact) {
-  __shared__ float part[4][RT * 16][kTok];
+  __shared__ float part[T][4][RT * 16][kTok];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, g = lane >> 4;
-  const int64_t c = blockIdx.x / tiles_per_chunk;
-  const int t0 = (int)(blockIdx.x % tiles_per_chunk) * kTok;
-  const int nt = min(kTok, k - t0);
-  const int64_t tok0 = c * (int64_t)k + t0;
+  const int groups = (tiles_per_chunk + T - 1) / T;   // T token tiles of one chunk per workgroup
+  const int64_t c = blockIdx.x / groups;
+  const int tile0 = (int)(blockIdx.x % groups) * T;
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int d = L.d, E = L.E;
   const uint16_t *wr = static_cast<const uint16_t *>(L.w_router) + (size_t)layer * E * d;
   const int tok = n & 7;
-  const bool tok_ok = tok < nt;
-  const float *xrow = x + (tok0 + (tok_ok ? tok : 0)) * d;
+  bool tok_ok[T];
+  const float *xrow[T];
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    const int t0 = (tile0 + tt) * kTok;
+    tok_ok[tt] = t0 + tok < k;
+    xrow[tt] = x + (c * (int64_t)k + (tok_ok[tt] ? t0 + tok : 0)) * d;
+  }
   const int n_ksteps = (d + 31) / 32;
 
-  f32x4_t acc[RT][2];
+  f32x4_t acc[T][RT][2];
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt) acc[rt][0] = acc[rt][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[tt][rt][0] = acc[tt][rt][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   for (int ks0 = wave; ks0 < n_ksteps; ks0 += 4 * KB) {
     uint4 a[KB][RT];
-    float4 xa[KB], xb[KB];
+    float4 xa[KB][T], xb[KB][T];
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
       const int col = (ks0 + 4 * u) * 32 + g * 8;   // d is a multiple of 8: a lane's 8 elements are all in or all out
@@ -285,47 +292,60 @@ __global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, cons
         const int row = min(rt * 16 + n, E - 1);   // rows at or above E repeat the last one; never read back
         a[u][rt] = ok ? *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + col) : make_uint4(0, 0, 0, 0);
       }
-      const float4 *px = reinterpret_cast<const float4 *>(xrow + col);
-      xa[u] = ok ? px[0] : make_float4(0.f, 0.f, 0.f, 0.f);
-      xb[u] = ok ? px[1] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt) {
+        const float4 *px = reinterpret_cast<const float4 *>(xrow[tt] + col);
+        xa[u][tt] = ok ? px[0] : make_float4(0.f, 0.f, 0.f, 0.f);
+        xb[u][tt] = ok ? px[1] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
 #pragma unroll
     for (int u = 0; u < KB; ++u) {
-      const float xv[8] = {xa[u].x, xa[u].y, xa[u].z, xa[u].w, xb[u].x, xb[u].y, xb[u].z, xb[u].w};
-      uint32_t p0[8], p1[8];   // this lane's piece for the first and for the second B fragment
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const uint32_t h = bf16_bits_of(xv[q]);
-        const float r1 = xv[q] - __uint_as_float(h << 16);
-        const uint32_t m = bf16_bits_of(r1);
-        const float r2 = r1 - __uint_as_float(m << 16);
-        const uint32_t l = bf16_bits_of(r2);
-        p0[q] = tok_ok ? (n < 8 ? h : m) : 0u;
-        p1[q] = (tok_ok && n < 8) ? l : 0u;
-      }
-      const uint4 b0 = make_uint4(p0[0] | p0[1] << 16, p0[2] | p0[3] << 16, p0[4] | p0[5] << 16, p0[6] | p0[7] << 16);
-      const uint4 b1 = make_uint4(p1[0] | p1[1] << 16, p1[2] | p1[3] << 16, p1[4] | p1[5] << 16, p1[6] | p1[7] << 16);
+      for (int tt = 0; tt < T; ++tt) {
+        const float xv[8] = {xa[u][tt].x, xa[u][tt].y, xa[u][tt].z, xa[u][tt].w,
+                             xb[u][tt].x, xb[u][tt].y, xb[u][tt].z, xb[u][tt].w};
+        uint32_t p0[8], p1[8];   // this lane's piece for the first and for the second B fragment
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        acc[rt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u][rt]),
-                                                             __builtin_bit_cast(bf16x8_t, b0), acc[rt][0], 0, 0, 0);
-        acc[rt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u][rt]),
-                                                             __builtin_bit_cast(bf16x8_t, b1), acc[rt][1], 0, 0, 0);
+        for (int q = 0; q < 8; ++q) {
+          const uint32_t h = bf16_bits_of(xv[q]);
+          const float r1 = xv[q] - __uint_as_float(h << 16);
+          const uint32_t m = bf16_bits_of(r1);
+          const float r2 = r1 - __uint_as_float(m << 16);
+          const uint32_t l = bf16_bits_of(r2);
+          p0[q] = tok_ok[tt] ? (n < 8 ? h : m) : 0u;
+          p1[q] = (tok_ok[tt] && n < 8) ? l : 0u;
+        }
+        const uint4 b0 = make_uint4(p0[0] | p0[1] << 16, p0[2] | p0[3] << 16, p0[4] | p0[5] << 16, p0[6] | p0[7] << 16);
+        const uint4 b1 = make_uint4(p1[0] | p1[1] << 16, p1[2] | p1[3] << 16, p1[4] | p1[5] << 16, p1[6] | p1[7] << 16);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          acc[tt][rt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8_t, a[u][rt]), __builtin_bit_cast(bf16x8_t, b0), acc[tt][rt][0], 0, 0, 0);
+          acc[tt][rt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+              __builtin_bit_cast(bf16x8_t, a[u][rt]), __builtin_bit_cast(bf16x8_t, b1), acc[tt][rt][1], 0, 0, 0);
+        }
       }
     }
   }
   // accumulator element q of lane (n, g) is expert rt * 16 + 4 * g + q, column n: token n & 7,
   // piece h (n < 8) or m (n >= 8) in the first fragment, l (n < 8) in the second
 #pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
+  for (int tt = 0; tt < T; ++tt)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float hm = acc[rt][0][q] + __shfl_xor(acc[rt][0][q], 8, kWave);
-      const int i = rt * 16 + 4 * g + q;
-      if (n < 8) part[wave][i][n] = hm + acc[rt][1][q];
-    }
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float hm = acc[tt][rt][0][q] + __shfl_xor(acc[tt][rt][0][q], 8, kWave);
+        const int i = rt * 16 + 4 * g + q;
+        if (n < 8) part[tt][wave][i][n] = hm + acc[tt][rt][1][q];
+      }
   __syncthreads();
-  finish_tile(L, layer, part, tok0, nt, scores, token_mask, preact);
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    const int t0 = (tile0 + tt) * kTok;
+    if (t0 < k) finish_tile(L, layer, part[tt], c * (int64_t)k + t0, min(kTok, k - t0), scores, token_mask, preact);
+  }
 }
 
 // Second half of the split router: one wave per token turns A^0 (in `scores`) into the mask word(s)
@@ -408,14 +428,19 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
   dim3 grid((unsigned)blocks);
   if (wdtype == BLOCKFFN_BF16) {
     const int rt = (L.E + 15) / 16;
-#define BLOCKFFN_ROUTER(RT, KB)                                                                               \
-  hipLaunchKernelGGL((router_mfma_kernel<RT, KB>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, \
-                     token_mask, preact)
-    if (rt <= 1) BLOCKFFN_ROUTER(1, 4);
-    else if (rt <= 2) BLOCKFFN_ROUTER(2, 2);
-    else if (rt <= 4) BLOCKFFN_ROUTER(4, 2);
-    else if (rt <= 8) BLOCKFFN_ROUTER(8, 2);
-    else BLOCKFFN_ROUTER(16, 1);
+#define BLOCKFFN_ROUTER(RT, KB, T)                                                                     \
+  hipLaunchKernelGGL((router_mfma_kernel<RT, KB, T>), dim3((unsigned)(n_chunks * ((tiles + T - 1) / T))), block, 0, \
+                     s, L, chunk_layer, x, k, tiles, scores, token_mask, preact)
+    // Every workgroup pulls the whole router matrix of its chunk's layer through its L1 (512 KiB at
+    // E = 128, d = 2048, against 64 KiB of x per 8 tokens): with several token tiles per chunk a
+    // workgroup takes 2 or 4 of them per pass over the matrix, as many as the accumulators allow.
+    // (only while that still leaves four workgroups per CU)
+    const bool multi = tiles >= 2 && blocks / 2 >= 1024, quad = tiles >= 4 && blocks / 4 >= 1024;
+    if (rt <= 1) { if (quad) BLOCKFFN_ROUTER(1, 4, 4); else if (multi) BLOCKFFN_ROUTER(1, 4, 2); else BLOCKFFN_ROUTER(1, 4, 1); }
+    else if (rt <= 2) { if (quad) BLOCKFFN_ROUTER(2, 2, 4); else if (multi) BLOCKFFN_ROUTER(2, 2, 2); else BLOCKFFN_ROUTER(2, 2, 1); }
+    else if (rt <= 4) { if (quad) BLOCKFFN_ROUTER(4, 1, 4); else if (multi) BLOCKFFN_ROUTER(4, 2, 2); else BLOCKFFN_ROUTER(4, 2, 1); }
+    else if (rt <= 8) { if (multi) BLOCKFFN_ROUTER(8, 1, 2); else BLOCKFFN_ROUTER(8, 2, 1); }
+    else BLOCKFFN_ROUTER(16, 1, 1);
 #undef BLOCKFFN_ROUTER
   } else
     hipLaunchKernelGGL((router_kernel<float, false>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores, token_mask,
