@@ -378,18 +378,13 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
           const char *cur = tile_ptr(layer, e, rr, m) + (size_t)kc0 * 2;
           // first block of the tile that follows this one in (K-chunk, rr, m) order
           const char *nxt_tile;
-          bool nxt_ok = true;
           if (m + 1 < NM) nxt_tile = tile_ptr(layer, e, rr, m + 1) + (size_t)kc0 * 2;
           else if (rr + 1 < RT) nxt_tile = tile_ptr(layer, e, rr + 1, 0) + (size_t)kc0 * 2;
           else if (!last_kc) nxt_tile = tile_ptr(layer, e, 0, 0) + (size_t)(kc0 + KC) * 2;
-          else {
-            nxt_tile = tile_ptr(layer_n, e_n, 0, 0);
-            nxt_ok = has_next;
-          }
+          else nxt_tile = tile_ptr(layer_n, e_n, 0, 0);   // nothing follows: expert 0's first tile, never used
           for (int kb = 0; kb < nkb; ++kb) {
             const bool tail = kb + 1 == nkb;
             const char *nxt = tail ? nxt_tile : cur + (size_t)(kb + 1) * 1024;
-            const bool ok = tail ? nxt_ok : true;
             if (rr == RT - 1 && m == NM - 1 && tail && need_f) {
 #pragma unroll
               for (int j = 0; j < PF; ++j) {
@@ -405,7 +400,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
                 const uint4 b = xB[(size_t)((kb * kRing + i) * NB + bf) * 64 + lane];
                 acc[rr][m][acc_of(NB, bf)] = mfma16(ring[i], b, acc[rr][m][acc_of(NB, bf)]);
               }
-              if (ok) ring[i] = *reinterpret_cast<const uint4 *>(nxt + i * 64);
+              ring[i] = *reinterpret_cast<const uint4 *>(nxt + i * 64);   // nxt is always a valid tile
             }
           }
         }
