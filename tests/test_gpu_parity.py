@@ -68,6 +68,7 @@ def impl(request, monkeypatch):
     (512, 256, 64, 8, 5),     # the most experts: four full mask words, 16 router row tiles
     (256, 8, 1024, 4, 2),     # the widest expert
     (16384, 4, 8, 2, 2),      # the longest hidden size
+    (512, 32, 64, 8, 67),     # 64 chunks or more: a chunk's down-projection workgroups share an XCD; ragged count
 ])
 def test_shapes(d, E, d_e, k, C, wdtype, gated, impl):
     if impl == "generic" and wdtype == "f32":
@@ -92,6 +93,34 @@ def test_large_chunks(k, d_e, C, gated, impl):
     gemm = k > 32 and impl == "auto"
     print(pu.assert_floats_close(gpu, ref, "bf16", dense=(k <= 40), bar=pu.GEMM_BAR if gemm else None,
                                  l2_bar=pu.GEMM_L2_BAR if gemm else None))
+
+
+@pytest.mark.parametrize("gated", [True, False])
+def test_k32_many_chunks(gated):
+    """70 chunks of 32 tokens (64 or more, not a multiple of 8): the double-buffered up kernel's
+    items and the down kernel's column blocks are placed by XCD, the last group of 8 chunks is
+    ragged; mid holds four fragments per K-step."""
+    import oracle
+    w = wl.Workload("t", d=1024, E=32, d_e=128, wdtype="bf16", gated=gated, k=32, n_chunks=70, sigma=0.3, seed=77)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    ref = pu.run_oracle(layers, x, w.k, None, dense=False)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, None, dense=False)
+    pu.assert_integers_equal(gpu, ref)
+    e_y = pu.row_rel_err(gpu["y"], ref["y"]).max(initial=0.0)
+    assert e_y <= pu.TIGHT["bf16"], "sparse FFN output off by %.3g" % e_y
+    # With 2240 tokens some have a single, barely active expert: sqrt(mean square + eps) is then
+    # close to sqrt(eps) and magnifies the fp32 summation error of the pre-activation.  Same bound
+    # as in test_router_with_many_token_tiles: 1e-5 of the row's rms plus that error behind the
+    # normalisation.
+    _, _, a0 = oracle.router(pu.oracle_layer(layers, 0), x.numpy(), return_a0=True)
+    mag = np.abs(x.numpy()).astype(np.float64) @ np.abs(layers["w_router"][0].double().numpy()).T + 1.0
+    a1 = np.maximum(a0, 0.0)
+    scale = np.sqrt((a1 * a1).mean(axis=1) + 1e-6)
+    rms = np.sqrt((ref["scores"].astype(np.float64) ** 2).mean(axis=1))
+    allowed = 1e-5 * np.maximum(rms, 1e-30) + 2.0 * 1e-6 * mag.max(axis=1) / scale
+    assert np.all(np.abs(gpu["scores"] - ref["scores"]).max(axis=1) <= allowed)
+    np.testing.assert_array_equal(gpu["scores"] == 0, ref["scores"] == 0)
 
 
 def test_layer_rotation_gain_and_eps():
@@ -222,14 +251,15 @@ def test_full_size_spec_k8_sampled_chunks():
 
 
 @pytest.mark.parametrize("E", [5, 16, 31, 64, 100, 128, 130, 256])
-@pytest.mark.parametrize("k", [1, 8, 11])
+@pytest.mark.parametrize("k", [1, 8, 11, 20, 28])
 def test_router_with_many_token_tiles(E, k):
     """Enough token tiles that the router takes its many-tile kernel (the matrix-core one for bf16
     weights), every count of 16-expert row tiles, a hidden size that ends in a partial K-step
     (520 = 16 * 32 + 8), gain and three weight sets; scores, masks and pre-activations against the
-    oracle's router."""
+    oracle's router.  k = 20 and 28 come with enough chunks that a workgroup takes two or four
+    token tiles of a chunk per pass over the router matrix, the last one ragged or past the chunk."""
     import oracle
-    d, C, n_layers = 520, 300, 3
+    d, C, n_layers = 520, (300 if k <= 11 else 1500), 3
     w = wl.Workload("t", d=d, E=E, d_e=8, wdtype="bf16", gated=False, k=k, n_chunks=C, sigma=0.3, seed=E * 31 + k)
     layers = wl.make_layers(w, n_layers, gain=True)
     cl = wl.make_chunk_layer(w, n_layers)
