@@ -32,7 +32,7 @@ HBM_PEAK = 8.0e12  # bytes/s, MI355X HBM3E
 
 # HBM bytes per launch of the up kernel from rocprofv3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
 # factors a plain 1 GiB device copy gives), keyed by (workload, replicas, gated); see profiles/.
-MEASURED_TRAFFIC = {("spec_k8", 32, True): 22181623 * 1024 * 2.0 + 170216 * 1024 * 1.0}
+MEASURED_TRAFFIC = {("spec_k8", 32, True): 22229467 * 1024 * 2.0 + 170216 * 1024 * 1.0}
 
 
 def parse():
