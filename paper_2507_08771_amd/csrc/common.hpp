@@ -156,8 +156,9 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
                               hipStream_t s);
 
 // Flat list of the active experts in groups of `group` consecutive slots: items[i] = chunk * E +
-// first slot of the group, *total = its length (n_active == nullptr: every chunk has E slots).
-// items needs n_chunks * E entries.
+// first slot of the group, full groups first, then the chunks' shorter last groups, longest first;
+// total[0] = its length (n_active == nullptr: every chunk has E slots), total[16 .. 19] = 0 (a
+// 16-byte block of zeros for the kernels that follow).  items needs n_chunks * E entries, total 20.
 hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int group, int32_t *items,
                            int32_t *total, hipStream_t s);
 

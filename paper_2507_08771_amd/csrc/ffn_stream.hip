@@ -110,6 +110,7 @@ __global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restric
     }
   }
   if (tid == 0) *total = carry;
+  if (tid < 4) total[16 + tid] = 0;   // the block of zeros the down kernel stages absent tokens from
 }
 
 // ------------------------------------------------------------------------------------------------ x split
@@ -188,18 +189,22 @@ __device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], 
   }
 }
 
-// mid in memory is in the order the down kernel's B operand is read from LDS:
-// [chunk][slot][K-step = d_e / 32][NB fragments][64 lanes] of 8 bf16, lane gg * 16 + n holding the
-// expert's neurons 32 * K-step + 8 gg .. + 7 for fragment column n.  The up kernels hold, per lane
-// (n, g) of row tile T, the four neurons 16 T + 4 g .. + 3: half (g & 1) of the 16-byte entry of
-// lane (2 (T & 1) + g / 2) * 16 + n in K-step T / 2.  The 64 lanes of one store then cover 512
-// contiguous bytes (in a row-major [fragment row][d_e] layout they were 16 pieces of 32 bytes,
-// and the partial-line writes held the weight stream up for an eighth of the kernel's time).
-// Returns the address for fragment 0; fragment bf is 128 uint2 further.
-__device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int NB, int T, int g, int n) {
-  const size_t entry = ((kstep0 + (T >> 1)) * NB) * 64 + ((T & 1) * 2 + (g >> 1)) * 16 + n;
+// mid in memory, k <= 8 (NB = 1): in the order the down kernel's B operand is read from LDS,
+// [chunk][slot][K-step = d_e / 32][64 lanes] of 8 bf16, lane gg * 16 + n holding the expert's
+// neurons 32 * K-step + 8 gg .. + 7 for fragment column n (0-7: hi of tokens 0-7, 8-15: their lo).
+// The up kernels hold, per lane (n, g) of row tile T, the four neurons 16 T + 4 g .. + 3: half
+// (g & 1) of the 16-byte entry of lane (2 (T & 1) + g / 2) * 16 + n in K-step T / 2, so the 64
+// lanes of one store cover 512 contiguous bytes and the down kernel's staging is a linear copy.
+__device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int T, int g, int n) {
+  const size_t entry = (kstep0 + (T >> 1)) * 64 + ((T & 1) * 2 + (g >> 1)) * 16 + n;
   return reinterpret_cast<uint2 *>(midB) + entry * 2 + (g & 1);
 }
+// k > 8 (NB = 2, 4): token-major, [chunk][slot][token][hi, lo][d_e] bf16, and only the rows of
+// tokens whose mask bit for the slot's expert is set (and whose score is not zero) are written;
+// tok_bits[chunk * E + slot] has bit t set for them.  At k = 32 about 60 % of the (token, slot)
+// pairs of a union are such zeros, and what the stores of mid cost is their traffic to HBM (3 % of
+// the up kernel's bytes took 11 % of its time); the down kernel stages the other tokens from a
+// 16-byte block of zeros.
 
 // Epilogue of one (chunk, slot), entirely inside the wave: lane (n = lane % 16, g) holds rows
 // 4g .. 4g + 3 of each tile.  Swish / gating, router score and mask bit; mid is written split into
@@ -207,15 +212,18 @@ __device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int N
 template <int NB, int NM, int RT>
 __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_tiles(NB)],
                                               const float (&f_tok)[acc_tiles(NB)], const LayerView &L, int64_t c,
-                                              int s, int lane, int wave, uint16_t *__restrict__ midB) {
+                                              int s, int lane, int wave, uint16_t *__restrict__ midB,
+                                              uint32_t *__restrict__ tok_bits) {
   constexpr int NA = acc_tiles(NB);
   const int E = L.E, d_e = L.d_e;
   const int g = lane >> 4;
   const int n = lane & 15;
+  uint32_t bits = 0;
 #pragma unroll
   for (int q = 0; q < NA; ++q) {
     const float f = f_tok[q];
-    const bool on = f != 0.0f;   // a masked term, and one with a zero score, store +0
+    const bool on = f != 0.0f;   // a masked term, and one with a zero score, is +0 in mid
+    if (NB > 1) bits |= ((uint32_t)__ballot(on) & 0xffffu) << (16 * q);   // lanes 0-15: g = 0, token 16 q + n
 #pragma unroll
     for (int rr = 0; rr < RT; ++rr) {
       uint32_t phi[4], plo[4];
@@ -235,16 +243,17 @@ __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_til
       }
       const uint2 vhi = make_uint2(phi[0] | phi[1] << 16, phi[2] | phi[3] << 16);
       const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
-      uint2 *base = mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), NB, rr * 4 + wave, g, n);
       if (NB == 1) {
         // fragment column n: hi for n < 8, lo of token n - 8 for n >= 8
-        *base = n < 8 ? vhi : vlo;
-      } else {
-        base[(q * 2) * 128] = vhi;
-        base[(q * 2 + 1) * 128] = vlo;
+        *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rr * 4 + wave, g, n) = n < 8 ? vhi : vlo;
+      } else if (on) {
+        uint16_t *row = midB + (((size_t)c * E + s) * (NB * 8) + q * 16 + n) * 2 * d_e + (rr * 4 + wave) * 16 + 4 * g;
+        *reinterpret_cast<uint2 *>(row) = vhi;
+        *reinterpret_cast<uint2 *>(row + d_e) = vlo;
       }
     }
   }
+  if (NB > 1 && wave == 0 && lane == 0) tok_bits[(size_t)c * E + s] = bits;
 }
 
 // NB: B fragments per K-step (see the top of the file); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
@@ -254,7 +263,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
-    int group, int k, uint16_t *__restrict__ midB) {
+    int group, int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits) {
   extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
   constexpr int KC = 2048 / NB;   // contraction elements per LDS fill
   constexpr int NA = acc_tiles(NB);
@@ -409,7 +418,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 
     float f_tok[NA];
     up_scores_finish<NB>(f_tok, raw, e, k, lane);
-    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB);
+    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits);
 
     if (!has_next) break;
     item = next_item;
@@ -434,7 +443,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
-    int k, uint16_t *__restrict__ midB) {
+    int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits) {
   static_assert(NB == 2 || NB == 4, "8 or 16 K-steps per buffer");
   constexpr int FPT = 32 / NB;            // K-steps (fragments of one tile) per K-chunk
   constexpr int KB = 32 * FPT;            // contraction elements per buffer
@@ -641,7 +650,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     for (int sl = 0; sl < G; ++sl) read_scores(f_tok[sl], ipar, sl, pick(es, sl));
 #pragma unroll
     for (int sl = 0; sl < G; ++sl)
-      if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB);
+      if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB, tok_bits);
     ipar ^= 1;   // the next item's scores go to the other half: a slower wave may still be reading this one
 
     if (!has_next) break;
@@ -754,7 +763,7 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
     split_bf16(on ? f * h : 0.0f, hi, lo);
     packed[q] = n < 8 ? hi : lo;
   }
-  *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), 1, rt, g, n) =
+  *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rt, g, n) =
       make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
 }
 
@@ -773,7 +782,8 @@ template <int NB, int KSD, int MW, int RING>
 __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, int64_t n_chunks, int k, int col_blocks, int splits,
-    const uint16_t *__restrict__ midB, float *__restrict__ out, size_t split_stride) {
+    const uint16_t *__restrict__ midB, const uint32_t *__restrict__ tok_bits, const uint4 *__restrict__ zero16,
+    float *__restrict__ out, size_t split_stride) {
   constexpr int kFrag = KSD * MW;             // weight fragments per slot and wave
   static_assert(kFrag % RING == 0, "ring must divide the fragments of a slot");
   constexpr int kStage = KSD * NB * 64;       // uint4 of mid per slot
@@ -832,14 +842,29 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       for (int i = 0; i < RING; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + frag_off(i));
     }
     const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NB * 16) * d_e);
-    // mid of one slot is stored as it is read: [K-step][NB][lane = gg * 16 + n] of 8 bf16
-    auto stage_src = [&](int s, int idx) { return mid_c + (size_t)s * kStage + idx; };
+    // B-operand order in LDS is [K-step][NB][lane = gg * 16 + n] of 8 bf16.  k <= 8: mid is stored
+    // like that.  k > 8: mid is token-major and holds only the rows of the tokens in `bits`; entry
+    // (K-step, fragment bf, gg, n) is 16 bytes of row (token 16 (bf / 2) + n, hi or lo = bf & 1),
+    // or of the block of zeros.
+    auto slot_bits = [&](int s) { return NB == 1 ? 0u : tok_bits[c * E + min(s, s_hi - 1)]; };
+    auto stage_src = [&](int s, int idx, uint32_t bits) -> const uint4 * {
+      if (NB == 1) return mid_c + (size_t)s * kStage + idx;
+      const int ln = idx & 63, bf = (idx >> 6) % NB, ks = idx / (64 * NB);
+      const int n = ln & 15, gg = ln >> 4, t = (bf >> 1) * 16 + n;
+      const uint4 *row = mid_c + ((size_t)s * (NB * 16) + t * 2 + (bf & 1)) * (d_e / 8) + ks * 4 + gg;
+      return (bits >> t) & 1 ? row : zero16;
+    };
+    {
+      const uint32_t bits = slot_bits(s_lo);
 #pragma unroll
-    for (int q = 0; q < kPerThread; ++q) {
-      const int idx = tid + q * kThreads;
-      if (idx < kStage) midS[0][idx] = *stage_src(s_lo, idx);
+      for (int q = 0; q < kPerThread; ++q) {
+        const int idx = tid + q * kThreads;
+        if (idx < kStage) midS[0][idx] = *stage_src(s_lo, idx, bits);
+      }
     }
     __syncthreads();
+    // the token bits of the slot staged in iteration s (slot s + 1) are fetched an iteration ahead
+    uint32_t bits_stage = slot_bits(s_lo + 1), bits_after = slot_bits(s_lo + 2);
 
     for (int s = s_lo; s < s_hi; ++s) {
       const bool has_next = s + 1 < s_hi;
@@ -854,8 +879,10 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
       for (int q = 0; q < kPerThread; ++q) {
         const int idx = tid + q * kThreads;
         if (q * kThreads + wave * 64 < kStage)   // uniform over the wave (kStage is a multiple of 64)
-          load_to_lds16(stage_src(s_stage, idx), stage_dst + q * kThreads + wave * 64);
+          load_to_lds16(stage_src(s_stage, idx, bits_stage), stage_dst + q * kThreads + wave * 64);
       }
+      bits_stage = bits_after;
+      bits_after = slot_bits(s + 3);
       const char *cur = slot_ptr(e);
       const uint4 *bS = midS[(s - s_lo) & 1];
 #pragma unroll
@@ -918,7 +945,7 @@ template <int NB, int NM, int RT>
 hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                      const int32_t *items, const int32_t *total, int group, int64_t max_items, int k, uint16_t *midB,
-                     hipStream_t s) {
+                     uint32_t *tok_bits, hipStream_t s) {
   static bool attr_set = false;
   auto kern = up_stream_kernel<NB, NM, RT>;
   if (!attr_set) {
@@ -929,7 +956,7 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4
   }
   const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
-                     active_idx, n_active, items, total, group, k, midB);
+                     active_idx, n_active, items, total, group, k, midB, tok_bits);
   return hipGetLastError();
 }
 
@@ -937,7 +964,7 @@ template <int NB, int NM, int RT, int G>
 hipError_t launch_up_db(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                         const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                         const int32_t *items, const int32_t *total, int64_t max_items, int k, uint16_t *midB,
-                        hipStream_t s) {
+                        uint32_t *tok_bits, hipStream_t s) {
   static bool attr_set = false;
   auto kern = up_stream_db_kernel<NB, NM, RT, G>;
   if (!attr_set) {
@@ -948,7 +975,7 @@ hipError_t launch_up_db(const LayerView &L, const int32_t *chunk_layer, const ui
   }
   const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
-                     active_idx, n_active, items, total, k, midB);
+                     active_idx, n_active, items, total, k, midB, tok_bits);
   return hipGetLastError();
 }
 
@@ -977,8 +1004,8 @@ int down_splits(const LayerView &L, int64_t n_chunks) {
 
 template <int NB, int KSD>
 hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
-                       const int32_t *n_active, int64_t n_chunks, int k, const uint16_t *midB, float *part, float *y,
-                       hipStream_t s) {
+                       const int32_t *n_active, int64_t n_chunks, int k, const uint16_t *midB, const uint32_t *tok_bits,
+                       const uint4 *zero16, float *part, float *y, hipStream_t s) {
   const int splits = down_splits(L, n_chunks);
   const size_t stride = (size_t)n_chunks * k * L.d;
   if (splits == 0) {
@@ -987,14 +1014,15 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
     const int64_t grid = down_grid_chunks(n_chunks) * col_blocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, kRing>), dim3((unsigned)grid), dim3(kThreads), 0, s, L,
-                       chunk_layer, active_idx, n_active, n_chunks, k, col_blocks, 1, midB, y, stride);
+                       chunk_layer, active_idx, n_active, n_chunks, k, col_blocks, 1, midB, tok_bits, zero16, y, stride);
     return hipGetLastError();
   }
   constexpr int MW = 8 / KSD;
   const int col_blocks = L.d / (4 * MW * 16);
   const int64_t grid = down_grid_chunks(n_chunks) * col_blocks * splits;
   hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
-                     active_idx, n_active, n_chunks, k, col_blocks, splits, midB, splits > 1 ? part : y, stride);
+                     active_idx, n_active, n_chunks, k, col_blocks, splits, midB, tok_bits, zero16, splits > 1 ? part : y,
+                     stride);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || splits == 1) return err;
   const size_t n4 = stride / 4;
@@ -1008,6 +1036,8 @@ int b_frags(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
 struct StreamWs {
   uint16_t *midB;
   int32_t *items, *total;
+  uint32_t *tok_bits;    // [chunk * E + slot]: the tokens whose rows of mid are written (k > 8)
+  const uint4 *zero16;   // 16 bytes of zeros, written with the work list
   uint4 *xS;     // the chunks' x split into bf16 hi/lo in B-operand order
   float *part;   // partial sums of the split down projection (few chunks only)
 };
@@ -1021,7 +1051,8 @@ size_t mid_bytes(const LayerView &L, int64_t n_chunks, int k) {
 }
 
 size_t item_bytes(const LayerView &L, int64_t n_chunks) {
-  return (((size_t)n_chunks * L.E + 64) * sizeof(int32_t) + 255) & ~(size_t)255;
+  // 64 words of counters and constants, the item list, the token bits of every slot
+  return (((size_t)n_chunks * L.E * 2 + 64) * sizeof(int32_t) + 255) & ~(size_t)255;
 }
 
 StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
@@ -1030,6 +1061,8 @@ StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
   w.midB = reinterpret_cast<uint16_t *>(p);
   w.total = reinterpret_cast<int32_t *>(p + mid_bytes(L, n_chunks, k));
   w.items = w.total + 64;
+  w.tok_bits = reinterpret_cast<uint32_t *>(w.items + (size_t)n_chunks * L.E);
+  w.zero16 = reinterpret_cast<const uint4 *>(w.total + 16);
   w.xS = reinterpret_cast<uint4 *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks));
   w.part = reinterpret_cast<float *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks) + xs_bytes(L, n_chunks, k));
   return w;
@@ -1103,9 +1136,10 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
     if constexpr ((nb == 2 || (nb == 4 && (rt * nm) % 2 == 0)) && up_group(nb, rt, nm) > 1)               \
       if (use_db)                                                                                         \
         return launch_up_db<nb, nm, rt, up_group(nb, rt, nm)>(L, chunk_layer, w.xS, scores, token_mask, active_idx, \
-                                                              n_active, w.items, w.total, max_items, k, w.midB, s); \
+                                                              n_active, w.items, w.total, max_items, k, w.midB,     \
+                                                              w.tok_bits, s);                                         \
     return launch_up<nb, nm, rt>(L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, \
-                                 group, max_items, k, w.midB, s);                                         \
+                                 group, max_items, k, w.midB, w.tok_bits, s);                             \
   }
   BLOCKFFN_CASE(1, 1, 1) BLOCKFFN_CASE(1, 1, 2) BLOCKFFN_CASE(1, 1, 4)
   BLOCKFFN_CASE(1, 2, 1) BLOCKFFN_CASE(1, 2, 2) BLOCKFFN_CASE(1, 2, 4)
@@ -1125,7 +1159,8 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
   const int NB = b_frags(k), KSD = L.d_e / 32;
 #define BLOCKFFN_CASE(nb, ksd) \
   if (NB == nb && KSD == ksd) \
-    return launch_down<nb, ksd>(L, chunk_layer, active_idx, n_active, n_chunks, k, w.midB, w.part, y, s);
+    return launch_down<nb, ksd>(L, chunk_layer, active_idx, n_active, n_chunks, k, w.midB, w.tok_bits, w.zero16, \
+                                w.part, y, s);
   BLOCKFFN_CASE(1, 2) BLOCKFFN_CASE(1, 4) BLOCKFFN_CASE(1, 8)
   BLOCKFFN_CASE(2, 2) BLOCKFFN_CASE(2, 4) BLOCKFFN_CASE(2, 8)
   BLOCKFFN_CASE(4, 2) BLOCKFFN_CASE(4, 4) BLOCKFFN_CASE(4, 8)
