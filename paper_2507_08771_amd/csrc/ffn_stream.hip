@@ -22,7 +22,8 @@
 //         into hi/lo bf16 once per item into LDS in B-operand order; each wave owns distinct
 //         neuron rows of W_up (and W_gate) over the full contraction, so waves never exchange
 //         partial sums.  Swish/gating, router score and mask are applied in registers and mid
-//         is written already split into bf16 hi/lo in the B-operand order of the down kernel.
+//         is written already split into bf16 hi/lo: in the B-operand order of the down kernel at
+//         k <= 8, token-major with the rows of absent tokens left out at k > 8.
 //   down  grid (chunk, 512 output columns); the reduction runs over the union's slots and the
 //         expert's neurons; mid of the next slot is staged through LDS (double buffered) while
 //         the current slot's W_down rows stream; one writer per output element.
