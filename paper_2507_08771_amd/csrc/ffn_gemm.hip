@@ -85,6 +85,32 @@ __global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restr
   }
 }
 
+// The tokens of a chunk that have expert e (mask bit set), in ascending order: lists[(c E + e) k ..],
+// counts[c E + e].  One wave per (chunk, expert).  At the 512-token prefill chunk the union holds
+// nearly every expert but a token only a fifth of them, so the up projection of an expert runs
+// over its own tokens only (the product is the same: the other tokens' terms are masked to zero).
+__global__ __launch_bounds__(64) void token_list_kernel(const uint64_t *__restrict__ token_mask, int W, int E, int k,
+                                                        int32_t *__restrict__ lists, int32_t *__restrict__ counts) {
+  const int lane = threadIdx.x;
+  const int64_t c = blockIdx.x / E;
+  const int e = blockIdx.x % E;
+  int32_t *list = lists + ((size_t)c * E + e) * k;
+  int base = 0;
+  for (int t0 = 0; t0 < k; t0 += 64) {
+    const int t = t0 + lane;
+    const bool bit = t < k && ((token_mask[(c * k + t) * W + (e >> 6)] >> (e & 63)) & 1);
+    const uint64_t b = __ballot(bit);
+    if (bit) list[base + __popcll(b & ((1ull << lane) - 1))] = t;
+    base += __popcll(b);
+  }
+  if (lane == 0) counts[(size_t)c * E + e] = base;
+}
+
+__global__ __launch_bounds__(kThreads) void zero_kernel(uint4 *__restrict__ p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (size_t)gridDim.x * kThreads)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
 // One stage in LDS: operand fragment F (A fragments first, then B) owns 2 KiB: block h (1 KiB)
 // holds rows 8h .. 8h + 7 of the fragment, both K-steps: a whole 128-byte line per row.  The
 // stage is filled by LDS-direct loads (global_load_lds_dwordx4: lane j's 16 bytes land at the
@@ -268,8 +294,8 @@ template <typename T, int NM>
 __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint16_t *__restrict__ xb,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, int k, int tiles_t, int tiles_j,
-    uint16_t *__restrict__ H) {
+    const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, const int32_t *__restrict__ lists,
+    const int32_t *__restrict__ counts, int k, int tiles_t, int tiles_j, uint16_t *__restrict__ H) {
   extern __shared__ uint4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4;
@@ -289,6 +315,11 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   e = min(max(e, 0), E - 1);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int t0 = tt * T::TN;
+  // with token lists the tile's columns are the expert's own tokens list[t0 ..]; H was zeroed and
+  // the rows of the other tokens stay zero
+  const int32_t *list = lists ? lists + ((size_t)c * E + e) * k : nullptr;
+  const int m_e = lists ? min(max(counts[(size_t)c * E + e], 0), k) : k;
+  if (t0 >= m_e) return;   // uniform over the workgroup
   constexpr int kNeurons = T::TM / NM;   // neurons per workgroup
   const int j0 = tj * kNeurons;
   const size_t w_expert = ((size_t)layer * E + e) * d_e;
@@ -306,7 +337,11 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
     int f_rel, rf, piece;
     load_role<T>(i, lane, is_b, f_rel, rf, piece);
     const int f = f0 + f_rel;
-    const int row = is_b ? min(t0 + f * 16 + rf, k - 1) : j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
+    int row = j0 + (gate_wave ? f - T::FA / 2 : f) * 16 + rf;
+    if (is_b) {
+      const int idx = min(t0 + f * 16 + rf, m_e - 1);
+      row = list ? list[idx] : idx;
+    }
     off[i] = row * d + piece * 8;
   }
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
@@ -330,11 +365,14 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // epilogue does not start with a round trip to memory
   const int n = lane & 15;
   float f_tok[T::FJ];
+  int tok_of[T::FJ];   // the chunk's token behind column j of this lane, -1 past the list
 #pragma unroll
   for (int j = 0; j < T::FJ; ++j) {
-    const int t = t0 + (wc * T::FJ + j) * 16 + n;
+    const int idx = t0 + (wc * T::FJ + j) * 16 + n;
+    const int t = idx < m_e ? (list ? list[idx] : idx) : -1;
+    tok_of[j] = t;
     f_tok[j] = 0.0f;
-    if (t < k) {
+    if (t >= 0) {
       const int64_t tok = c * k + t;
       const bool on = token_mask ? (bool)((token_mask[tok * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
       f_tok[j] = on ? scores[tok * E + e] : 0.0f;
@@ -345,8 +383,8 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   // D[i = neuron 4g + q of the fragment][j = token n of the fragment]
 #pragma unroll
   for (int j = 0; j < T::FJ; ++j) {
-    const int t = t0 + (wc * T::FJ + j) * 16 + n;
-    if (t >= k) continue;
+    const int t = tok_of[j];
+    if (t < 0) continue;
     const bool on = f_tok[j] != 0.0f;   // a masked term, and one scaled by a zero score, store +0
     const float f = f_tok[j];
     constexpr int kOut = T::FI / NM;
@@ -472,6 +510,7 @@ int down_splits(const LayerView &L, int64_t n_chunks, int k) {
 struct GemmWs {
   uint16_t *xb, *H;
   int32_t *total, *items;
+  int32_t *lists, *counts;   // per (chunk, expert): its tokens
   float *part;
 };
 
@@ -485,6 +524,10 @@ GemmWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
   w.total = reinterpret_cast<int32_t *>(p);
   w.items = w.total + 64;
   p += align256(((size_t)n_chunks * L.E + 64) * sizeof(int32_t));
+  w.lists = reinterpret_cast<int32_t *>(p);
+  p += align256((size_t)n_chunks * L.E * k * sizeof(int32_t));
+  w.counts = reinterpret_cast<int32_t *>(p);
+  p += align256((size_t)n_chunks * L.E * sizeof(int32_t));
   w.part = reinterpret_cast<float *>(p);
   return w;
 }
@@ -496,6 +539,7 @@ hipError_t launch_up_tile(const LayerView &L, bool gated, const int32_t *chunk_l
   const int tiles_t = (k + T::TN - 1) / T::TN, tiles_j = L.d_e / (T::TM / (gated ? 2 : 1));
   const int64_t grid = (n_chunks * L.E + 7) / 8 * 8 * tiles_t * tiles_j;   // items rounded up to the 8 XCDs
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int32_t *lists = token_mask ? w.lists : nullptr;   // no mask: every token has every expert
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 1>),
@@ -507,10 +551,10 @@ hipError_t launch_up_tile(const LayerView &L, bool gated, const int32_t *chunk_l
   }
   if (gated)
     hipLaunchKernelGGL((up_gemm_kernel<T, 2>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
-                       w.xb, scores, token_mask, active_idx, w.items, w.total, k, tiles_t, tiles_j, w.H);
+                       w.xb, scores, token_mask, active_idx, w.items, w.total, lists, w.counts, k, tiles_t, tiles_j, w.H);
   else
     hipLaunchKernelGGL((up_gemm_kernel<T, 1>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
-                       w.xb, scores, token_mask, active_idx, w.items, w.total, k, tiles_t, tiles_j, w.H);
+                       w.xb, scores, token_mask, active_idx, w.items, w.total, lists, w.counts, k, tiles_t, tiles_j, w.H);
   return hipGetLastError();
 }
 
@@ -543,7 +587,8 @@ bool gemm_supported(const LayerView &L, int wdtype, int k, bool gated) {
 size_t gemm_workspace_bytes(const LayerView &L, int64_t n_chunks, int k) {
   const int splits = down_splits(L, n_chunks, k);
   size_t b = align256((size_t)n_chunks * k * L.d * 2) + align256((size_t)n_chunks * L.E * k * L.d_e * 2) +
-             align256(((size_t)n_chunks * L.E + 64) * sizeof(int32_t));
+             align256(((size_t)n_chunks * L.E + 64) * sizeof(int32_t)) +
+             align256((size_t)n_chunks * L.E * k * sizeof(int32_t)) + align256((size_t)n_chunks * L.E * sizeof(int32_t));
   if (splits > 1) b += align256((size_t)splits * n_chunks * k * L.d * sizeof(float));
   return b;
 }
@@ -560,7 +605,18 @@ hipError_t launch_up_gemm(const LayerView &L, bool gated, const int32_t *chunk_l
   if (err != hipSuccess) return err;
   err = launch_worklist(n_active, n_chunks, L.E, 1, w.items, w.total, s);
   if (err != hipSuccess) return err;
-  if (big_up(L, k, gated))
+  if (token_mask) {
+    hipLaunchKernelGGL(token_list_kernel, dim3((unsigned)(n_chunks * L.E)), dim3(64), 0, s, token_mask, L.W, L.E, k,
+                       w.lists, w.counts);
+    const size_t n16 = (size_t)n_chunks * L.E * k * L.d_e / 8;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)std::min<size_t>((n16 + kThreads - 1) / kThreads, 4096)),
+                       dim3(kThreads), 0, s, reinterpret_cast<uint4 *>(w.H), n16);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
+  // With token lists an expert's tile has about k / 5 columns (102 of 512): 128 token columns hold
+  // them, and the 256-wide tile would spend more than half of its matrix work on padding.
+  if (big_up(L, k, gated) && !token_mask)
     return launch_up_tile<TileBig>(L, gated, chunk_layer, scores, token_mask, active_idx, w, n_chunks, k, s);
   return launch_up_tile<TileSmall>(L, gated, chunk_layer, scores, token_mask, active_idx, w, n_chunks, k, s);
 }

@@ -123,6 +123,18 @@ def test_k32_many_chunks(gated):
     np.testing.assert_array_equal(gpu["scores"] == 0, ref["scores"] == 0)
 
 
+@pytest.mark.parametrize("k,p_active", [(400, 0.5), (512, 0.95), (96, 0.02)])
+def test_large_chunks_token_lists(k, p_active):
+    """The up projection of a large chunk runs over each expert's own tokens: an expert with more
+    than 128 of them (two token tiles, the second ragged), with nearly all, and experts with a
+    handful or a single token."""
+    w = wl.Workload("t", d=1024, E=32, d_e=128, wdtype="bf16", gated=True, k=k, n_chunks=2, sigma=0.5, seed=k,
+                    p_active=p_active)
+    ref, gpu = both(w, dense=False)
+    pu.assert_integers_equal(gpu, ref)
+    print(pu.assert_floats_close(gpu, ref, "bf16", dense=False, bar=pu.GEMM_BAR, l2_bar=pu.GEMM_L2_BAR))
+
+
 def test_layer_rotation_gain_and_eps():
     # chunks walk through 5 distinct weight sets; RMSNorm gain drawn at random, large eps
     w = wl.Workload("t", d=512, E=48, d_e=32, wdtype="bf16", gated=True, k=8, n_chunks=23, sigma=0.3, seed=5)
