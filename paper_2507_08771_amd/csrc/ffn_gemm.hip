@@ -15,8 +15,12 @@
 //         few workgroups to fill the chip the slots are split and the partial sums are added
 //         by a second kernel in a fixed order (no atomics; results repeat bit for bit).
 //
-// As in the paper's kernel every token of the chunk is computed for every expert of the union
-// and the sparse pattern of A is applied afterwards.
+// The paper's kernel computes every token of the chunk for every expert of the union and applies
+// the sparse pattern of A afterwards; that is right for chunks of up to 32 tokens.  In a chunk
+// of hundreds of tokens the union holds nearly every expert while a token has a fifth of them,
+// so here the up projection of (chunk, expert) gathers the expert's own tokens (token_list_kernel)
+// into 128-column tiles and scatters their rows of mid; the other rows stay zero (mid is zeroed
+// first).  The terms left out are exactly those the mask would have zeroed.
 #include <algorithm>
 
 #include "common.hpp"
