@@ -500,10 +500,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   // Router scores and mask words of the item's tokens, [item parity][slot][score, mask lo, mask
   // hi][token], also by LDS-direct loads: wave sl requests slot sl's when the item starts, the
   // K-chunks' barriers publish them, the epilogue reads them from LDS.  Loaded into registers they
-  // made the epilogue wait for "every load so far" (the compiler cannot count across the K-chunk
-  // loop), which drained the ring; with the epilogue's stores, whose completion the ring's next
-  // counted wait includes, and the ring's restart that was three memory round trips per item in
-  // which the workgroup's four waves, tied together by the K-chunk barriers, requested nothing.
+  // made the epilogue start with a wait for "every load so far" (the compiler cannot count across
+  // the K-chunk loop), i.e. for the ring's 16 loads of the next item; this way the kernel has no
+  // such wait at all.
   __shared__ uint32_t scoreS[2][G][3][64];
   auto request_scores = [&](int ipar, int64_t c, uint32_t es, int k) {
     if (wave < G) {   // uniform over the wave; a slot past ns repeats the last one
