@@ -209,7 +209,7 @@ __device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int T
 
 // Epilogue of one (chunk, slot), entirely inside the wave: lane (n = lane % 16, g) holds rows
 // 4g .. 4g + 3 of each tile.  Swish / gating, router score and mask bit; mid is written split into
-// bf16 hi/lo in the order the down kernel's B operand reads it.
+// bf16 hi/lo in the layout described above.
 template <int NB, int NM, int RT>
 __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_tiles(NB)],
                                               const float (&f_tok)[acc_tiles(NB)], const LayerView &L, int64_t c,
