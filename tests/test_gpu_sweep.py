@@ -1,0 +1,64 @@
+"""Seeded sweep of shapes across the kernels' dispatch boundaries (chunk sizes around 8 / 16 / 32 /
+192, 63 / 64 / 65 chunks, one to 130 experts, three expert widths, gated and Eq. 2 experts, one
+or three weight sets, several activation rates): the whole path against the oracle."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_08771_amd import workloads as wl
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def draw(rng, large):
+    if large:
+        k = rng.choice([33, 48, 64, 100, 129, 191, 192, 200, 256, 257, 300, 400])
+        d, d_e, E = rng.choice([512, 1024]), rng.choice([64, 128, 256]), rng.choice([3, 8, 17, 32, 64])
+        C, p = rng.choice([1, 2, 3, 9]), rng.choice([0.05, 0.2, 0.6])
+    else:
+        k = rng.randint(1, 32)
+        d, d_e = rng.choice([512, 1024, 1536, 2048, 2560]), rng.choice([64, 128, 256])
+        E = rng.choice([1, 2, 7, 16, 33, 64, 65, 100, 128, 130])
+        C, p = rng.choice([1, 2, 3, 8, 9, 31, 63, 64, 65, 71, 130]), rng.choice([0.05, 0.2, 0.5])
+    while C * k * E * d_e * d > 6e10 and C > 1:   # keep the oracle's work to about a second
+        C = max(1, C // 2)
+    return dict(d=d, E=E, d_e=d_e, k=k, n_chunks=C, gated=rng.random() < 0.5, p_active=p,
+                sigma=rng.choice([0.0, 0.3, 0.6]))
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_seeded_shapes(seed):
+    rng = random.Random(seed)
+    done = 0
+    for it in range(30):
+        cfg = draw(rng, large=it % 5 == 4)
+        n_layers = rng.choice([1, 1, 3])
+        w = wl.Workload("sweep", wdtype="bf16", seed=1000 * seed + it, **cfg)
+        layers = wl.make_layers(w, n_layers)
+        cl = wl.make_chunk_layer(w, n_layers) if n_layers > 1 else None
+        try:
+            x = wl.make_tokens(w, layers, cl)
+        except RuntimeError:
+            continue   # the generator could not keep every pre-activation off the guard band
+        print("case", it, cfg, "layers", n_layers, flush=True)
+        ref = pu.run_oracle(layers, x, w.k, cl, dense=False)
+        gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, cl, dense=False)
+        pu.assert_integers_equal(gpu, ref)
+        np.testing.assert_array_equal(gpu["scores"] == 0, ref["scores"] == 0)
+        # scores: the bound of score_error_allowed(); the outputs of the rows that meet the plain
+        # 1e-5 bar (all but the few tokens whose only active expert is barely active, whose score
+        # error the FFN passes on) are held to the usual bars
+        err_s = np.abs(gpu["scores"].astype(np.float64) - ref["scores"]).max(axis=1)
+        assert np.all(err_s <= pu.score_error_allowed(layers, x, w.k, cl, ref["scores"]))
+        rms = np.sqrt((ref["scores"].astype(np.float64) ** 2).mean(axis=1))
+        good = err_s <= 1e-5 * np.maximum(rms, 1e-30)
+        assert good.mean() >= 0.9
+        e_y = pu.row_rel_err(gpu["y"][good], ref["y"][good]).max(initial=0.0)
+        bar = pu.GEMM_BAR if w.k > 32 else pu.TIGHT["bf16"]
+        assert e_y <= bar, "sparse FFN output off by %.3g (bar %.1g) in %s" % (e_y, bar, cfg)
+        done += 1
+    assert done >= 20
