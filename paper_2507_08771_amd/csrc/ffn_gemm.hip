@@ -18,7 +18,7 @@
 // The paper's kernel computes every token of the chunk for every expert of the union and applies
 // the sparse pattern of A afterwards; that is right for chunks of up to 32 tokens.  In a chunk
 // of hundreds of tokens the union holds nearly every expert while a token has a fifth of them,
-// so here the up projection of (chunk, expert) gathers the expert's own tokens (token_list_kernel)
+// so here the up projection of (chunk, expert) gathers the expert's own tokens (prepare_kernel)
 // into 128-column tiles and scatters their rows of mid; the other rows stay zero (mid is zeroed
 // first).  The terms left out are exactly those the mask would have zeroed.
 #include <algorithm>
@@ -76,29 +76,16 @@ __device__ __forceinline__ float swish_fast(float u) {
   return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
 }
 
-__global__ __launch_bounds__(kThreads) void cvt_bf16_kernel(const float *__restrict__ x, uint16_t *__restrict__ xb,
-                                                            size_t n8) {
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n8; i += (size_t)gridDim.x * kThreads) {
-    const float4 a = reinterpret_cast<const float4 *>(x)[2 * i], b = reinterpret_cast<const float4 *>(x)[2 * i + 1];
-    uint4 o;
-    o.x = bf16_bits(a.x) | bf16_bits(a.y) << 16;
-    o.y = bf16_bits(a.z) | bf16_bits(a.w) << 16;
-    o.z = bf16_bits(b.x) | bf16_bits(b.y) << 16;
-    o.w = bf16_bits(b.z) | bf16_bits(b.w) << 16;
-    reinterpret_cast<uint4 *>(xb)[i] = o;
-  }
-}
-
 // The tokens of a chunk that have expert e (mask bit set), in ascending order: lists[(c E + e) k ..],
 // counts[c E + e].  One wave per (chunk, expert).  At the 512-token prefill chunk the union holds
 // nearly every expert but a token only a fifth of them, so the up projection of an expert runs
 // over its own tokens only (the product is the same: the other tokens' terms are masked to zero).
-__global__ __launch_bounds__(64) void token_list_kernel(const uint64_t *__restrict__ token_mask, int W, int E, int k,
-                                                        int32_t *__restrict__ lists, int32_t *__restrict__ counts) {
-  const int lane = threadIdx.x;
-  const int64_t c = blockIdx.x / E;
-  const int e = blockIdx.x % E;
-  int32_t *list = lists + ((size_t)c * E + e) * k;
+__device__ __forceinline__ void token_list_wave(const uint64_t *__restrict__ token_mask, int W, int E, int k,
+                                                int64_t pair, int lane, int32_t *__restrict__ lists,
+                                                int32_t *__restrict__ counts) {
+  const int64_t c = pair / E;
+  const int e = (int)(pair % E);
+  int32_t *list = lists + (size_t)pair * k;
   int base = 0;
   for (int t0 = 0; t0 < k; t0 += 64) {
     const int t = t0 + lane;
@@ -107,12 +94,36 @@ __global__ __launch_bounds__(64) void token_list_kernel(const uint64_t *__restri
     if (bit) list[base + __popcll(b & ((1ull << lane) - 1))] = t;
     base += __popcll(b);
   }
-  if (lane == 0) counts[(size_t)c * E + e] = base;
+  if (lane == 0) counts[pair] = base;
 }
 
-__global__ __launch_bounds__(kThreads) void zero_kernel(uint4 *__restrict__ p, size_t n16) {
-  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (size_t)gridDim.x * kThreads)
-    p[i] = make_uint4(0, 0, 0, 0);
+// The three passes ahead of the up projection in one launch (they are independent, and as three
+// launches of a few microseconds each they ran one after the other): blocks [0, cvt_blocks) round
+// x to bf16, the next zero_blocks clear mid, the rest build the token lists, one wave per
+// (chunk, expert).  Without a mask there are no lists and nothing to clear.
+__global__ __launch_bounds__(kThreads) void prepare_kernel(const float *__restrict__ x, uint16_t *__restrict__ xb,
+                                                           size_t n8, int cvt_blocks, uint4 *__restrict__ H, size_t n16,
+                                                           int zero_blocks, const uint64_t *__restrict__ token_mask, int W,
+                                                           int E, int k, int64_t n_pairs, int32_t *__restrict__ lists,
+                                                           int32_t *__restrict__ counts) {
+  const int b = blockIdx.x;
+  if (b < cvt_blocks) {
+    for (size_t i = (size_t)b * kThreads + threadIdx.x; i < n8; i += (size_t)cvt_blocks * kThreads) {
+      const float4 a = reinterpret_cast<const float4 *>(x)[2 * i], c = reinterpret_cast<const float4 *>(x)[2 * i + 1];
+      uint4 o;
+      o.x = bf16_bits(a.x) | bf16_bits(a.y) << 16;
+      o.y = bf16_bits(a.z) | bf16_bits(a.w) << 16;
+      o.z = bf16_bits(c.x) | bf16_bits(c.y) << 16;
+      o.w = bf16_bits(c.z) | bf16_bits(c.w) << 16;
+      reinterpret_cast<uint4 *>(xb)[i] = o;
+    }
+  } else if (b < cvt_blocks + zero_blocks) {
+    for (size_t i = (size_t)(b - cvt_blocks) * kThreads + threadIdx.x; i < n16; i += (size_t)zero_blocks * kThreads)
+      H[i] = make_uint4(0, 0, 0, 0);
+  } else {
+    const int64_t pair = (int64_t)(b - cvt_blocks - zero_blocks) * (kThreads / 64) + (threadIdx.x >> 6);
+    if (pair < n_pairs) token_list_wave(token_mask, W, E, k, pair, threadIdx.x & 63, lists, counts);
+  }
 }
 
 // One stage in LDS: operand fragment F (A fragments first, then B) owns 2 KiB: block h (1 KiB)
@@ -603,21 +614,19 @@ hipError_t launch_up_gemm(const LayerView &L, bool gated, const int32_t *chunk_l
   if (n_chunks <= 0) return hipSuccess;
   GemmWs w = carve(L, n_chunks, k, ws);
   const size_t n8 = (size_t)n_chunks * k * L.d / 8;
-  hipLaunchKernelGGL(cvt_bf16_kernel, dim3((unsigned)std::min<size_t>((n8 + kThreads - 1) / kThreads, 4096)),
-                     dim3(kThreads), 0, s, x, w.xb, n8);
+  const size_t n16 = token_mask ? (size_t)n_chunks * L.E * k * L.d_e / 8 : 0;
+  const int64_t n_pairs = token_mask ? n_chunks * L.E : 0;
+  const int cvt_blocks = (int)std::min<size_t>((n8 + kThreads - 1) / kThreads, 2048);
+  const int zero_blocks = (int)std::min<size_t>((n16 + kThreads - 1) / kThreads, 2048);
+  const int64_t list_blocks = (n_pairs + kThreads / 64 - 1) / (kThreads / 64);
+  if (cvt_blocks + zero_blocks + list_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(prepare_kernel, dim3((unsigned)(cvt_blocks + zero_blocks + list_blocks)), dim3(kThreads), 0, s, x,
+                     w.xb, n8, cvt_blocks, reinterpret_cast<uint4 *>(w.H), n16, zero_blocks, token_mask, L.W, L.E, k,
+                     n_pairs, w.lists, w.counts);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   err = launch_worklist(n_active, n_chunks, L.E, 1, w.items, w.total, s);
   if (err != hipSuccess) return err;
-  if (token_mask) {
-    hipLaunchKernelGGL(token_list_kernel, dim3((unsigned)(n_chunks * L.E)), dim3(64), 0, s, token_mask, L.W, L.E, k,
-                       w.lists, w.counts);
-    const size_t n16 = (size_t)n_chunks * L.E * k * L.d_e / 8;
-    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)std::min<size_t>((n16 + kThreads - 1) / kThreads, 4096)),
-                       dim3(kThreads), 0, s, reinterpret_cast<uint4 *>(w.H), n16);
-    err = hipGetLastError();
-    if (err != hipSuccess) return err;
-  }
   // With token lists an expert's tile has about k / 5 columns (102 of 512): 128 token columns hold
   // them, and the 256-wide tile would spend more than half of its matrix work on padding.
   if (big_up(L, k, gated) && !token_mask)
