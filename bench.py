@@ -11,9 +11,16 @@ weight stream comes from HBM, as it does when one sequence walks through a model
 
 Prints ONE JSON line.  `value` is the active-expert weight bytes of the step divided by the
 step's wall time (GB/s); the same line carries microseconds per chunk, tokens/s, the
-fraction of the 8 TB/s HBM peak, the speedup over the dense FFN of equal size (same kernels,
-all experts), the per-kernel split measured with HIP events on the launch stream, the
-roofline of the dominant kernel, and the CPU oracle timed on a bounded sample.
+fraction of the 8 TB/s HBM peak and of the read-stream ceiling measured in the same process
+(a plain 128-bit-load read kernel over 8 GiB), the speedup over the dense FFN of equal size
+(same kernels, all experts), the per-kernel split measured with HIP events on the launch
+stream, the roofline of the dominant kernel, and the CPU oracle timed on a bounded sample.
+
+`--all` also runs every measured configuration (single-token decode, k = 8, k = 32 trees, the
+24-layer decode stack and the 512-token prefill), each with gated and with Eq. 2 experts, each
+cold (chunks rotating through distinct weight sets) and warm (one weight set, cache assisted),
+and appends one JSON record per run to gpurun_out/bench_all.jsonl; the line printed at the
+end is still the default one.
 """
 
 from __future__ import annotations
@@ -31,8 +38,12 @@ if ROOT not in sys.path:
 HBM_PEAK = 8.0e12  # bytes/s, MI355X HBM3E
 
 # HBM bytes per launch of the up kernel from rocprofv3 (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
-# factors a plain 1 GiB device copy gives), keyed by (workload, replicas, gated); see profiles/.
-MEASURED_TRAFFIC = {("spec_k8", 32, True): 22229467 * 1024 * 2.0 + 170216 * 1024 * 1.0}
+# factors a plain 1 GiB device copy gives), keyed by (workload, replicas, gated), each with the
+# profile summary it was read from: a number from an earlier build of the kernels, labelled as
+# such in the output (`traffic_source`), never a measurement of the run that prints it.
+MEASURED_TRAFFIC = {
+    ("spec_k8", 32, True): (22229467 * 1024 * 2.0 + 170216 * 1024 * 1.0, "profiles/spec_k8_stream_kernels.md"),
+}
 
 
 def parse():
@@ -59,7 +70,39 @@ def parse():
                    help="only run a plain device copy of 1 GiB five times (reference for the rocprofv3 byte counters)")
     p.add_argument("--traffic-bytes", type=float, default=None,
                    help="HBM bytes per launch of the dominant kernel from rocprofv3 counters, if known")
+    p.add_argument("--all", action="store_true",
+                   help="also run every configuration (gated and Eq. 2 experts, cold and warm) and append one "
+                        "JSON record each to gpurun_out/bench_all.jsonl")
+    p.add_argument("--no-ceiling", action="store_true", help="skip the read-stream ceiling measurement")
+    p.add_argument("--ceiling-gib", type=int, default=8, help="size of the buffer the read-stream ceiling is measured on")
     return p.parse_args()
+
+
+_CEILING = None
+
+
+def stream_ceiling(gib):
+    """GB/s of a plain 128-bit-load read stream over `gib` GiB on this device, best of the launch
+    shapes the library offers, each the mean of 5 launches after one warm-up.  Measured once per process."""
+    global _CEILING
+    if _CEILING is not None:
+        return _CEILING
+    import torch
+
+    from paper_2507_08771_amd import binding as B
+
+    buf = torch.empty((gib << 30,), dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    sink = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    best, per_variant = 0.0, {}
+    for variant in range(4):
+        us = timed_us(lambda: B.blockffn_stream_read(buf, variant, sink), reps=5)
+        per_variant[str(variant)] = buf.numel() / us / 1e3
+        best = max(best, per_variant[str(variant)])
+    del buf
+    torch.cuda.empty_cache()
+    _CEILING = {"GBps": best, "bytes": gib << 30, "by_launch_shape": per_variant}
+    return _CEILING
 
 
 def timed_us(fn, reps=5):
@@ -128,13 +171,14 @@ def extras(w, L, x, buf, chunk_layer):
 
 
 def cpu_baseline(w, layers, x, chunk_layer, n_sample, expert_bytes):
-    """The oracle as it stands, timed on the host cores over a bounded sample of the same workload."""
+    """The oracle as it stands, timed on the host cores over a bounded sample of the same workload.
+    Same source as the checker; built -O3 -march=native for the host it runs on (OpenMP over chunks)."""
     import numpy as np
 
     import oracle
     from paper_2507_08771_amd import workloads as wl
 
-    oracle.build()
+    oracle.use_native_build()
     cl = chunk_layer.cpu().numpy()
     order = np.argsort(cl, kind="stable")[:n_sample]          # chunks of the lowest-numbered weight sets
     groups = {}
@@ -155,42 +199,37 @@ def cpu_baseline(w, layers, x, chunk_layer, n_sample, expert_bytes):
     n = len(order)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": active * expert_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": "%d of %d chunks (router + union + chunk-sparse FFN in fp64), %.1f s" % (n, w.n_chunks, dt),
+            "sample": "%d of %d chunks (router + union + chunk-sparse FFN in fp64, gcc -O3 -march=native -fopenmp), "
+                      "%.1f s" % (n, w.n_chunks, dt),
             "us_per_chunk": dt / n * 1e6}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (chunks are independent and would "
-              "shard data-parallel with replicated weights); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def default_replicas(w):
+    """Weight sets the chunks rotate through when --replicas is not given: at least 64, so that no
+    two of the chunks in flight at one moment (about 50 at k = 8) read the same set, and at least
+    6 GiB of weights, 24 times the 256 MiB last-level cache."""
+    set_bytes = w.E * w.expert_bytes
+    return max(1, min(max(64, -(-(6 << 30) // set_bytes)), w.n_chunks))
 
+
+def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=None, dense_steps=None, warm=False,
+        with_cpu=False, with_extras=False):
+    """One workload: generates it, times `steps` steps, returns the record."""
+    import numpy as np
     import torch
 
     from paper_2507_08771_amd import binding as B
     from paper_2507_08771_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    torch.cuda.set_device(0)
     dev = "cuda"
-    if args.calibrate_copy:
-        src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)   # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
-        return
-    w = wl.WORKLOADS[args.workload]
-    if args.chunks:
-        w = w.replace(n_chunks=args.chunks)
-    if args.swish:
-        w = w.replace(gated=False)
-    set_bytes = w.E * w.expert_bytes
-    R = args.replicas if args.replicas > 0 else max(32, -(-(3 << 30) // set_bytes))
+    steps = args.steps if steps is None else steps
+    dense_steps = args.dense_steps if dense_steps is None else dense_steps
+    w = wl.WORKLOADS[name]
+    if chunks:
+        w = w.replace(n_chunks=chunks)
+    if gated is not None:
+        w = w.replace(gated=gated)
+    R = 1 if warm else (replicas if replicas > 0 else default_replicas(w))
     R = max(1, min(R, w.n_chunks))
 
     layers = wl.make_layers(w, R, device=dev)
@@ -206,7 +245,7 @@ def main():
     # of the stacked weights) and no per-chunk layer table for the kernels to look up
     layer_of = chunk_layer.cpu().tolist()
     views = ([B.Layer.from_dict({n: (None if t is None else t[r:r + 1]) for n, t in layers.items()}, gain=False)
-              for r in range(R)] if args.sequential else None)
+              for r in range(R)] if sequential else None)
 
     def step_sequential():
         for c in range(C):
@@ -219,7 +258,7 @@ def main():
                                   buf.n_active[c:c + 1], 1, k, buf.y[t0_:t1_], buf.workspace)
 
     def step(ev=None):
-        if args.sequential:
+        if sequential:
             if ev: ev[0].record()
             step_sequential()
             if ev:
@@ -240,20 +279,22 @@ def main():
         step()
     torch.cuda.synchronize()
     buf.stats.zero_()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    ms_per_step = wall / args.steps * 1e3
-    stage_us = {s: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps * 1e3 for i, s in enumerate(stages)}
+    ms_per_step = wall / steps * 1e3
+    step_ms = sorted(ev[0].elapsed_time(ev[4]) for ev in events)     # HIP events around each step
+    stage_us = {s: sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / steps * 1e3 for i, s in enumerate(stages)}
+    up_us = sorted(ev[2].elapsed_time(ev[3]) * 1e3 for ev in events)
     n_active_sum = int(buf.n_active.sum().item())
     stats = buf.stats.cpu().numpy()
-    tls = float(stats[0]) / (args.steps * w.n_tok * w.E)
-    cls = float(stats[1]) / (args.steps * C * w.E)
+    tls = float(stats[0]) / (steps * w.n_tok * w.E)
+    cls = float(stats[1]) / (steps * C * w.E)
     sw = 2 if w.wdtype == "bf16" else 4
     active_bytes = n_active_sum * w.expert_bytes
     up_bytes = n_active_sum * (w.n_mats - 1) * w.d * w.d_e * sw
@@ -262,7 +303,7 @@ def main():
     dense_ms = None
 
     def dense_step():
-        if not args.sequential:
+        if not sequential:
             B.blockffn_dense_ffn(L, x, buf.scores, C, k, y_dense, buf.workspace, chunk_layer)
             return
         for c in range(C):   # the dense layer stack: router, then every expert of the layer
@@ -271,42 +312,55 @@ def main():
             B.blockffn_router(Lc, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_])
             B.blockffn_dense_ffn(Lc, x[t0_:t1_], buf.scores[t0_:t1_], 1, k, y_dense[t0_:t1_], buf.workspace)
 
-    if args.dense_steps > 0:
+    if dense_steps > 0:
         dense_step()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for _ in range(args.dense_steps):
+        for _ in range(dense_steps):
             dense_step()
         e1.record()
         torch.cuda.synchronize()
-        dense_ms = e0.elapsed_time(e1) / args.dense_steps
+        dense_ms = e0.elapsed_time(e1) / dense_steps
     ffn_ms = (stage_us["up"] + stage_us["down"]) / 1e3
-    if args.sequential:   # whole steps on both sides (router included): there is no per-kernel split here
+    if sequential:   # whole steps on both sides (router included): there is no per-kernel split here
         ffn_ms = ms_per_step
 
     up_s = stage_us["up"] * 1e-6
-    if args.sequential:   # no per-kernel split in this mode: price the whole step against all active bytes
+    if sequential:   # no per-kernel split in this mode: price the whole step against all active bytes
         up_s, up_bytes = ms_per_step * 1e-3, active_bytes
+    traffic, traffic_source = None, None
+    if args.traffic_bytes is not None:
+        traffic, traffic_source = args.traffic_bytes, "--traffic-bytes"
+    elif not chunks and (w.name, R, w.gated) in MEASURED_TRAFFIC:
+        traffic, traffic_source = MEASURED_TRAFFIC[(w.name, R, w.gated)]
+        traffic_source += " (rocprofv3 counters of an earlier run of this workload, not of this run)"
+    value = active_bytes / (ms_per_step * 1e-3) / 1e9
+    dense_bytes = C * w.E * w.expert_bytes
     out = {
         "metric": "µs/chunk + active-weight HBM GB/s (%% peak) at k=%d; speedup vs dense FFN" % k,
-        "value": active_bytes / (ms_per_step * 1e-3) / 1e9,
+        "value": value,
         "unit": "GB/s (active-expert weight bytes / step wall time)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "step_ms_hip_events": {"median": step_ms[len(step_ms) // 2], "min": step_ms[0], "max": step_ms[-1]},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights, f32 activations and accumulation" if w.wdtype == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: d=%d E=%d d_e=%d %s experts, k=%d x %d chunks, sigma=%.2f, %d weight sets (%.2f GB)%s"
+        "config": {"workload": "%s: d=%d E=%d d_e=%d %s experts, k=%d x %d chunks, sigma=%.2f, %d weight sets (%.2f GB)%s%s"
                                % (w.name, w.d, w.E, w.d_e, "gated" if w.gated else "swish", k, C, w.sigma, R,
                                   R * w.E * w.expert_bytes / 1e9,
-                                  ", chunks enqueued one after the other" if args.sequential else ""),
-                   "replicas": R, "sequential": args.sequential},
+                                  ", chunks enqueued one after the other" if sequential else "",
+                                  ", WARM: one weight set for every chunk, served largely by the caches (not an HBM figure)"
+                                  if warm and C > 1 else ""),
+                   "name": w.name, "expert_kind": "gated" if w.gated else "swish",
+                   "replicas": R, "sequential": sequential, "mode": "warm" if warm and C > 1 else "cold"},
         "us_per_chunk": ms_per_step * 1e3 / C,
         "tokens_per_s": w.n_tok / (ms_per_step * 1e-3),
         "pct_hbm_peak": 100.0 * active_bytes / (ms_per_step * 1e-3) / HBM_PEAK,
         "stage_us": stage_us,
         "mean_active_experts": n_active_sum / C, "tls": tls, "cls_k": cls,
         "dense_ffn_ms": dense_ms, "sparse_ffn_ms": ffn_ms,
+        "dense_ffn_GBps": None if dense_ms is None else dense_bytes / (dense_ms * 1e-3) / 1e9,
         "speedup_vs_dense": None if dense_ms is None else dense_ms / ffn_ms,
         "E_over_mean_active": w.E * C / max(n_active_sum, 1),
         "paper_context": "up to 3.67x end-to-end over dense decoding on Jetson Orin NX (another machine, Table 6)",
@@ -314,15 +368,86 @@ def main():
                                % (" and W_gate" if w.gated else ""),
                      "bound": "hbm", "achieved": up_bytes / up_s / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": up_bytes / up_s / HBM_PEAK,
-                     "traffic": args.traffic_bytes if args.traffic_bytes is not None
-                     else (MEASURED_TRAFFIC.get((w.name, R, w.gated)) if not args.chunks else None),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes": up_bytes,
-                     "avg_launch_us": stage_us["up"]},
+                     "avg_launch_us": stage_us["up"],
+                     "launch_us_hip_events": {"median": up_us[len(up_us) // 2], "min": up_us[0]}},
     }
-    if args.extras:
+    if not args.no_ceiling:
+        del y_dense
+        ceil = stream_ceiling(args.ceiling_gib)
+        out["stream_ceiling_GBps"] = ceil["GBps"]
+        out["stream_ceiling"] = ceil
+        out["frac_of_ceiling"] = value / ceil["GBps"]
+        out["roofline"]["frac_of_stream_ceiling"] = out["roofline"]["achieved"] / ceil["GBps"]
+    if with_extras:
         out["extras"] = extras(w, L, x, buf, chunk_layer)
-    if not args.no_cpu_baseline:
+    if with_cpu:
         out["cpu_baseline"] = cpu_baseline(w, layers, x, chunk_layer, min(args.cpu_sample_chunks, C), w.expert_bytes)
+    return out
+
+
+# (workload, keyword arguments of run()) of --all: the measured configurations, cold
+ALL_RUNS = [
+    ("decode_k1", dict()),
+    ("spec_k8", dict()),
+    ("tree_k32", dict(steps=5, dense_steps=2)),
+    ("stack_decode_k8", dict(chunks=24, replicas=24, sequential=True)),
+    ("stack_prefill_512", dict(chunks=8, replicas=8, steps=10, dense_steps=2)),
+    ("paper_ar_k1", dict()),
+    ("paper_tree_k32", dict(steps=10, dense_steps=2)),
+]
+
+
+def run_all(args):
+    import torch
+
+    path = os.path.join(ROOT, "gpurun_out", "bench_all.jsonl")
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "a") as f:
+        for name, kw in ALL_RUNS:
+            kinds = (None,) if name.startswith("paper_") else (True, False)   # the paper shapes are Eq. 2 only
+            for gated in kinds:
+                for warm in (False, True):
+                    if warm and kw.get("sequential"):
+                        continue    # a layer stack has one weight set per layer by definition
+                    rec = run(args, name, gated=gated, warm=warm, **kw)
+                    f.write(json.dumps(rec) + "\n")
+                    f.flush()
+                    print("%-18s %-6s %-4s %8.1f GB/s  %5.1f %% of 8 TB/s  %8.2f us/chunk  speedup %s (bound %.2f)"
+                          % (name, rec["config"]["expert_kind"], rec["config"]["mode"], rec["value"], rec["pct_hbm_peak"],
+                             rec["us_per_chunk"],
+                             "-" if rec["speedup_vs_dense"] is None else "%.2f" % rec["speedup_vs_dense"],
+                             rec["E_over_mean_active"]), file=sys.stderr, flush=True)
+                    torch.cuda.empty_cache()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (chunks are independent and would "
+              "shard data-parallel with replicated weights); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "calibrate_copy_bytes_written": src.numel() * 4}))
+        return
+    if args.all:
+        run_all(args)
+    out = run(args, args.workload, gated=False if args.swish else None, replicas=args.replicas,
+              sequential=args.sequential, chunks=args.chunks, with_cpu=not args.no_cpu_baseline,
+              with_extras=args.extras)
     print(json.dumps(out))
 
 

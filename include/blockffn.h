@@ -34,7 +34,11 @@
  *   by argument checking.  No exceptions, no exit, no output to stdout/stderr.
  * - Inputs are assumed finite.  A NaN pre-activation counts as inactive.
  *
- * Limits: 1 <= N_e <= 256, 1 <= k <= 512, d % 8 == 0, d_e % 8 == 0, d_e <= 1024, d <= 16384.
+ * - An entry of active_idx below n_active that lies outside [0, N_e) is an empty slot: it
+ *   contributes nothing to y, on every kernel path (n_active itself is clamped into [0, N_e]).
+ *
+ * Limits: 1 <= N_e <= 256, 1 <= k <= 512, d % 8 == 0, d_e % 8 == 0, d_e <= 1024, d <= 16384,
+ * n_chunks * k < 2^31 and n_chunks * N_e < 2^31 per call (beyond: BLOCKFFN_ERR_UNSUPPORTED).
  */
 #ifndef BLOCKFFN_H
 #define BLOCKFFN_H
@@ -191,6 +195,22 @@ int blockffn_cls_sweep(const uint64_t *token_mask, int64_t n_tok, int64_t seq_le
  * The integer outputs are exact; ratio is their fp64 evaluation. */
 int blockffn_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_len, int32_t n_experts,
                          int64_t *num, int64_t *cnt, double *ratio, void *stream);
+
+/* Kernel selection for cross-checks (no step of the layer): the FFN entry points pick the
+ * weight-streaming or the matrix-core kernels where the shape allows and the shape-generic fp32
+ * ALU kernels otherwise.  mode 1 keeps every later call of the process on the shape-generic
+ * kernels, mode 0 on the automatic choice, mode -1 (the initial state) follows the environment
+ * variable BLOCKFFN_FORCE_GENERIC (=1: generic), which is read once per process.  Workspace sizes
+ * do not depend on it.  Returns BLOCKFFN_ERR_INVALID for any other mode. */
+int blockffn_force_generic(int mode);
+
+/* Measurement helper (no step of the layer): reads `bytes` bytes (rounded down to 16) at buf with
+ * plain 128-bit loads and nothing else, so that a benchmark can time what a pure read stream
+ * reaches on this device and report the weight-streaming kernels against that measured ceiling
+ * as well as against the nominal HBM peak.  buf: device memory, 16-byte aligned.  variant 0..3
+ * selects the tile a workgroup reads (1 MiB, 256 KiB, 256 KiB, 64 KiB) and the loads in flight per
+ * lane (8, 8, 16, 16).  sink: 4 writable device bytes (written to in practice never). */
+int blockffn_stream_read(const void *buf, size_t bytes, int32_t variant, uint32_t *sink, void *stream);
 
 /* Bytes of workspace the two FFN entry points need for this shape (0 on invalid arguments). */
 size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k);

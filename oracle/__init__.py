@@ -22,6 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "blockffn_oracle.c")
 _SO = os.path.join(_HERE, "liboracle.so")
 _lib = None
+_native = False
 
 
 def build(force: bool = False) -> str:
@@ -30,6 +31,24 @@ def build(force: bool = False) -> str:
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
+
+
+def use_native_build() -> str:
+    """Switch this process to a build of the SAME source with ``-O3 -march=native`` for the host it
+    runs on: the build the timed CPU baseline uses.  It is compiled on the spot into the host's
+    temp directory (code for this host's instruction set must not travel to another machine) and
+    keeps ISO floating-point semantics (-std=c11: no contraction, no fast-math), so it computes
+    what the -O2 build computes."""
+    global _lib, _native
+    import tempfile
+    so = os.path.join(tempfile.gettempdir(), "liboracle_native_%d.so" % os.getuid())
+    cmd = ["gcc", "-O3", "-march=native", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    _lib = ctypes.CDLL(so)
+    for name in ("oracle_router", "oracle_chunk_union", "oracle_sparse_ffn", "oracle_dense_ffn"):
+        getattr(_lib, name).restype = ctypes.c_int
+    _native = True
+    return so
 
 
 class _Layer(ctypes.Structure):

@@ -24,7 +24,8 @@ OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
            "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_workspace_bytes", "blockffn_strerror",
            "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio", "blockffn_router_preact",
-           "blockffn_router_losses", "blockffn_losses_workspace_bytes", "blockffn_offload_sim")
+           "blockffn_router_losses", "blockffn_losses_workspace_bytes", "blockffn_offload_sim",
+           "blockffn_stream_read", "blockffn_force_generic")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -71,6 +72,10 @@ def lib() -> ctypes.CDLL:
         L.blockffn_offload_sim.restype = ctypes.c_int
         L.blockffn_cls_sweep.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.blockffn_reuse_ratio.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
+        L.blockffn_force_generic.argtypes = [ctypes.c_int]
+        L.blockffn_force_generic.restype = ctypes.c_int
+        L.blockffn_stream_read.argtypes = [vp, sz, i32, vp, vp]
+        L.blockffn_stream_read.restype = ctypes.c_int
         L.blockffn_workspace_bytes.argtypes = [lp, i64, i32]
         L.blockffn_workspace_bytes.restype = sz
         L.blockffn_strerror.argtypes = [ctypes.c_int]
@@ -205,6 +210,17 @@ def blockffn_dense_ffn(layer: Layer, x, scores, n_chunks: int, k: int, y, worksp
     _check(lib().blockffn_dense_ffn(layer.ref(), _p(chunk_layer), _p(x), _p(scores), n_chunks, k, _p(y),
                                     _p(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "blockffn_dense_ffn")
+
+
+def blockffn_force_generic(mode: int):
+    """1: every later FFN call on the shape-generic kernels; 0: automatic choice; -1: as the environment says."""
+    _check(lib().blockffn_force_generic(int(mode)), "blockffn_force_generic")
+
+
+def blockffn_stream_read(buf: torch.Tensor, variant: int, sink: torch.Tensor, stream=None):
+    """Plain read stream over the whole of ``buf`` (measurement helper)."""
+    _check(lib().blockffn_stream_read(_p(buf), buf.numel() * buf.element_size(), variant, _p(sink), _stream(stream)),
+           "blockffn_stream_read")
 
 
 def blockffn_sparse_ffn_up(layer: Layer, x, scores, token_mask, active_idx, n_active, n_chunks: int, k: int,

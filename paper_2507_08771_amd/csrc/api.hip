@@ -43,16 +43,24 @@ int check_layer(const blockffn_layer *l, LayerView &v) {
 int check_chunks(int64_t n_chunks, int32_t k) {
   if (n_chunks < 0 || k < 1) return BLOCKFFN_ERR_INVALID;
   if (k > kMaxK) return BLOCKFFN_ERR_UNSUPPORTED;
-  if (n_chunks > (int64_t)1 << 40) return BLOCKFFN_ERR_UNSUPPORTED;
+  if (n_chunks * k > 0x7fffffffLL) return BLOCKFFN_ERR_UNSUPPORTED;   // tokens per call
   return BLOCKFFN_OK;
 }
 
 // BLOCKFFN_FORCE_GENERIC=1 in the environment keeps every shape on the shape-generic kernels
-// (used to compare the two implementations on the same inputs).
+// (used to compare the two implementations on the same inputs).  Read once, when the first FFN
+// call of the process arrives: later changes of the environment are not seen; a process that
+// wants to switch at run time calls blockffn_force_generic().
+std::atomic<int> g_force_generic{-1};   // -1: as the environment said; 0 / 1: set by blockffn_force_generic()
 bool force_generic() {
-  const char *e = std::getenv("BLOCKFFN_FORCE_GENERIC");
-  return e != nullptr && e[0] == '1';
+  static const bool from_env = [] {
+    const char *e = std::getenv("BLOCKFFN_FORCE_GENERIC");
+    return e != nullptr && e[0] == '1';
+  }();
+  const int set = g_force_generic.load(std::memory_order_relaxed);
+  return set < 0 ? from_env : set != 0;
 }
+
 bool use_stream(const LayerView &v, int wdtype, int32_t k) { return !force_generic() && stream_supported(v, wdtype, k); }
 bool use_gemm(const LayerView &v, int wdtype, int32_t k, bool gated) {
   return !force_generic() && gemm_supported(v, wdtype, k, gated);
@@ -89,6 +97,7 @@ int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_lay
   }
   if (!aligned(active_idx, 4) || !aligned(n_active, 4) || !aligned(chunk_layer, 4)) return BLOCKFFN_ERR_INVALID;
   if (n_chunks == 0) return BLOCKFFN_OK;
+  if (n_chunks * v.E > 0x7fffffffLL) return BLOCKFFN_ERR_UNSUPPORTED;   // (chunk, slot) pairs are indexed in 32 bits
   const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
   const size_t need = workspace_need(v, layer->wdtype, gated, n_chunks, k);
   if (workspace == nullptr || !aligned(workspace, 256)) return BLOCKFFN_ERR_INVALID;
@@ -253,6 +262,19 @@ int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, 
                     workspace, workspace_bytes, stream);
 }
 
+int blockffn_force_generic(int mode) {
+  if (mode < -1 || mode > 1) return BLOCKFFN_ERR_INVALID;
+  g_force_generic.store(mode, std::memory_order_relaxed);
+  return BLOCKFFN_OK;
+}
+
+int blockffn_stream_read(const void *buf, size_t bytes, int32_t variant, uint32_t *sink, void *stream) {
+  if (buf == nullptr || sink == nullptr || !aligned(buf, 16) || !aligned(sink, 4)) return BLOCKFFN_ERR_INVALID;
+  if (variant < 0 || variant > 3) return BLOCKFFN_ERR_INVALID;
+  hipError_t err = launch_stream_read(buf, bytes, variant, sink, static_cast<hipStream_t>(stream));
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
 size_t blockffn_workspace_bytes(const blockffn_layer *layer, int64_t n_chunks, int32_t k) {
   LayerView v;
   if (check_layer(layer, v) != BLOCKFFN_OK) return 0;
@@ -271,6 +293,6 @@ const char *blockffn_strerror(int code) {
   }
 }
 
-int blockffn_version(void) { return 100; }
+int blockffn_version(void) { return 101; }
 
 }  // extern "C"

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/blockffn.h"
 
 namespace blockffn {
@@ -111,6 +113,47 @@ __device__ __forceinline__ int clamp_layer(const int32_t *chunk_layer, int64_t c
   return l < 0 ? 0 : (l >= n_layers ? n_layers - 1 : l);
 }
 
+// ------------------------------------------------------------------------------------------------ host: per device
+// The library keeps nothing per process that depends on the device: what it caches (the number
+// of compute units, "this kernel's LDS limit has been raised") is kept per device ordinal, in
+// atomics, so that threads driving different GPUs - or the same one - need no lock.
+constexpr int kMaxDevices = 64;
+
+// Ordinal of the calling thread's current device, or -1 (unknown, or beyond kMaxDevices: nothing is cached then).
+inline int current_device() {
+  int dev = -1;
+  return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices ? dev : -1;
+}
+
+// Compute units of the current device (256 if the runtime will not say).
+inline int num_cus() {
+  static std::atomic<int> cus[kMaxDevices];
+  const int dev = current_device();
+  if (dev >= 0) {
+    const int known = cus[dev].load(std::memory_order_relaxed);
+    if (known > 0) return known;
+  }
+  int n = 0;
+  if (dev < 0 || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+  cus[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
+// Runs `f` (a set-up step that is idempotent, e.g. hipFuncSetAttribute) until it has succeeded
+// once on the current device.  Two threads may both run it the first time; neither skips it.
+struct PerDeviceOnce {
+  std::atomic<uint64_t> done{0};
+  static_assert(kMaxDevices <= 64, "one bit per device");
+  template <typename F>
+  hipError_t run(F f) {
+    const int dev = current_device();
+    if (dev >= 0 && ((done.load(std::memory_order_acquire) >> dev) & 1)) return hipSuccess;
+    const hipError_t e = f();
+    if (e == hipSuccess && dev >= 0) done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+    return e;
+  }
+};
+
 // Launchers implemented in the .hip files (host side).  Each returns a hipError_t.
 hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
                          int64_t n_chunks, int k, float *scores, uint64_t *token_mask, float *preact,
@@ -171,5 +214,9 @@ hipError_t launch_up_gemm(const LayerView &L, bool gated, const int32_t *chunk_l
 hipError_t launch_down_gemm(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
                             const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
                             hipStream_t s);
+
+// Plain read stream over `bytes` bytes (measurement helper): variant 0..3 selects the tile per
+// workgroup (1 MiB, 256 KiB, 256 KiB, 64 KiB) and the loads in flight per lane (8, 8, 16, 16).
+hipError_t launch_stream_read(const void *buf, size_t bytes, int variant, uint32_t *sink, hipStream_t s);
 
 }  // namespace blockffn

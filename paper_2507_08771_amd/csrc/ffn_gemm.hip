@@ -2,9 +2,14 @@
 // here one expert's weights are reused by hundreds of tokens, the work is a dense grouped
 // contraction over the experts of the union and the matrix cores are the bound, not HBM.
 //
-//   x  -> bf16 once (round to nearest even); products are bf16 x bf16 accumulated in fp32.
+//   x  -> two bf16 planes, hi = bf16(x) and lo = bf16(x - hi) (x = hi + lo to 16 significant
+//         bits, as on the streaming path); products are bf16 x bf16, exact in fp32, accumulated
+//         in fp32.  The up projection walks the contraction twice per stage, once against each
+//         plane, with the same weight lines (the second request finds them in L2), so the fp32
+//         activations the configurations state reach the product to 2^-17 and mid is the only
+//         value rounded to bf16 on the way to y (once, 2^-9 relative per element).
 //   up    one workgroup = (item of the (chunk, slot) list, TN tokens, TM/2 neurons): a
-//         TM x TN x d contraction (TM/2 W_up rows and the matching W_gate rows against TN
+//         TM x TN x 2d contraction (TM/2 W_up rows and the matching W_gate rows against TN
 //         tokens; TM = TN = 256, or 128 for short chunks), both operands staged through
 //         double-buffered LDS (LDS-direct global loads of whole 128-byte lines, 8 lanes per
 //         row; an XOR swizzle of the pieces keeps the fragment reads conflict free).
@@ -98,9 +103,10 @@ __device__ __forceinline__ void token_list_wave(const uint64_t *__restrict__ tok
 }
 
 // The three passes ahead of the up projection in one launch (they are independent, and as three
-// launches of a few microseconds each they ran one after the other): blocks [0, cvt_blocks) round
-// x to bf16, the next zero_blocks clear mid, the rest build the token lists, one wave per
-// (chunk, expert).  Without a mask there are no lists and nothing to clear.
+// launches of a few microseconds each they ran one after the other): blocks [0, cvt_blocks) split
+// x into its bf16 planes (hi at xb, lo at xb + 8 n8), the next zero_blocks clear mid, the rest
+// build the token lists, one wave per (chunk, expert).  Without a mask there are no lists and
+// nothing to clear.
 __global__ __launch_bounds__(kThreads) void prepare_kernel(const float *__restrict__ x, uint16_t *__restrict__ xb,
                                                            size_t n8, int cvt_blocks, uint4 *__restrict__ H, size_t n16,
                                                            int zero_blocks, const uint64_t *__restrict__ token_mask, int W,
@@ -110,12 +116,17 @@ __global__ __launch_bounds__(kThreads) void prepare_kernel(const float *__restri
   if (b < cvt_blocks) {
     for (size_t i = (size_t)b * kThreads + threadIdx.x; i < n8; i += (size_t)cvt_blocks * kThreads) {
       const float4 a = reinterpret_cast<const float4 *>(x)[2 * i], c = reinterpret_cast<const float4 *>(x)[2 * i + 1];
-      uint4 o;
-      o.x = bf16_bits(a.x) | bf16_bits(a.y) << 16;
-      o.y = bf16_bits(a.z) | bf16_bits(a.w) << 16;
-      o.z = bf16_bits(c.x) | bf16_bits(c.y) << 16;
-      o.w = bf16_bits(c.z) | bf16_bits(c.w) << 16;
-      reinterpret_cast<uint4 *>(xb)[i] = o;
+      const float v[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+      uint32_t hi[8], lo[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        hi[q] = bf16_bits(v[q]);
+        lo[q] = bf16_bits(v[q] - __uint_as_float(hi[q] << 16));
+      }
+      reinterpret_cast<uint4 *>(xb)[i] =
+          make_uint4(hi[0] | hi[1] << 16, hi[2] | hi[3] << 16, hi[4] | hi[5] << 16, hi[6] | hi[7] << 16);
+      reinterpret_cast<uint4 *>(xb)[n8 + i] =
+          make_uint4(lo[0] | lo[1] << 16, lo[2] | lo[3] << 16, lo[4] | lo[5] << 16, lo[6] | lo[7] << 16);
     }
   } else if (b < cvt_blocks + zero_blocks) {
     for (size_t i = (size_t)(b - cvt_blocks) * kThreads + threadIdx.x; i < n16; i += (size_t)zero_blocks * kThreads)
@@ -310,7 +321,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint16_t *__restrict__ xb,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr, const int32_t *__restrict__ lists,
-    const int32_t *__restrict__ counts, int k, int tiles_t, int tiles_j, uint16_t *__restrict__ H) {
+    const int32_t *__restrict__ counts, int k, int tiles_t, int tiles_j, size_t x_plane, uint16_t *__restrict__ H) {
   extern __shared__ uint4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4;
@@ -326,8 +337,9 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   const int code = items[item];
   const int64_t c = code / E;
   const int s = code - (int)c * E;
-  int e = active_idx ? active_idx[c * E + s] : s;
-  e = min(max(e, 0), E - 1);
+  const int e = active_idx ? active_idx[c * E + s] : s;
+  // a list entry outside [0, E) (an invalid input) is an empty slot: its rows of H stay zero
+  if ((unsigned)e >= (unsigned)E) return;   // uniform over the workgroup
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int t0 = tt * T::TN;
   // with token lists the tile's columns are the expert's own tokens list[t0 ..]; H was zeroed and
@@ -362,11 +374,13 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
   const uint16_t *wsel = static_cast<const uint16_t *>(gate_wave ? L.w_gate : L.w_up) + w_expert * d;
   const uint16_t *xsel = xb + (size_t)c * k * d;
   // every tile of the launch reads the chunk's x: each starts at another stage of the
-  // contraction, so that they do not all ask the L2 for the same lines at the same moment
+  // contraction, so that they do not all ask the L2 for the same lines at the same moment.
+  // Stage (or pair of K-steps) 2 v is stage v of the contraction against the hi plane of x,
+  // 2 v + 1 the same weight lines against the lo plane.
   const int n_st = d / T::TK, rot = (int)(((unsigned)item * 5u) % (unsigned)n_st);
-  auto stage_of = [&](int st) { const int v = st + rot; return v >= n_st ? v - n_st : v; };
+  auto stage_of = [&](int st) { const int v = (st >> 1) + rot; return v >= n_st ? v - n_st : v; };
   auto base_a = [&](int st) { return wsel + (size_t)stage_of(st) * T::TK; };
-  auto base_b = [&](int st) { return xsel + (size_t)stage_of(st) * T::TK; };
+  auto base_b = [&](int st) { return xsel + (st & 1 ? x_plane : (size_t)0) + (size_t)stage_of(st) * T::TK; };
 
   f32x4 acc[T::FI][T::FJ];
 #pragma unroll
@@ -393,7 +407,7 @@ __global__ __launch_bounds__(T::THREADS) void up_gemm_kernel(
       f_tok[j] = on ? scores[tok * E + e] : 0.0f;
     }
   }
-  run_mainloop<T>(lds, d / T::TK, base_a, base_b, off, acc, a_lo, a_hi, wc);
+  run_mainloop<T>(lds, 2 * (d / T::TK), base_a, base_b, off, acc, a_lo, a_hi, wc);
 
   // D[i = neuron 4g + q of the fragment][j = token n of the fragment]
 #pragma unroll
@@ -532,8 +546,8 @@ struct GemmWs {
 GemmWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
   char *p = static_cast<char *>(ws);
   GemmWs w;
-  w.xb = reinterpret_cast<uint16_t *>(p);
-  p += align256((size_t)n_chunks * k * L.d * 2);
+  w.xb = reinterpret_cast<uint16_t *>(p);   // two planes: bf16 hi, bf16 lo
+  p += align256((size_t)n_chunks * k * L.d * 2 * 2);
   w.H = reinterpret_cast<uint16_t *>(p);
   p += align256((size_t)n_chunks * L.E * k * L.d_e * 2);
   w.total = reinterpret_cast<int32_t *>(p);
@@ -555,21 +569,24 @@ hipError_t launch_up_tile(const LayerView &L, bool gated, const int32_t *chunk_l
   const int64_t grid = (n_chunks * L.E + 7) / 8 * 8 * tiles_t * tiles_j;   // items rounded up to the 8 XCDs
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
   const int32_t *lists = token_mask ? w.lists : nullptr;   // no mask: every token has every expert
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 1>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 2>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    if (e1 != hipSuccess || e2 != hipSuccess) return e1 != hipSuccess ? e1 : e2;
-    attr_set = true;
-  }
+  static PerDeviceOnce lds_limit;   // one per tile type
+  const hipError_t e = lds_limit.run([&] {
+    const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 1>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(up_gemm_kernel<T, 2>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    return e1 != hipSuccess ? e1 : e2;
+  });
+  if (e != hipSuccess) return e;
+  const size_t x_plane = (size_t)n_chunks * k * L.d;   // elements between the hi and the lo plane of x
   if (gated)
     hipLaunchKernelGGL((up_gemm_kernel<T, 2>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
-                       w.xb, scores, token_mask, active_idx, w.items, w.total, lists, w.counts, k, tiles_t, tiles_j, w.H);
+                       w.xb, scores, token_mask, active_idx, w.items, w.total, lists, w.counts, k, tiles_t, tiles_j,
+                       x_plane, w.H);
   else
     hipLaunchKernelGGL((up_gemm_kernel<T, 1>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
-                       w.xb, scores, token_mask, active_idx, w.items, w.total, lists, w.counts, k, tiles_t, tiles_j, w.H);
+                       w.xb, scores, token_mask, active_idx, w.items, w.total, lists, w.counts, k, tiles_t, tiles_j,
+                       x_plane, w.H);
   return hipGetLastError();
 }
 
@@ -581,13 +598,12 @@ hipError_t launch_down_tile(const LayerView &L, const int32_t *chunk_layer, cons
   const int64_t n_groups = n_chunks * splits;
   const int64_t grid = (n_groups + 7) / 8 * 8 * tiles_t * tiles_c;
   if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(down_gemm_kernel<T>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static PerDeviceOnce lds_limit;   // one per tile type
+  const hipError_t e = lds_limit.run([&] {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(down_gemm_kernel<T>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+  });
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((down_gemm_kernel<T>), dim3((unsigned)grid), dim3(T::THREADS), T::LDS_BYTES, s, L, chunk_layer,
                      active_idx, n_active, k, tiles_t, tiles_c, splits, n_groups, H, out, stride);
   return hipGetLastError();
@@ -601,7 +617,7 @@ bool gemm_supported(const LayerView &L, int wdtype, int k, bool gated) {
 
 size_t gemm_workspace_bytes(const LayerView &L, int64_t n_chunks, int k) {
   const int splits = down_splits(L, n_chunks, k);
-  size_t b = align256((size_t)n_chunks * k * L.d * 2) + align256((size_t)n_chunks * L.E * k * L.d_e * 2) +
+  size_t b = align256((size_t)n_chunks * k * L.d * 2 * 2) + align256((size_t)n_chunks * L.E * k * L.d_e * 2) +
              align256(((size_t)n_chunks * L.E + 64) * sizeof(int32_t)) +
              align256((size_t)n_chunks * L.E * k * sizeof(int32_t)) + align256((size_t)n_chunks * L.E * sizeof(int32_t));
   if (splits > 1) b += align256((size_t)splits * n_chunks * k * L.d * sizeof(float));

@@ -70,48 +70,103 @@ constexpr int up_group(int NB, int RT, int NM) {
 // Flat work list: items[i] = chunk * E + slot for every `group`-th slot below n_active[chunk]
 // (an item stands for up to `group` consecutive slots of one chunk).  The persistent workgroups
 // take items at a fixed stride, so the list is ordered by size: first every item of `group`
-// slots, chunk after chunk, then the chunks' last, shorter items, longest first.  Every
-// workgroup then gets the same number of full items (to within one) and the short ones fill the
-// end of the launch; in chunk order a workgroup could draw several short items and another none
-// (7 % between the busiest workgroup and the mean at 39 active experts per chunk, group = 4).
-__global__ __launch_bounds__(1024) void worklist_kernel(const int32_t *__restrict__ n_active, int64_t n_chunks, int E,
-                                                        int group, int32_t *__restrict__ items,
-                                                        int32_t *__restrict__ total) {
-  __shared__ int wave_tot[16];
-  __shared__ int carry;
+// slots, chunk after chunk (pass 0), then the chunks' last, shorter items, longest first (pass p
+// holds the chunks whose last item has group - p slots).  Every workgroup then gets the same
+// number of full items (to within one) and the short ones fill the end of the launch; in chunk
+// order a workgroup could draw several short items and another none (7 % between the busiest
+// workgroup and the mean at 39 active experts per chunk, group = 4).
+//
+// One workgroup per 1024 chunks.  A chunk's place in the list depends on the counts of all chunks
+// (earlier passes) and of the chunks before it (its own pass); instead of a scan across
+// workgroups, which needs a second launch or workgroups waiting for each other, every workgroup
+// counts for itself: the totals of each pass and what lies before its own first chunk.  That is
+// one coalesced sweep over n_active per workgroup (64 workgroups x 256 KiB at 65 536 chunks),
+// far less than a launch costs, and no workgroup ever waits for another.
+constexpr int kListChunks = 1024;   // chunks per workgroup = threads per workgroup
+constexpr int kMaxGroup = 4;
+
+__device__ __forceinline__ int items_of(int n_act, int group, int pass, int &first) {
+  const int full = n_act / group, rem = n_act - full * group;
+  first = pass == 0 ? 0 : full;
+  return pass == 0 ? full : (rem == group - pass ? 1 : 0);
+}
+
+__global__ __launch_bounds__(kListChunks) void worklist_kernel(const int32_t *__restrict__ n_active, int64_t n_chunks,
+                                                               int E, int group, int32_t *__restrict__ items,
+                                                               int32_t *__restrict__ total) {
+  __shared__ int red[2 * kMaxGroup][kListChunks / 64];
+  __shared__ int pass_base[kMaxGroup + 1];   // first list index of each pass for this workgroup's first chunk; [group]: list length
+  __shared__ int wave_tot[kListChunks / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) carry = 0;
-  __syncthreads();
-  // pass 0: the full items; pass p > 0: the chunks whose last item has group - p slots
-  for (int pass = 0; pass < group; ++pass) {
-    for (int64_t c0 = 0; c0 < n_chunks; c0 += 1024) {
-      const int64_t c = c0 + tid;
-      int n = 0, first = 0;
-      if (c < n_chunks) {
-        const int n_act = n_active ? min(max(n_active[c], 0), E) : E;
-        const int full = n_act / group, rem = n_act - full * group;
-        n = pass == 0 ? full : (rem == group - pass ? 1 : 0);
-        first = pass == 0 ? 0 : full;
-      }
-      int incl = n;
+  const int64_t c_first = (int64_t)blockIdx.x * kListChunks;
+  auto n_act_of = [&](int64_t c) { return n_active ? min(max(n_active[c], 0), E) : E; };
+
+  // all[p]: items of pass p over every chunk; before[p]: over the chunks ahead of this workgroup's
+  int all[kMaxGroup], before[kMaxGroup];
 #pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int v = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += v;
-      }
-      if (lane == 63) wave_tot[wave] = incl;
-      __syncthreads();
-      int base = carry;
-      for (int w = 0; w < wave; ++w) base += wave_tot[w];
-      const int start = base + incl - n;
-      for (int s = 0; s < n; ++s) items[start + s] = (int32_t)(c * E + (first + s) * group);
-      __syncthreads();
-      if (tid == 1023) carry = base + incl;
-      __syncthreads();
+  for (int p = 0; p < kMaxGroup; ++p) all[p] = before[p] = 0;
+  for (int64_t c = tid; c < n_chunks; c += kListChunks) {
+    const int n_act = n_act_of(c);
+#pragma unroll
+    for (int p = 0; p < kMaxGroup; ++p) {
+      int first;
+      const int n = p < group ? items_of(n_act, group, p, first) : 0;
+      all[p] += n;
+      before[p] += c < c_first ? n : 0;
     }
   }
-  if (tid == 0) *total = carry;
-  if (tid < 4) total[16 + tid] = 0;   // the block of zeros the down kernel stages absent tokens from
+#pragma unroll
+  for (int p = 0; p < kMaxGroup; ++p) {
+    int a = all[p], b = before[p];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      a += __shfl_xor(a, off, kWave);
+      b += __shfl_xor(b, off, kWave);
+    }
+    if (lane == 0) {
+      red[p][wave] = a;
+      red[kMaxGroup + p][wave] = b;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int start = 0;
+    for (int p = 0; p < group; ++p) {
+      int a = 0, b = 0;
+      for (int w = 0; w < kListChunks / 64; ++w) {
+        a += red[p][w];
+        b += red[kMaxGroup + p][w];
+      }
+      pass_base[p] = start + b;
+      start += a;
+    }
+    pass_base[group] = start;
+  }
+  __syncthreads();
+
+  const int64_t c = c_first + tid;
+  const int n_act = c < n_chunks ? n_act_of(c) : 0;
+  for (int pass = 0; pass < group; ++pass) {
+    int first = 0;
+    const int n = c < n_chunks ? items_of(n_act, group, pass, first) : 0;
+    int incl = n;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off, kWave);
+      if (lane >= off) incl += v;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int base = pass_base[pass];
+    for (int w = 0; w < wave; ++w) base += wave_tot[w];
+    const int start = base + incl - n;
+    for (int s = 0; s < n; ++s) items[start + s] = (int32_t)(c * E + (first + s) * group);
+    __syncthreads();   // wave_tot is rewritten by the next pass
+  }
+  if (blockIdx.x == 0) {
+    if (tid == 0) *total = pass_base[group];
+    if (tid < 4) total[16 + tid] = 0;   // the block of zeros the down kernel stages absent tokens from
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ x split
@@ -179,13 +234,13 @@ __device__ __forceinline__ void up_scores(ScoreRaw<NB> &raw, const LayerView &L,
 }
 
 template <int NB>
-__device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], const ScoreRaw<NB> &raw, int e, int k,
-                                                 int lane) {
+__device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], const ScoreRaw<NB> &raw, int e, bool valid,
+                                                 int k, int lane) {
   const int n = lane & 15;
 #pragma unroll
   for (int q = 0; q < acc_tiles(NB); ++q) {
     const int t = NB == 1 ? (n & 7) : q * 16 + n;
-    const bool on = t < k && ((raw.mask[q] >> (e & 63)) & 1);
+    const bool on = valid && t < k && ((raw.mask[q] >> (e & 63)) & 1);
     f_tok[q] = on ? raw.score[q] : 0.0f;
   }
 }
@@ -274,9 +329,13 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   const int total = *total_ptr;
   const size_t row_bytes = (size_t)d * 2;
 
+  // A list entry outside [0, E) (an invalid input) is an empty slot: the kernel streams a valid
+  // expert in its place (the index is clamped) and writes zeros to mid, as if no token had it.
+  // Returned: the clamped index, with bit 30 set when the entry was out of range.
+  constexpr int kBad = 1 << 30;
   auto slot_expert = [&](int64_t c, int s) {
     const int e = active_idx ? active_idx[c * E + s] : s;
-    return min(max(e, 0), E - 1);
+    return min(max(e, 0), E - 1) | ((unsigned)e >= (unsigned)E ? kBad : 0);
   };
   // an item is up to `group` consecutive slots of one chunk: the chunk's split x is written to
   // LDS once per item and serves all of them
@@ -303,6 +362,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   int s, ns;        // current slot and slots left in the item (this one included)
   item_decode(item, c, s, ns);
   int e = slot_expert(c, s);
+  bool e_ok = !(e & kBad);
+  e &= ~kBad;
   int layer = clamp_layer(chunk_layer, c, L.n_layers);
   int64_t c_loaded = -1;   // chunk and K-chunk whose split x is in LDS
   int kc_loaded = -1;
@@ -333,6 +394,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       }
     }
     if (has_next) e_n = slot_expert(c_n, s_n);
+    const bool e_ok_n = !(e_n & kBad);
+    e_n &= ~kBad;
 
     f32x4 acc[RT][NM][NA];
 #pragma unroll
@@ -418,12 +481,12 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     }
 
     float f_tok[NA];
-    up_scores_finish<NB>(f_tok, raw, e, k, lane);
+    up_scores_finish<NB>(f_tok, raw, e, e_ok, k, lane);
     up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits);
 
     if (!has_next) break;
     item = next_item;
-    c = c_n; s = s_n; ns = ns_n; e = e_n; layer = layer_n;
+    c = c_n; s = s_n; ns = ns_n; e = e_n; e_ok = e_ok_n; layer = layer_n;
   }
 }
 
@@ -489,6 +552,17 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     for (int sl = 0; sl < G; ++sl) v |= (uint32_t)slot_expert(c, s0 + min(sl, ns - 1)) << (8 * sl);
     return v;   // slots past ns repeat the last one and are never used
   };
+  // bit sl set: the list entry of slot sl is outside [0, E) (an invalid input): an empty slot, for
+  // which a valid expert is streamed (the clamped index) and no row of mid is written
+  auto slots_bad = [&](int64_t c, int s0, int ns) {
+    uint32_t v = 0;
+    if (active_idx) {
+#pragma unroll
+      for (int sl = 0; sl < G; ++sl)
+        v |= ((unsigned)active_idx[c * E + s0 + min(sl, ns - 1)] >= (unsigned)E ? 1u : 0u) << sl;
+    }
+    return v;
+  };
   // LDS-direct fill of one buffer: 32 KiB, 8 loads per wave
   auto fill = [&](int64_t c, int kc, int buf) {
     const uint4 *src = xS + ((size_t)c * (d / 32) + (size_t)kc * FPT) * NB * 64 + wave * (kBuf / 4) + lane;
@@ -516,13 +590,13 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
       }
     }
   };
-  auto read_scores = [&](float (&f_tok)[NA], int ipar, int sl, int e) {
+  auto read_scores = [&](float (&f_tok)[NA], int ipar, int sl, int e, bool valid) {
     const int n = lane & 15;
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
       const int t = q * 16 + n;   // NB = 2: one accumulator tile, tokens 0-15
       const uint32_t word = token_mask ? scoreS[ipar][sl][1 + ((e >> 5) & 1)][t] : ~0u;
-      const bool on = t < k && ((word >> (e & 31)) & 1);
+      const bool on = valid && t < k && ((word >> (e & 31)) & 1);
       f_tok[q] = on ? __uint_as_float(scoreS[ipar][sl][0][t]) : 0.0f;
     }
   };
@@ -539,19 +613,20 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   int s0, ns;
   item_decode(item, c, s0, ns);
   int layer = clamp_layer(chunk_layer, c, L.n_layers);
-  uint32_t es = slots_experts(c, s0, ns);
+  uint32_t es = slots_experts(c, s0, ns), bad = slots_bad(c, s0, ns);
 
   // next item (valid while has_next) and the prefetch cursor
   bool has_next = false;
   int64_t c_n = c;
   int s0_n = 0, ns_n = 1, layer_n = layer;
-  uint32_t esn = es;
+  uint32_t esn = es, bad_n = bad;
   auto decode_next = [&](int next_item) {
     has_next = next_item < total;
     if (has_next) {
       item_decode(next_item, c_n, s0_n, ns_n);
       layer_n = clamp_layer(chunk_layer, c_n, L.n_layers);
       esn = slots_experts(c_n, s0_n, ns_n);
+      bad_n = slots_bad(c_n, s0_n, ns_n);
     }
   };
   decode_next(item + item_step);
@@ -647,7 +722,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 
     float f_tok[G][NA];
 #pragma unroll
-    for (int sl = 0; sl < G; ++sl) read_scores(f_tok[sl], ipar, sl, pick(es, sl));
+    for (int sl = 0; sl < G; ++sl) read_scores(f_tok[sl], ipar, sl, pick(es, sl), !((bad >> sl) & 1));
 #pragma unroll
     for (int sl = 0; sl < G; ++sl)
       if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB, tok_bits);
@@ -657,6 +732,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     item += item_step;
     c = c_n; s0 = s0_n; ns = ns_n; layer = layer_n;
     es = esn;
+    bad = bad_n;
     cu_next = false;   // the cursor was in this item already (an item is longer than the ring)
     decode_next(item + item_step);
   }
@@ -689,6 +765,8 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
     e = active_idx[c * E + s];
     if (s >= n_active[c]) return;
   }
+  // a list entry outside [0, E) is an empty slot: zeros in mid (a valid expert is streamed in its place)
+  const bool e_ok = (unsigned)e < (unsigned)E;
   e = min(max(e, 0), E - 1);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int kq0 = wave * (d / 4);
@@ -743,7 +821,7 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   bool on = false;
   if (tok < k) {
     const int64_t t = c * k + tok;
-    on = token_mask ? (bool)((token_mask[t * L.W + (e >> 6)] >> (e & 63)) & 1) : true;
+    on = e_ok && (token_mask ? (bool)((token_mask[t * L.W + (e >> 6)] >> (e & 63)) & 1) : true);
     f = scores[t * E + e];
   }
   uint32_t packed[4];
@@ -927,33 +1005,17 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   }
 }
 
-int g_num_cus = 0;
-
-int num_cus() {
-  if (g_num_cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      g_num_cus = n;
-    else
-      g_num_cus = 256;
-  }
-  return g_num_cus;
-}
-
 template <int NB, int NM, int RT>
 hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                      const int32_t *items, const int32_t *total, int group, int64_t max_items, int k, uint16_t *midB,
                      uint32_t *tok_bits, hipStream_t s) {
-  static bool attr_set = false;
+  static PerDeviceOnce lds_limit;   // one per instantiation
   auto kern = up_stream_kernel<NB, NM, RT>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kXBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  const hipError_t e = lds_limit.run([&] {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kXBytes);
+  });
+  if (e != hipSuccess) return e;
   const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
                      active_idx, n_active, items, total, group, k, midB, tok_bits);
@@ -965,14 +1027,12 @@ hipError_t launch_up_db(const LayerView &L, const int32_t *chunk_layer, const ui
                         const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                         const int32_t *items, const int32_t *total, int64_t max_items, int k, uint16_t *midB,
                         uint32_t *tok_bits, hipStream_t s) {
-  static bool attr_set = false;
+  static PerDeviceOnce lds_limit;   // one per instantiation
   auto kern = up_stream_db_kernel<NB, NM, RT, G>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kXBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  const hipError_t e = lds_limit.run([&] {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kXBytes);
+  });
+  if (e != hipSuccess) return e;
   const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
                      active_idx, n_active, items, total, k, midB, tok_bits);
@@ -1072,7 +1132,11 @@ StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
 
 hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int group, int32_t *items,
                            int32_t *total, hipStream_t s) {
-  hipLaunchKernelGGL(worklist_kernel, dim3(1), dim3(1024), 0, s, n_active, n_chunks, E, group, items, total);
+  if (group < 1 || group > kMaxGroup) return hipErrorInvalidValue;
+  const int64_t blocks = (n_chunks + kListChunks - 1) / kListChunks;
+  if (blocks < 1 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(worklist_kernel, dim3((unsigned)blocks), dim3(kListChunks), 0, s, n_active, n_chunks, E, group,
+                     items, total);
   return hipGetLastError();
 }
 

@@ -21,13 +21,16 @@ RTOL = {"f32": 1e-5, "bf16": 2e-2}
 # fp32 accumulation with activations carried as two bf16 halves (16 significant bits) on the
 # matrix-core path: error is a few 1e-6 of the row rms; 1e-4 leaves a wide margin.
 TIGHT = {"f32": 1e-5, "bf16": 1e-4}
-# Large chunks (k > 32) run as a bf16 x bf16 grouped contraction: x and mid are rounded to bf16
-# (relative error uniform in +-2^-9 per element).  Three such roundings (x into the up and the
-# gate product, mid into the down product) leave about 3e-3 of the row rms per output element
-# (measured: L2-relative 2.9e-3 .. 4.1e-3), and the largest of a row's 2048 elements sits at
-# 4 to 6 sigma.  Held: the stated bar on the row maximum, and 5e-3 on the row's L2-relative error.
+# Large chunks (k > 32) run as a bf16 x bf16 grouped contraction on the matrix cores.  x enters as
+# two bf16 halves (16 significant bits, as on the streaming path); mid is rounded to bf16 once
+# (relative error at most 2^-9 per element, about 1.1e-3 rms).  That one rounding leaves 1.6e-3 of
+# the row's norm at the median and up to 2.7e-3 on rows made of a single 64-neuron expert (measured,
+# and reproduced by rounding the oracle's own mid to bf16 on the CPU); the largest of a row's elements
+# sits at 4 to 5 sigma of that.  Held: the stated 2e-2 on the row maximum, 1.5e-2 on the pinned
+# few-term rows, 3.5e-3 on every row's L2-relative error.
 GEMM_BAR = 2e-2
-GEMM_L2_BAR = 5e-3
+GEMM_FEW_TERMS_BAR = 1.5e-2
+GEMM_L2_BAR = 3.5e-3
 
 
 def oracle_layer(layers, l, eps=1e-6, use_gain=True, use_bias=True):
@@ -106,26 +109,89 @@ def row_rel_err(v, ref):
     return np.where(zero, 0.0, err / np.where(zero, 1.0, rms))
 
 
-def score_error_allowed(layers, x, k, chunk_layer, ref_scores, eps=1e-6):
-    """Per-token bound on |score - reference|: 1e-5 of the row's rms, plus what an fp32 summation
-    error of 1e-6 * (sum_j |x_j| |W_ji| + 1) on the pre-activations becomes behind the normalisation.
-    A token whose only active expert is barely active has sqrt(mean square + eps) close to sqrt(eps),
-    which magnifies that error; the plain 1e-5 bar does not hold for such rows whatever the order
-    of the fp32 additions."""
-    xn = wl.to_numpy(x).astype(np.float64)
+def preact_roundings(d):
+    """Number of fp32 roundings on the longest chain of additions behind one pre-activation A^0 in
+    the router kernels (products are exact: fused multiply-adds on the vector ALUs, bf16 x bf16
+    on the matrix cores).
+      matrix cores: a wave accumulates every fourth K-step of 32 elements, ceil(ceil(d / 32) / 4)
+        accumulator updates, each taking in a 32-term dot product (a tree of depth 5); then the
+        h / m / l columns (2), the four waves pairwise (2), the bias (1);
+      vector ALUs: chains of 8 fused multiply-adds per 2048 columns, a 6-level reduction across
+        the wave, one addition per 2048-column block, the four waves (2), the bias (1).
+    Each rounding moves the sum by at most 2^-24 of its magnitude, which is bounded by
+    mag = |b| + sum_j |x_j| |W_ij|; so |A^0 - exact| <= preact_roundings(d) * 2^-24 * mag to first
+    order, whatever the order of the additions inside those chains."""
+    ksteps = -(-d // 32)
+    mfma = -(-ksteps // 4) + 5 + 2 + 2 + 1
+    blocks = -(-d // 2048)
+    valu = 8 * blocks + 6 + blocks + 2 + 1
+    return max(mfma, valu)
+
+
+def preact_error_allowed(layers, l, xs, use_bias=True):
+    """Per (token, expert) bound on |A^0_fp32 - A^0_exact| for layer l: see preact_roundings()."""
+    mag = np.abs(xs).astype(np.float64) @ np.abs(layers["w_router"][int(l)].double().numpy()).T
+    if use_bias and layers.get("b_router") is not None:
+        mag = mag + np.abs(layers["b_router"][int(l)].double().numpy())[None, :]
+    return preact_roundings(xs.shape[1]) * 2.0 ** -24 * mag
+
+
+def score_error_from_preact(a0, delta, ref_scores, eps, gmax):
+    """Per-token bound on max_i |score_i - reference| given the bound `delta` on the pre-activations.
+    score_i = g_i a1_i / s with s = sqrt(mean_j a1_j^2 + eps).  To first order
+      |d score_i| <= g_i (|d a1_i| / s + a1_i |d s| / s^2),   |d s| = |sum_j a1_j d a1_j| / (E s) <= dmax
+    (Cauchy-Schwarz: sum_j a1_j <= sqrt(E) sqrt(sum_j a1_j^2) <= E s), hence
+      |d score_i| <= gmax dmax / s * (1 + max_i a1_i / s).
+    A token whose only active expert is barely active has s close to sqrt(eps), which is what makes
+    the plain "1e-5 of the row's rms" bar unreachable for it in any fp32 order of additions.  That
+    plain bar (for the arithmetic after A^0: the sum of squares, the root, the division) is added."""
+    a1 = np.maximum(a0, 0.0)
+    s = np.sqrt((a1 * a1).mean(axis=1) + eps)
+    dmax = delta.max(axis=1)
+    rms = np.sqrt((ref_scores.astype(np.float64) ** 2).mean(axis=1))
+    return 1e-5 * np.maximum(rms, 1e-30) + gmax * dmax / s * (1.0 + a1.max(axis=1) / s)
+
+
+def score_error_allowed(layers, x, k, chunk_layer, ref_scores, eps=1e-6, use_gain=True, use_bias=True):
+    """Per-token bound on |score - reference| for a whole batch (chunks may use different layers)."""
+    xn = wl.to_numpy(x)
     T = xn.shape[0]
     cl = np.zeros(T // k, np.int64) if chunk_layer is None else wl.to_numpy(chunk_layer).astype(np.int64)
     allowed = np.zeros(T)
     for l in np.unique(cl):
         tok = np.nonzero(np.repeat(cl == l, k))[0]
-        _, _, a0 = oracle.router(oracle_layer(layers, int(l), eps=eps), xn[tok].astype(np.float32), return_a0=True)
-        mag = np.abs(xn[tok]) @ np.abs(layers["w_router"][int(l)].double().numpy()).T + 1.0
-        a1 = np.maximum(a0, 0.0)
-        scale = np.sqrt((a1 * a1).mean(axis=1) + eps)
-        gmax = 1.0 if layers.get("g_rms") is None else float(layers["g_rms"][int(l)].max())
-        rms = np.sqrt((ref_scores[tok].astype(np.float64) ** 2).mean(axis=1))
-        allowed[tok] = 1e-5 * np.maximum(rms, 1e-30) + 2.0 * gmax * 1e-6 * mag.max(axis=1) / scale
+        _, _, a0 = oracle.router(oracle_layer(layers, int(l), eps=eps, use_gain=use_gain, use_bias=use_bias),
+                                 xn[tok], return_a0=True)
+        delta = preact_error_allowed(layers, l, xn[tok], use_bias)
+        gmax = float(layers["g_rms"][int(l)].max()) if use_gain and layers.get("g_rms") is not None else 1.0
+        allowed[tok] = score_error_from_preact(a0, delta, ref_scores[tok], eps, gmax)
     return allowed
+
+
+def assert_scores_within_allowance(gpu_scores, ref_scores, allowed, what=""):
+    """Scores against the derived bound; prints how much of the allowance the worst row uses."""
+    err = np.abs(gpu_scores.astype(np.float64) - ref_scores).max(axis=1)
+    used = float((err / allowed).max(initial=0.0))
+    print("score error: worst row uses %.3f of its allowance %s" % (used, what), flush=True)
+    assert used <= 1.0, "router score beyond the derived fp32 bound (%.3f of it) %s" % (used, what)
+    return used
+
+
+def oracle_ffn_on_gpu_routing(layers, x, k, chunk_layer, gpu, eps=1e-6, use_gain=True, use_bias=True):
+    """The oracle's chunk-sparse FFN driven by the scores, masks and lists the HIP path produced:
+    judges the FFN kernels on every row, independently of the router's rounding."""
+    xn = wl.to_numpy(x)
+    T, d = xn.shape
+    C = T // k
+    cl = np.zeros(C, np.int64) if chunk_layer is None else wl.to_numpy(chunk_layer).astype(np.int64)
+    y = np.zeros((T, d), np.float64)
+    for l in np.unique(cl):
+        L = oracle_layer(layers, int(l), eps, use_gain, use_bias)
+        cs = np.nonzero(cl == l)[0]
+        tok = (cs[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+        y[tok] = oracle.sparse_ffn(L, xn[tok], gpu["scores"][tok], gpu["token_mask"][tok], gpu["active_idx"][cs],
+                                   gpu["n_active"][cs], k)
+    return y
 
 
 def assert_integers_equal(gpu, ref, chunks=None, k=None):

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert set(B.EXPORTS) <= set(names)
     for n in names:
         assert hasattr(lib, n), n
-    assert lib.blockffn_version() == 100
+    assert lib.blockffn_version() == 101
 
 
 def test_binding_has_the_same_names():
@@ -103,6 +103,31 @@ def test_union_and_ffn_argument_checks():
     assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 4, 8, FAKE, FAKE, need - 1, None) == B.ERR_WORKSPACE
     assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, None, 4, 8, FAKE, FAKE, need, None) == B.ERR_INVALID
     assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 0, 8, FAKE, None, 0, None) == B.OK
+
+
+def test_sizes_beyond_32_bit_indexing_are_unsupported():
+    """(chunk, slot) pairs and tokens are indexed in 32 bits inside the kernels: larger calls are
+    refused as unsupported before anything is launched (not reported as a launch failure)."""
+    lib = B.lib()
+    lay = layer()
+    big = 1 << 40
+    sparse = lambda n_chunks, k: lib.blockffn_sparse_ffn(ctypes.byref(lay), None, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                                         n_chunks, k, FAKE, FAKE, big, None)
+    assert sparse(1 << 26, 8) == B.ERR_UNSUPPORTED       # 2^26 chunks x 64 experts = 2^32 pairs
+    assert sparse(1 << 28, 8) == B.ERR_UNSUPPORTED       # 2^31 tokens
+    assert router_rc(lay, n_chunks=1 << 28, k=8) == B.ERR_UNSUPPORTED
+    assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 1 << 26, 8, FAKE, FAKE, big, None) == B.ERR_UNSUPPORTED
+    assert lib.blockffn_workspace_bytes(ctypes.byref(lay), 1 << 28, 8) == 0
+
+
+def test_force_generic_modes():
+    lib = B.lib()
+    for mode in (1, 0, -1):
+        assert lib.blockffn_force_generic(mode) == B.OK
+    assert lib.blockffn_force_generic(2) == B.ERR_INVALID and lib.blockffn_force_generic(-2) == B.ERR_INVALID
+    assert lib.blockffn_stream_read(None, 1024, 0, FAKE, None) == B.ERR_INVALID
+    assert lib.blockffn_stream_read(FAKE, 1024, 4, FAKE, None) == B.ERR_INVALID
+    assert lib.blockffn_stream_read(FAKE, 1024, 0, None, None) == B.ERR_INVALID
 
 
 def test_statistics_argument_checks():

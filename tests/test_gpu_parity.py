@@ -35,13 +35,11 @@ def test_tiny_f32_k4_full_config():
 
 
 @pytest.fixture(params=["auto", "generic"])
-def impl(request, monkeypatch):
+def impl(request):
     """auto: the library picks its kernels by shape; generic: every shape on the shape-generic kernels."""
-    if request.param == "generic":
-        monkeypatch.setenv("BLOCKFFN_FORCE_GENERIC", "1")
-    else:
-        monkeypatch.delenv("BLOCKFFN_FORCE_GENERIC", raising=False)
-    return request.param
+    B.blockffn_force_generic(1 if request.param == "generic" else 0)
+    yield request.param
+    B.blockffn_force_generic(0)
 
 
 @pytest.mark.parametrize("gated", [True, False])
@@ -110,16 +108,10 @@ def test_k32_many_chunks(gated):
     e_y = pu.row_rel_err(gpu["y"], ref["y"]).max(initial=0.0)
     assert e_y <= pu.TIGHT["bf16"], "sparse FFN output off by %.3g" % e_y
     # With 2240 tokens some have a single, barely active expert: sqrt(mean square + eps) is then
-    # close to sqrt(eps) and magnifies the fp32 summation error of the pre-activation.  Same bound
-    # as in test_router_with_many_token_tiles: 1e-5 of the row's rms plus that error behind the
-    # normalisation.
-    _, _, a0 = oracle.router(pu.oracle_layer(layers, 0), x.numpy(), return_a0=True)
-    mag = np.abs(x.numpy()).astype(np.float64) @ np.abs(layers["w_router"][0].double().numpy()).T + 1.0
-    a1 = np.maximum(a0, 0.0)
-    scale = np.sqrt((a1 * a1).mean(axis=1) + 1e-6)
-    rms = np.sqrt((ref["scores"].astype(np.float64) ** 2).mean(axis=1))
-    allowed = 1e-5 * np.maximum(rms, 1e-30) + 2.0 * 1e-6 * mag.max(axis=1) / scale
-    assert np.all(np.abs(gpu["scores"] - ref["scores"]).max(axis=1) <= allowed)
+    # close to sqrt(eps) and magnifies the fp32 summation error of the pre-activation; the scores
+    # are held to the bound derived from those additions (parity_util.score_error_allowed).
+    pu.assert_scores_within_allowance(gpu["scores"], ref["scores"],
+                                      pu.score_error_allowed(layers, x, w.k, None, ref["scores"]))
     np.testing.assert_array_equal(gpu["scores"] == 0, ref["scores"] == 0)
 
 
@@ -290,15 +282,158 @@ def test_router_with_many_token_tiles(E, k):
         tok = np.nonzero(np.repeat(cls == l, k))[0]
         r_scores, r_mask, a0 = oracle.router(OL, xs[tok], return_a0=True)
         np.testing.assert_array_equal(g_mask[tok], r_mask)
-        mag = np.abs(xs[tok]).astype(np.float64) @ np.abs(layers["w_router"][l].double().numpy()).T + 1.0
-        delta = 1e-6 * mag                      # fp32 summation error allowed on a pre-activation
-        assert np.all(np.abs(g_pre[tok] - a0) <= delta)
+        # pre-activations: the bound derived from the fp32 additions behind each of them
+        delta = pu.preact_error_allowed(layers, l, xs[tok])
+        used = float((np.abs(g_pre[tok] - a0) / delta).max())
+        print("layer %d: worst pre-activation uses %.3f of its allowance" % (l, used), flush=True)
+        assert used <= 1.0
         # scores: 1e-5 of the row's rms, plus what the allowed error of the pre-activations becomes
         # behind the normalisation (a token whose only active expert is barely active has
         # sqrt(mean square + eps) close to sqrt(eps), which magnifies it)
-        a1 = np.maximum(a0, 0.0)
-        scale = np.sqrt((a1 * a1).mean(axis=1) + 1e-6)
-        gmax = float(layers["g_rms"][l].max())
-        rms = np.sqrt((r_scores.astype(np.float64) ** 2).mean(axis=1))
-        allowed = 1e-5 * np.maximum(rms, 1e-30) + 2.0 * gmax * delta.max(axis=1) / scale
-        assert np.all(np.abs(g_scores[tok] - r_scores).max(axis=1) <= allowed)
+        allowed = pu.score_error_from_preact(a0, delta, r_scores, 1e-6, float(layers["g_rms"][l].max()))
+        pu.assert_scores_within_allowance(g_scores[tok], r_scores, allowed, "(layer %d)" % l)
+
+
+@pytest.mark.parametrize("E,k,C,fine", [
+    (70, 8, 200, False),     # two mask words, one token tile per workgroup (5 row tiles of 16 experts)
+    (70, 16, 1100, True),    # two token tiles of a chunk per workgroup
+    (64, 32, 1100, True),    # four token tiles per workgroup
+    (30, 28, 1200, False),   # four token tiles, the last one ragged, a partial row tile of experts
+    (16, 8, 300, True),      # a single row tile
+    (130, 11, 300, True),    # three mask words, nine row tiles, ragged token tile
+])
+def test_exact_arithmetic_router_fixture_on_the_matrix_cores(E, k, C, fine):
+    """The exact-arithmetic fixture with bf16 weights and enough token tiles that the matrix-core
+    router is dispatched, with one, two and four token tiles of a chunk per workgroup.  Weights are
+    j / 64 with |j| <= 8 (exact in bf16), the bias a multiple of 2^-8, the hidden size 520 ends in a
+    partial K-step.  x is i / 4 with |i| <= 4 (one bf16 piece), or `fine`: i / 1024 with
+    |i| <= 2048 (12 significant bits: two or three bf16 pieces).  Every product is a multiple of
+    2^-16 and every partial sum stays below 2^8, so all sums are exact in fp32 in any order of
+    addition: masks and pre-activations must equal the integer result."""
+    rng = np.random.default_rng(1000 * E + k)
+    d, T = 520, k * C
+    xs, xmax = (1024, 2048) if fine else (4, 4)
+    xi = rng.integers(-xmax, xmax + 1, (T, d))
+    wi = rng.integers(-8, 9, (E, d))
+    bi = rng.integers(-300, 300, E)
+    w_router = torch.tensor(wi / 64.0, dtype=torch.float32).to(torch.bfloat16)
+    assert torch.equal(w_router.float(), torch.tensor(wi / 64.0, dtype=torch.float32))
+    zeros = lambda *shape: torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    L = B.Layer(w_router[None].cuda(), zeros(1, E, 8, d), zeros(1, E, d, 8), None,
+                torch.tensor(bi / 256.0, dtype=torch.float32)[None].cuda(), None, 1e-6)
+    x = torch.tensor(xi / float(xs), dtype=torch.float32)
+    assert torch.equal((x.double() * xs).round().long(), torch.tensor(xi))
+    W = (E + 63) // 64
+    scores = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    mask = torch.empty((T, W), dtype=torch.int64, device="cuda")
+    pre = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    B.blockffn_router_preact(L, x.cuda(), C, k, scores, mask, pre)
+    torch.cuda.synchronize()
+    unit = 1.0 / (xs * 64)                      # 2^-8 or 2^-16: what one step of x times one step of W is worth
+    exact = xi @ wi.T + bi * (xs // 4)          # A^0 in those units (the bias is a multiple of 2^-8)
+    np.testing.assert_array_equal(pre.cpu().numpy().astype(np.float64), exact * unit)
+    want = np.zeros((T, W), np.uint64)
+    for i in range(E):
+        want[:, i // 64] |= (exact[:, i] > 0).astype(np.uint64) << np.uint64(i % 64)
+    np.testing.assert_array_equal(mask.cpu().numpy().view(np.uint64), want)
+    np.testing.assert_array_equal(scores.cpu().numpy() > 0, exact > 0)
+
+
+@pytest.mark.parametrize("seed,gated,p_active,sigma", [(1049, True, 0.2, 0.6), (7, True, 0.05, 0.3),
+                                                       (8, False, 0.05, 0.6), (9, False, 0.2, 0.0)])
+def test_large_chunk_rows_of_few_terms(seed, gated, p_active, sigma):
+    """Rows of y made of one or two short experts (8 experts of 64 neurons, 257 tokens): the fewest
+    terms a row of the large-chunk path can average its rounding over.  The first case is the
+    input on which the path, while it still rounded x to bf16, left a row at 2.3e-2 of its rms."""
+    w = wl.Workload("t", d=1024, E=8, d_e=64, wdtype="bf16", gated=gated, k=257, n_chunks=3, sigma=sigma, seed=seed,
+                    p_active=p_active)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    ref = pu.run_oracle(layers, x, w.k, dense=False)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, dense=False)
+    pu.assert_integers_equal(gpu, ref)
+    n_act = np.array([bin(int(v)).count("1") for v in ref["token_mask"][:, 0]])
+    assert (n_act == 1).sum() >= 20          # the rows this test is about are there
+    # a token whose single expert is barely active has an ill-conditioned score (see
+    # score_error_allowed); the FFN is judged on every row with the scores it was given
+    pu.assert_scores_within_allowance(gpu["scores"], ref["scores"],
+                                      pu.score_error_allowed(layers, x, w.k, None, ref["scores"], use_gain=False))
+    y_ref = pu.oracle_ffn_on_gpu_routing(layers, x, w.k, None, gpu, use_gain=False)
+    e_y = pu.row_rel_err(gpu["y"], y_ref)
+    num, den = ((gpu["y"] - y_ref) ** 2).sum(axis=1), (y_ref ** 2).sum(axis=1)
+    l2 = np.sqrt(num[den > 0] / den[den > 0])
+    print("row max / rms: worst %.3e median %.3e; L2-relative: worst %.3e median %.3e"
+          % (e_y.max(), np.median(e_y[den > 0]), l2.max(), np.median(l2)), flush=True)
+    # mid is the one value rounded to bf16 on this path (2^-9 relative per element): measured on these
+    # inputs 1.26e-2 / 2.7e-3 at worst; held with the margin that leaves under the stated 2e-2
+    assert e_y.max() <= pu.GEMM_FEW_TERMS_BAR and l2.max() <= pu.GEMM_L2_BAR
+
+
+@pytest.mark.parametrize("d,E,d_e,k,C", [(2048, 64, 128, 8, 3),     # few chunks: one workgroup per (slot, row tile)
+                                         (1024, 32, 128, 8, 80),    # the persistent up kernel
+                                         (2048, 64, 128, 32, 3),    # double-buffered up kernel, items of several slots
+                                         (2048, 64, 256, 24, 3),    # single-buffer kernel at k > 8
+                                         (1024, 32, 128, 100, 2),   # large chunks: token lists
+                                         (264, 16, 24, 4, 7)])      # the shape-generic kernels
+def test_list_entry_out_of_range_is_an_empty_slot(d, E, d_e, k, C):
+    """An entry of active_idx below n_active that lies outside [0, N_e) contributes nothing, on
+    every kernel path: the result equals the oracle's for the list with that expert left out."""
+    import oracle
+    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=True, k=k, n_chunks=C, sigma=0.3, seed=3 * k + E,
+                    p_active=0.4)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k)
+    L, buf = gpu["_layer"], gpu["_buf"]
+    idx, n_act = gpu["active_idx"].copy(), gpu["n_active"].copy()
+    assert n_act.min() >= 3
+    bad = idx.copy()
+    ref_idx = np.full_like(idx, -1)
+    for c in range(C):
+        kill = [1, n_act[c] - 1] if c % 2 == 0 else [0]        # slots overwritten with invalid entries
+        bad[c, kill] = [-1, E + 5][:len(kill)]
+        keep = [s for s in range(n_act[c]) if s not in kill]
+        ref_idx[c, :len(keep)] = idx[c, keep]
+    ref_n = (ref_idx >= 0).sum(axis=1).astype(np.int32)
+    buf.active_idx.copy_(torch.tensor(bad))
+    y = torch.full_like(buf.y, float("nan"))
+    B.blockffn_sparse_ffn(L, x.cuda(), buf.scores, buf.token_mask, buf.active_idx, buf.n_active, C, k, y, buf.workspace)
+    torch.cuda.synchronize()
+    y_ref = oracle.sparse_ffn(pu.oracle_layer(layers, 0), x.numpy(), gpu["scores"], gpu["token_mask"], ref_idx, ref_n, k)
+    e = pu.row_rel_err(y.cpu().numpy(), y_ref).max(initial=0.0)
+    assert e <= (pu.GEMM_BAR if k > 32 else pu.TIGHT["bf16"]), e
+
+
+def test_work_list_of_many_chunks():
+    """66 000 chunks: the flat work list is built by 65 workgroups, each placing its 1024 chunks
+    behind the items of all earlier chunks and passes.  Properties on every chunk, the oracle on
+    sampled ones (first, last, both sides of the workgroups' boundaries)."""
+    w = wl.Workload("t", d=512, E=8, d_e=64, wdtype="bf16", gated=True, k=2, n_chunks=66000, sigma=0.3, seed=21,
+                    p_active=0.3)
+    layers = wl.make_layers(w, 2, device="cuda")
+    cl = wl.make_chunk_layer(w, 2, device="cuda")
+    x = wl.make_tokens(w, layers, cl, device="cuda")
+    gpu = pu.run_gpu(layers, x, w.k, cl)
+    chunks = [0, 1, 1023, 1024, 1025, 2047, 2048, 33333, 65535, 65536, 65537, 65998, 65999]
+    layers_cpu = {n: (None if t is None else t.cpu()) for n, t in layers.items()}
+    ref = pu.run_oracle(layers_cpu, x.cpu(), w.k, cl.cpu(), chunks=chunks)
+    pu.assert_integers_equal(gpu, ref, chunks=chunks, k=w.k)
+    rows = (np.asarray(chunks)[:, None] * w.k + np.arange(w.k)[None, :]).reshape(-1)
+    e = pu.row_rel_err(gpu["y"][rows], ref["y"][rows]).max(initial=0.0)
+    assert e <= pu.TIGHT["bf16"], e
+    # every chunk: a token without an active expert has an exactly zero row, every other a non-zero
+    # one (an item missing from the list, or listed twice, would leave a slot's mid stale or unset)
+    none_active = gpu["token_mask"][:, 0] == 0
+    assert np.all(gpu["y"][none_active] == 0)
+    assert np.all(np.abs(gpu["y"][~none_active]).max(axis=1) > 0)
+    assert np.isfinite(gpu["y"]).all()
+    # the same batch in two halves gives the same bits (each half builds its own, shorter list)
+    L, buf = gpu["_layer"], gpu["_buf"]
+    half = w.n_chunks // 2
+    y2 = torch.empty_like(buf.y)
+    for lo, n in ((0, half), (half, w.n_chunks - half)):
+        t0, t1 = lo * w.k, (lo + n) * w.k
+        B.blockffn_sparse_ffn(L, x[t0:t1], buf.scores[t0:t1], buf.token_mask[t0:t1], buf.active_idx[lo:lo + n],
+                              buf.n_active[lo:lo + n], n, w.k, y2[t0:t1], buf.workspace, cl[lo:lo + n].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(y2, buf.y)

@@ -43,22 +43,33 @@ def test_seeded_shapes(seed):
         try:
             x = wl.make_tokens(w, layers, cl)
         except RuntimeError:
+            print("case", it, cfg, "not generated (guard band)", flush=True)
             continue   # the generator could not keep every pre-activation off the guard band
         print("case", it, cfg, "layers", n_layers, flush=True)
         ref = pu.run_oracle(layers, x, w.k, cl, dense=False)
         gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, cl, dense=False)
         pu.assert_integers_equal(gpu, ref)
         np.testing.assert_array_equal(gpu["scores"] == 0, ref["scores"] == 0)
-        # scores: the bound of score_error_allowed(); the outputs of the rows that meet the plain
-        # 1e-5 bar (all but the few tokens whose only active expert is barely active, whose score
-        # error the FFN passes on) are held to the usual bars
-        err_s = np.abs(gpu["scores"].astype(np.float64) - ref["scores"]).max(axis=1)
-        assert np.all(err_s <= pu.score_error_allowed(layers, x, w.k, cl, ref["scores"]))
-        rms = np.sqrt((ref["scores"].astype(np.float64) ** 2).mean(axis=1))
-        good = err_s <= 1e-5 * np.maximum(rms, 1e-30)
-        assert good.mean() >= 0.9
-        e_y = pu.row_rel_err(gpu["y"][good], ref["y"][good]).max(initial=0.0)
+        # scores: every row inside the bound derived from the fp32 additions behind A^0
+        pu.assert_scores_within_allowance(gpu["scores"], ref["scores"],
+                                          pu.score_error_allowed(layers, x, w.k, cl, ref["scores"]), "(case %d)" % it)
+        # FFN: EVERY row against the oracle's FFN driven by the scores, masks and lists the HIP path
+        # produced (a token whose only active expert is barely active carries a magnified score error
+        # that the FFN passes on; judged this way the FFN kernels answer for their own arithmetic only)
+        y_ref = pu.oracle_ffn_on_gpu_routing(layers, x, w.k, cl, gpu)
+        e_y = pu.row_rel_err(gpu["y"], y_ref).max(initial=0.0)
         bar = pu.GEMM_BAR if w.k > 32 else pu.TIGHT["bf16"]
         assert e_y <= bar, "sparse FFN output off by %.3g (bar %.1g) in %s" % (e_y, bar, cfg)
+        if w.k > 32:
+            num = ((gpu["y"] - y_ref) ** 2).sum(axis=1)
+            den = (y_ref ** 2).sum(axis=1)
+            l2 = np.sqrt(num[den > 0] / den[den > 0]).max(initial=0.0)
+            assert l2 <= pu.GEMM_L2_BAR, "L2-relative error %.3g (bar %.1g) in %s" % (l2, pu.GEMM_L2_BAR, cfg)
+        # and the end-to-end output of the rows whose scores meet the plain bar, against the plain oracle
+        err_s = np.abs(gpu["scores"].astype(np.float64) - ref["scores"]).max(axis=1)
+        rms = np.sqrt((ref["scores"].astype(np.float64) ** 2).mean(axis=1))
+        good = err_s <= 1e-5 * np.maximum(rms, 1e-30)
+        e_y = pu.row_rel_err(gpu["y"][good], ref["y"][good]).max(initial=0.0)
+        assert e_y <= bar, "end-to-end output off by %.3g (bar %.1g) in %s" % (e_y, bar, cfg)
         done += 1
-    assert done >= 20
+    assert done >= 28, "only %d of 30 shapes could be generated" % done
