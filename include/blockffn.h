@@ -58,8 +58,12 @@ enum {
   BLOCKFFN_ERR_INVALID = -1,     /* NULL pointer, size < 1, d or d_e not a multiple of 8, misaligned weights */
   BLOCKFFN_ERR_UNSUPPORTED = -2, /* shape or dtype outside the limits above */
   BLOCKFFN_ERR_WORKSPACE = -3,   /* workspace smaller than blockffn_workspace_bytes() */
-  BLOCKFFN_ERR_LAUNCH = -4       /* the HIP runtime refused a launch */
+  BLOCKFFN_ERR_LAUNCH = -4,      /* the HIP runtime refused a launch */
+  BLOCKFFN_ERR_SCRATCH = -5      /* blockffn_sparse_ffn_static: the shape needs more than BLOCKFFN_STATIC_SCRATCH_BYTES */
 };
+
+/* Size of the per-device static scratch array behind blockffn_sparse_ffn_static. */
+#define BLOCKFFN_STATIC_SCRATCH_BYTES (128u << 20)
 
 typedef struct blockffn_layer {
   int32_t d;           /* d_h: hidden size */
@@ -113,6 +117,22 @@ int blockffn_sparse_ffn(const blockffn_layer *layer, const int32_t *chunk_layer,
 int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
                        const float *scores, int64_t n_chunks, int32_t k, float *y,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* blockffn_sparse_ffn for callers that cannot allocate device memory and so have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as blockffn_sparse_ffn; the workspace is a static device array of
+ * BLOCKFFN_STATIC_SCRATCH_BYTES (128 MiB) that every GPU the library runs on holds until the
+ * process ends.  The call allocates and frees nothing.  A shape whose blockffn_workspace_bytes()
+ * exceeds that size returns BLOCKFFN_ERR_SCRATCH and enqueues nothing (at N_e = 64, d_e = 256,
+ * d = 2048 the array holds 200 chunks of 8 tokens, 56 chunks of 32 tokens, or one 512-token
+ * prefill chunk).  All calls on one GPU share the array: calls
+ * that overlap in time on one GPU (two streams, two threads) race; calls on one stream, and calls
+ * on different GPUs, do not.  Nothing in the array needs clearing between calls: every word a
+ * kernel reads is written earlier in the same call. */
+int blockffn_sparse_ffn_static(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                               const float *scores, const uint64_t *token_mask,
+                               const int32_t *active_idx, const int32_t *n_active, int64_t n_chunks,
+                               int32_t k, float *y, void *stream);
 
 /* The two halves of blockffn_sparse_ffn as separate enqueues (Sec. 3.3 describes the up and
  * the down projection as two sparse matrix products with the intermediate `mid` between

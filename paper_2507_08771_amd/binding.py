@@ -19,13 +19,15 @@ LIB_PATH = os.path.join(HERE, "libblockffn.so")
 
 F32, BF16 = 0, 1
 EXPERT_SWISH, EXPERT_GATED = 0, 1
-OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
+OK, ERR_INVALID, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH, ERR_SCRATCH = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 128 << 20
 
 EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
            "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_workspace_bytes", "blockffn_strerror",
            "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio", "blockffn_router_preact",
            "blockffn_router_losses", "blockffn_losses_workspace_bytes", "blockffn_offload_sim",
-           "blockffn_stream_read", "blockffn_force_generic")
+           "blockffn_sparse_ffn_static", "blockffn_stream_read",
+           "blockffn_force_generic")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -62,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.blockffn_chunk_union.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp]
         L.blockffn_sparse_ffn.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
         L.blockffn_dense_ffn.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
+        L.blockffn_sparse_ffn_static.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp]
         L.blockffn_sparse_ffn_up.argtypes = [lp, vp, vp, vp, vp, vp, vp, i64, i32, vp, sz, vp]
         L.blockffn_sparse_ffn_down.argtypes = [lp, vp, vp, vp, i64, i32, vp, vp, sz, vp]
         L.blockffn_router_preact.argtypes = [lp, vp, vp, i64, i32, vp, vp, vp, vp]
@@ -83,7 +86,8 @@ def lib() -> ctypes.CDLL:
         L.blockffn_version.restype = ctypes.c_int
         for n in ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "blockffn_dense_ffn",
                   "blockffn_sparse_ffn_up", "blockffn_sparse_ffn_down", "blockffn_cls_sweep",
-                  "blockffn_reuse_ratio", "blockffn_router_preact", "blockffn_router_losses"):
+                  "blockffn_reuse_ratio", "blockffn_router_preact", "blockffn_router_losses",
+                  "blockffn_sparse_ffn_static"):
             getattr(L, n).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -203,6 +207,14 @@ def blockffn_sparse_ffn(layer: Layer, x, scores, token_mask, active_idx, n_activ
                                      _p(n_active), n_chunks, k, _p(y), _p(workspace),
                                      workspace.numel() * workspace.element_size(), _stream(stream)),
            "blockffn_sparse_ffn")
+
+
+def blockffn_sparse_ffn_static(layer: Layer, x, scores, token_mask, active_idx, n_active, n_chunks: int, k: int, y,
+                               chunk_layer=None, stream=None):
+    """blockffn_sparse_ffn on the library's static scratch: no workspace argument, nothing allocated."""
+    _check(lib().blockffn_sparse_ffn_static(layer.ref(), _p(chunk_layer), _p(x), _p(scores), _p(token_mask),
+                                            _p(active_idx), _p(n_active), n_chunks, k, _p(y), _stream(stream)),
+           "blockffn_sparse_ffn_static")
 
 
 def blockffn_dense_ffn(layer: Layer, x, scores, n_chunks: int, k: int, y, workspace: torch.Tensor,

@@ -1,10 +1,17 @@
 // C ABI of the library: argument checking and dispatch.  No kernel lives here.
 #include <algorithm>
 #include <cstdlib>
+#include <mutex>
 
 #include "common.hpp"
 
 using namespace blockffn;
+
+// Scratch of blockffn_sparse_ffn_static: one copy per device, held from the moment the library's
+// code is loaded on that device until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress(); the device address it yields (static_scratch() below) is what the
+// kernels, like any workspace pointer, are given.
+static __device__ __align__(256) unsigned char scratch[BLOCKFFN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -61,6 +68,21 @@ bool force_generic() {
   return set < 0 ? from_env : set != 0;
 }
 
+// Device address of `scratch` on the current device; looked up once per device.
+int static_scratch(void **out) {
+  static std::mutex mu;
+  static void *ptr[kMaxDevices];   // zero-initialised
+  const int dev = current_device();
+  if (dev < 0) return BLOCKFFN_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return BLOCKFFN_ERR_LAUNCH;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return BLOCKFFN_OK;
+}
 bool use_stream(const LayerView &v, int wdtype, int32_t k) { return !force_generic() && stream_supported(v, wdtype, k); }
 bool use_gemm(const LayerView &v, int wdtype, int32_t k, bool gated) {
   return !force_generic() && gemm_supported(v, wdtype, k, gated);
@@ -75,7 +97,7 @@ size_t workspace_need(const LayerView &v, int wdtype, bool gated, int64_t n_chun
   return bytes;
 }
 
-enum { kPhaseUp = 1, kPhaseDown = 2 };
+enum { kPhaseUp = 1, kPhaseDown = 2, kStaticScratch = 4 };   // kStaticScratch: the workspace is the static array
 
 int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
                const float *scores, const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
@@ -100,6 +122,12 @@ int ffn_common(int phases, const blockffn_layer *layer, const int32_t *chunk_lay
   if (n_chunks * v.E > 0x7fffffffLL) return BLOCKFFN_ERR_UNSUPPORTED;   // (chunk, slot) pairs are indexed in 32 bits
   const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
   const size_t need = workspace_need(v, layer->wdtype, gated, n_chunks, k);
+  if (phases & kStaticScratch) {
+    if (need > (size_t)BLOCKFFN_STATIC_SCRATCH_BYTES) return BLOCKFFN_ERR_SCRATCH;
+    rc = static_scratch(&workspace);
+    if (rc != BLOCKFFN_OK) return rc;
+    workspace_bytes = (size_t)BLOCKFFN_STATIC_SCRATCH_BYTES;
+  }
   if (workspace == nullptr || !aligned(workspace, 256)) return BLOCKFFN_ERR_INVALID;
   if (workspace_bytes < need) return BLOCKFFN_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -240,6 +268,14 @@ int blockffn_sparse_ffn(const blockffn_layer *layer, const int32_t *chunk_layer,
                     k, y, workspace, workspace_bytes, stream);
 }
 
+int blockffn_sparse_ffn_static(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                               const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
+                               const int32_t *n_active, int64_t n_chunks, int32_t k, float *y, void *stream) {
+  if (active_idx == nullptr || n_active == nullptr || token_mask == nullptr) return BLOCKFFN_ERR_INVALID;
+  return ffn_common(kPhaseUp | kPhaseDown | kStaticScratch, layer, chunk_layer, x, scores, token_mask, active_idx,
+                    n_active, n_chunks, k, y, nullptr, 0, stream);
+}
+
 int blockffn_sparse_ffn_up(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
                            const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
                            const int32_t *n_active, int64_t n_chunks, int32_t k, void *workspace,
@@ -289,6 +325,7 @@ const char *blockffn_strerror(int code) {
     case BLOCKFFN_ERR_UNSUPPORTED: return "unsupported shape or dtype";
     case BLOCKFFN_ERR_WORKSPACE: return "workspace too small";
     case BLOCKFFN_ERR_LAUNCH: return "HIP launch error";
+    case BLOCKFFN_ERR_SCRATCH: return "shape needs more than the static scratch holds (BLOCKFFN_STATIC_SCRATCH_BYTES)";
     default: return "unknown error code";
   }
 }

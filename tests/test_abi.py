@@ -36,7 +36,7 @@ def test_binding_has_the_same_names():
 
 def test_strerror():
     assert B.strerror(0) == "ok"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert B.strerror(code) not in ("ok", "unknown error code")
     assert B.strerror(-99) == "unknown error code"
 
@@ -118,6 +118,29 @@ def test_sizes_beyond_32_bit_indexing_are_unsupported():
     assert router_rc(lay, n_chunks=1 << 28, k=8) == B.ERR_UNSUPPORTED
     assert lib.blockffn_dense_ffn(ctypes.byref(lay), None, FAKE, FAKE, 1 << 26, 8, FAKE, FAKE, big, None) == B.ERR_UNSUPPORTED
     assert lib.blockffn_workspace_bytes(ctypes.byref(lay), 1 << 28, 8) == 0
+
+
+def test_static_scratch_entry_point_argument_checks():
+    """The entry point without a workspace argument: same argument checks as blockffn_sparse_ffn,
+    and a shape that needs more than the static array is refused with its own code.  None of
+    these calls reaches the GPU."""
+    lib = B.lib()
+    lay = layer()
+    f = lambda n_chunks=4, k=8, x=FAKE, scores=FAKE, mask=FAKE, idx=FAKE, n_act=FAKE, y=FAKE, l=lay: \
+        lib.blockffn_sparse_ffn_static(ctypes.byref(l), None, x, scores, mask, idx, n_act, n_chunks, k, y, None)
+    assert f(n_chunks=0) == B.OK
+    assert f(x=None) == B.ERR_INVALID and f(scores=None) == B.ERR_INVALID and f(mask=None) == B.ERR_INVALID
+    assert f(idx=None) == B.ERR_INVALID and f(n_act=None) == B.ERR_INVALID and f(y=None) == B.ERR_INVALID
+    assert f(k=0) == B.ERR_INVALID and f(k=513) == B.ERR_UNSUPPORTED
+    assert f(l=layer(d=2044)) == B.ERR_INVALID
+    assert lib.blockffn_workspace_bytes(ctypes.byref(lay), 2048, 8) > B.STATIC_SCRATCH_BYTES
+    assert f(n_chunks=2048) == B.ERR_SCRATCH
+    # the capacities the header names
+    big = layer(d_e=256)
+    for n_chunks, k in ((200, 8), (56, 32), (1, 512)):
+        assert lib.blockffn_workspace_bytes(ctypes.byref(big), n_chunks, k) <= B.STATIC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "blockffn.h")).read()
+    assert re.search(r"#define\s+BLOCKFFN_STATIC_SCRATCH_BYTES\s+\(128u << 20\)", text)
 
 
 def test_force_generic_modes():
