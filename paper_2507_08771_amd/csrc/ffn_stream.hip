@@ -27,35 +27,15 @@
 //   down  grid (chunk, 512 output columns); the reduction runs over the union's slots and the
 //         expert's neurons; mid of the next slot is staged through LDS (double buffered) while
 //         the current slot's W_down rows stream; one writer per output element.
-#include <algorithm>
-
-#include "common.hpp"
+#include "stream_common.hpp"
 
 namespace blockffn {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-constexpr int kThreads = 256;
+constexpr int kThreads = kStreamThreads;
 constexpr int kRing = 16;          // 128-bit loads in flight per lane
 constexpr int kXBytes = 64 * 1024; // LDS for the split activations of one K-chunk
-
-__device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
-                                                 0, 0);
-}
-
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
-}
-
-// x = hi + lo with hi = bf16(x) and lo = bf16(x - hi); 16-bit patterns in the low halves
-__device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
-  hi = bf16_bits(x);
-  lo = bf16_bits(x - __uint_as_float(hi << 16));
-}
 
 constexpr int acc_tiles(int NB) { return NB == 4 ? 2 : 1; }
 constexpr int acc_of(int NB, int bf) { return NB == 4 ? bf / 2 : 0; }
@@ -245,16 +225,7 @@ __device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], 
   }
 }
 
-// mid in memory, k <= 8 (NB = 1): in the order the down kernel's B operand is read from LDS,
-// [chunk][slot][K-step = d_e / 32][64 lanes] of 8 bf16, lane gg * 16 + n holding the expert's
-// neurons 32 * K-step + 8 gg .. + 7 for fragment column n (0-7: hi of tokens 0-7, 8-15: their lo).
-// The up kernels hold, per lane (n, g) of row tile T, the four neurons 16 T + 4 g .. + 3: half
-// (g & 1) of the 16-byte entry of lane (2 (T & 1) + g / 2) * 16 + n in K-step T / 2, so the 64
-// lanes of one store cover 512 contiguous bytes and the down kernel's staging is a linear copy.
-__device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int T, int g, int n) {
-  const size_t entry = (kstep0 + (T >> 1)) * 64 + ((T & 1) * 2 + (g >> 1)) * 16 + n;
-  return reinterpret_cast<uint2 *>(midB) + entry * 2 + (g & 1);
-}
+// mid in memory, k <= 8 (NB = 1): mid_entry() in stream_common.hpp.
 // k > 8 (NB = 2, 4): token-major, [chunk][slot][token][hi, lo][d_e] bf16, and only the rows of
 // tokens whose mask bit for the slot's expert is set (and whose score is not zero) are written;
 // tok_bits[chunk * E + slot] has bit t set for them.  At k = 32 about 60 % of the (token, slot)
@@ -770,6 +741,16 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   e = min(max(e, 0), E - 1);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int kq0 = wave * (d / 4);
+  const int tok = n & 7, half = n >> 3;
+  // score and mask word of this lane's token, for the epilogue (wave 0): requested first, so that
+  // they are back before the weights instead of costing a round trip after them
+  float f = 0.0f;
+  uint64_t mword = ~0ull;
+  if (wave == 0 && tok < k) {
+    const int64_t t = c * k + tok;
+    if (token_mask) mword = token_mask[t * L.W + (e >> 6)];
+    f = scores[t * E + e];
+  }
 
   uint4 a[NM][FW];
 #pragma unroll
@@ -782,7 +763,6 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   // x of this wave's quarter of the contraction.  Fragment column n carries token n & 7, its hi
   // part for n < 8 and its lo part for n >= 8, so lanes n and n + 8 need the same 8 floats: each
   // loads one half (4 floats), splits it, and the two exchange what the other needs.
-  const int tok = n & 7, half = n >> 3;
   const float *xrow = x + (c * k + min(tok, k - 1)) * d + kq0 + g * 8 + half * 4;
   float4 xv[FW];
 #pragma unroll
@@ -817,13 +797,7 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   __syncthreads();
   if (wave != 0) return;
 
-  float f = 0.0f;
-  bool on = false;
-  if (tok < k) {
-    const int64_t t = c * k + tok;
-    on = e_ok && (token_mask ? (bool)((token_mask[t * L.W + (e >> 6)] >> (e & 63)) & 1) : true);
-    f = scores[t * E + e];
-  }
+  const bool on = e_ok && tok < k && ((mword >> (e & 63)) & 1);
   uint32_t packed[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
@@ -1052,16 +1026,6 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const float *
   }
 }
 
-// Few chunks: narrow column blocks (8 fragments per slot and wave) and up to 8 slot splits, so
-// that one chunk still spreads over the whole chip.
-int down_splits(const LayerView &L, int64_t n_chunks) {
-  const int64_t wide = n_chunks * (L.d / 512);
-  if (wide >= 2 * num_cus()) return 0;   // 0: the wide, unsplit configuration
-  const int ksd = L.d_e / 32;
-  const int64_t narrow = n_chunks * (L.d / (64 * (8 / ksd)));
-  return (int)std::min<int64_t>(8, std::max<int64_t>(1, (num_cus() + narrow - 1) / narrow));
-}
-
 template <int NB, int KSD>
 hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,
                        const int32_t *n_active, int64_t n_chunks, int k, const uint16_t *midB, const uint32_t *tok_bits,
@@ -1089,43 +1053,6 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)std::min<size_t>((n4 + kThreads - 1) / kThreads, 1024)),
                      dim3(kThreads), 0, s, part, splits, stride, n4, y);
   return hipGetLastError();
-}
-
-int b_frags(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
-
-struct StreamWs {
-  uint16_t *midB;
-  int32_t *items, *total;
-  uint32_t *tok_bits;    // [chunk * E + slot]: the tokens whose rows of mid are written (k > 8)
-  const uint4 *zero16;   // 16 bytes of zeros, written with the work list
-  uint4 *xS;     // the chunks' x split into bf16 hi/lo in B-operand order
-  float *part;   // partial sums of the split down projection (few chunks only)
-};
-
-size_t xs_bytes(const LayerView &L, int64_t n_chunks, int k) {
-  return (size_t)n_chunks * (L.d / 32) * b_frags(k) * 64 * sizeof(uint4);   // a multiple of 1024
-}
-
-size_t mid_bytes(const LayerView &L, int64_t n_chunks, int k) {
-  return ((size_t)n_chunks * L.E * b_frags(k) * 16 * L.d_e * 2 + 255) & ~(size_t)255;
-}
-
-size_t item_bytes(const LayerView &L, int64_t n_chunks) {
-  // 64 words of counters and constants, the item list, the token bits of every slot
-  return (((size_t)n_chunks * L.E * 2 + 64) * sizeof(int32_t) + 255) & ~(size_t)255;
-}
-
-StreamWs carve(const LayerView &L, int64_t n_chunks, int k, void *ws) {
-  char *p = static_cast<char *>(ws);
-  StreamWs w;
-  w.midB = reinterpret_cast<uint16_t *>(p);
-  w.total = reinterpret_cast<int32_t *>(p + mid_bytes(L, n_chunks, k));
-  w.items = w.total + 64;
-  w.tok_bits = reinterpret_cast<uint32_t *>(w.items + (size_t)n_chunks * L.E);
-  w.zero16 = reinterpret_cast<const uint4 *>(w.total + 16);
-  w.xS = reinterpret_cast<uint4 *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks));
-  w.part = reinterpret_cast<float *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks) + xs_bytes(L, n_chunks, k));
-  return w;
 }
 
 }  // namespace
@@ -1158,10 +1085,10 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
                             const int32_t *n_active, int64_t n_chunks, int k, void *ws, hipStream_t s) {
   if (n_chunks <= 0) return hipSuccess;
   if (n_chunks * L.E > 0x7fffffffLL) return hipErrorInvalidValue;
-  StreamWs w = carve(L, n_chunks, k, ws);
+  StreamWs w = carve_stream(L, n_chunks, k, ws);
   const int NB = b_frags(k), RT = L.d_e / 64;
   const int64_t max_items = n_chunks * L.E;
-  if (NB == 1 && max_items <= 2048 && (L.d == 1024 || L.d == 2048)) {
+  if (few_chunks(L, n_chunks, k)) {
     // few chunks: one workgroup per (item, 16-row tile)
     const dim3 grid((unsigned)(max_items * (L.d_e / 16)));
 #define BLOCKFFN_SPLIT(nm, fw)                                                                             \
@@ -1219,7 +1146,7 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
                               const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
                               hipStream_t s) {
   if (n_chunks <= 0) return hipSuccess;
-  StreamWs w = carve(L, n_chunks, k, const_cast<void *>(ws));
+  StreamWs w = carve_stream(L, n_chunks, k, const_cast<void *>(ws));
   const int NB = b_frags(k), KSD = L.d_e / 32;
 #define BLOCKFFN_CASE(nb, ksd) \
   if (NB == nb && KSD == ksd) \

@@ -1,0 +1,99 @@
+// What the weight-streaming kernels of ffn_stream.hip and the single-launch kernel for a few chunks
+// (ffn_few.hip) share: the matrix-core step, the bf16 hi/lo split of an fp32 value, the layout
+// of mid at k <= 8 and the carving of the workspace.
+#pragma once
+
+#include <algorithm>
+
+#include "common.hpp"
+
+namespace blockffn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kStreamThreads = 256;
+
+__device__ __forceinline__ f32x4 mfma16(uint4 a, uint4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                 0, 0);
+}
+
+__device__ __forceinline__ uint32_t bf16_bits(float f) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
+}
+
+// x = hi + lo with hi = bf16(x) and lo = bf16(x - hi); 16-bit patterns in the low halves
+__device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
+  hi = bf16_bits(x);
+  lo = bf16_bits(x - __uint_as_float(hi << 16));
+}
+
+// mid in memory, k <= 8 (one B fragment per K-step): in the order the down kernel's B operand is
+// read from LDS, [chunk][slot][K-step = d_e / 32][64 lanes] of 8 bf16, lane gg * 16 + n holding the
+// expert's neurons 32 * K-step + 8 gg .. + 7 for fragment column n (0-7: hi of tokens 0-7, 8-15:
+// their lo).  The up kernels hold, per lane (n, g) of row tile T, the four neurons 16 T + 4 g .. + 3:
+// half (g & 1) of the 16-byte entry of lane (2 (T & 1) + g / 2) * 16 + n in K-step T / 2, so the 64
+// lanes of one store cover 512 contiguous bytes and the down kernel's staging is a linear copy.
+__device__ __forceinline__ uint2 *mid_entry(uint16_t *midB, size_t kstep0, int T, int g, int n) {
+  const size_t entry = (kstep0 + (T >> 1)) * 64 + ((T & 1) * 2 + (g >> 1)) * 16 + n;
+  return reinterpret_cast<uint2 *>(midB) + entry * 2 + (g & 1);
+}
+
+// ------------------------------------------------------------------------------------------------ workspace
+
+inline int b_frags(int k) { return k <= 8 ? 1 : (k <= 16 ? 2 : 4); }
+
+struct StreamWs {
+  uint16_t *midB;
+  int32_t *items, *total;
+  uint32_t *tok_bits;    // [chunk * E + slot]: the tokens whose rows of mid are written (k > 8)
+  const uint4 *zero16;   // 16 bytes of zeros, written with the work list
+  uint4 *xS;     // the chunks' x split into bf16 hi/lo in B-operand order
+  float *part;   // partial sums of the split down projection (few chunks only)
+};
+
+inline size_t xs_bytes(const LayerView &L, int64_t n_chunks, int k) {
+  return (size_t)n_chunks * (L.d / 32) * b_frags(k) * 64 * sizeof(uint4);   // a multiple of 1024
+}
+
+inline size_t mid_bytes(const LayerView &L, int64_t n_chunks, int k) {
+  return ((size_t)n_chunks * L.E * b_frags(k) * 16 * L.d_e * 2 + 255) & ~(size_t)255;
+}
+
+inline size_t item_bytes(const LayerView &L, int64_t n_chunks) {
+  // 64 words of counters and constants, the item list, the token bits of every slot
+  return (((size_t)n_chunks * L.E * 2 + 64) * sizeof(int32_t) + 255) & ~(size_t)255;
+}
+
+inline StreamWs carve_stream(const LayerView &L, int64_t n_chunks, int k, void *ws) {
+  char *p = static_cast<char *>(ws);
+  StreamWs w;
+  w.midB = reinterpret_cast<uint16_t *>(p);
+  w.total = reinterpret_cast<int32_t *>(p + mid_bytes(L, n_chunks, k));
+  w.items = w.total + 64;
+  w.tok_bits = reinterpret_cast<uint32_t *>(w.items + (size_t)n_chunks * L.E);
+  w.zero16 = reinterpret_cast<const uint4 *>(w.total + 16);
+  w.xS = reinterpret_cast<uint4 *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks));
+  w.part = reinterpret_cast<float *>(p + mid_bytes(L, n_chunks, k) + item_bytes(L, n_chunks) + xs_bytes(L, n_chunks, k));
+  return w;
+}
+
+// Few chunks: narrow column blocks (8 fragments per slot and wave) and up to 8 slot splits, so
+// that one chunk still spreads over the whole chip.  0: the wide, unsplit configuration.
+inline int down_splits(const LayerView &L, int64_t n_chunks) {
+  const int64_t wide = n_chunks * (L.d / 512);
+  if (wide >= 2 * num_cus()) return 0;
+  const int ksd = L.d_e / 32;
+  const int64_t narrow = n_chunks * (L.d / (64 * (8 / ksd)));
+  return (int)std::min<int64_t>(8, std::max<int64_t>(1, (num_cus() + narrow - 1) / narrow));
+}
+
+// A launch with this few (chunk, slot) pairs cannot occupy the chip with one workgroup per pair:
+// the up projection runs one workgroup per (pair, 16-row tile) with the contraction split over the
+// waves (k <= 8, d = 1024 or 2048).
+inline bool few_chunks(const LayerView &L, int64_t n_chunks, int k) {
+  return k <= 8 && n_chunks * L.E <= 2048 && (L.d == 1024 || L.d == 2048);
+}
+
+}  // namespace blockffn

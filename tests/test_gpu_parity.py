@@ -437,3 +437,52 @@ def test_work_list_of_many_chunks():
                               buf.n_active[lo:lo + n], n, w.k, y2[t0:t1], buf.workspace, cl[lo:lo + n].contiguous())
     torch.cuda.synchronize()
     assert torch.equal(y2, buf.y)
+
+
+@pytest.mark.parametrize("d,E,d_e,k,C,gated", [
+    (2048, 64, 256, 8, 1, True),     # one chunk of the layer-stack shape: 8 slot splits of the down projection
+    (2048, 64, 128, 5, 3, False),    # Eq. 2 experts, ragged chunk
+    (1024, 32, 64, 1, 9, True),      # single tokens, four row tiles per wave in the down items
+    (2048, 128, 128, 8, 2, True),    # two mask words
+    (1024, 16, 256, 7, 30, False),   # more chunks than slot splits are needed for: splits = 1
+])
+def test_few_chunks(d, E, d_e, k, C, gated):
+    """A handful of short chunks (one workgroup per (slot, 16-row tile) in the up projection, narrow
+    column blocks and slot splits in the down projection).  The combined entry point and the two
+    halves enqueued separately must agree bit for bit, for the sparse and the dense path, with an
+    empty union among the chunks, and on a second run over a dirty workspace."""
+    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.3, seed=d_e + k + C)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    if C > 1:
+        x[k:2 * k] = 0.0        # chunk 1: no expert active (the bias is negative)
+    import oracle
+    ref = pu.run_oracle(layers, x, w.k, dense=False)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, dense=True)       # blockffn_sparse_ffn / blockffn_dense_ffn
+    pu.assert_integers_equal(gpu, ref)
+    pu.assert_scores_within_allowance(gpu["scores"], ref["scores"],
+                                      pu.score_error_allowed(layers, x, w.k, None, ref["scores"], use_gain=False))
+    # the FFN on the scores it was given (a token whose only active expert is barely active has an
+    # ill-conditioned score, see score_error_allowed)
+    OL = pu.oracle_layer(layers, 0, use_gain=False)
+    e_y = pu.row_rel_err(gpu["y"], pu.oracle_ffn_on_gpu_routing(layers, x, w.k, None, gpu, use_gain=False)).max(initial=0.0)
+    e_d = pu.row_rel_err(gpu["y_dense"], oracle.dense_ffn(OL, x.numpy(), gpu["scores"])).max(initial=0.0)
+    print("y %.3g  y_dense %.3g" % (e_y, e_d), flush=True)
+    assert e_y <= pu.TIGHT["bf16"] and e_d <= pu.TIGHT["bf16"]
+    if C > 1:
+        assert gpu["n_active"][1] == 0 and np.all(gpu["y"][k:2 * k] == 0)
+    L, buf, xd = gpu["_layer"], gpu["_buf"], x.cuda()
+    y1 = buf.y.clone()
+    for dense in (False, True):
+        idx, n_act, mask = (None, None, None) if dense else (buf.active_idx, buf.n_active, buf.token_mask)
+        y2 = torch.full_like(buf.y, float("nan"))
+        B.blockffn_sparse_ffn_up(L, xd, buf.scores, mask, idx, n_act, C, k, buf.workspace)
+        B.blockffn_sparse_ffn_down(L, idx, n_act, C, k, y2, buf.workspace)
+        torch.cuda.synchronize()
+        want = torch.tensor(gpu["y_dense"]).cuda() if dense else y1
+        assert torch.equal(y2, want), "dense" if dense else "sparse"
+    buf.workspace.fill_(0xff)
+    y3 = torch.full_like(buf.y, float("nan"))
+    B.blockffn_sparse_ffn(L, xd, buf.scores, buf.token_mask, buf.active_idx, buf.n_active, C, k, y3, buf.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(y3, y1)
