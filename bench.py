@@ -204,6 +204,41 @@ def cpu_baseline(w, layers, x, chunk_layer, n_sample, expert_bytes):
             "us_per_chunk": dt / n * 1e6}
 
 
+def library_dense(w, layers, x, scores, y_ours, R, steps):
+    """An independently written dense comparator: the dense FFN of equal parameter count (every
+    expert, Eq. 1) through the vendor's GEMM library (torch.bmm on bf16, fp32 accumulation), the way
+    a dense model would run it.  One batched call takes one chunk of every weight set (batch index =
+    weight set), so every weight is read once per chunk, cold, exactly as in the library's own
+    dense path; W_down is laid out [d][E * d_e] for it beforehand, outside the timed region.
+    Activations are bf16 here (x rounded once): a timing comparator, checked loosely against
+    blockffn_dense_ffn."""
+    import torch
+    import torch.nn.functional as F
+
+    C, k, d, E, d_e = w.n_chunks, w.k, w.d, w.E, w.d_e
+    N, m = E * d_e, C // R
+    xb = x.view(m, R, k, d).to(torch.bfloat16)
+    sc = scores.view(m, R, k, E).to(torch.bfloat16)
+    wu_t = layers["w_up"].view(R, N, d).transpose(1, 2)
+    wg_t = layers["w_gate"].view(R, N, d).transpose(1, 2) if w.gated else None
+    wd_t = layers["w_down"].permute(0, 2, 1, 3).reshape(R, d, N).contiguous().transpose(1, 2)   # [R][N][d] view
+    y = torch.empty((m, R, k, d), dtype=torch.bfloat16, device=x.device)
+
+    def step():
+        for j in range(m):
+            u = torch.bmm(xb[j], wu_t)
+            h = F.silu(torch.bmm(xb[j], wg_t)) * u if w.gated else F.silu(u)
+            h = (h.view(R, k, E, d_e) * sc[j].unsqueeze(-1)).view(R, k, N)
+            torch.bmm(h, wd_t, out=y[j])
+
+    us = timed_us(step, reps=steps)
+    # chunk c = j * R + r is row (j, r): same order as x
+    ours = y_ours.view(m, R, k, d)
+    diff = (y.float() - ours).pow(2).sum().sqrt() / ours.pow(2).sum().sqrt()
+    return {"ms": us / 1e3, "rel_l2_diff_to_dense_ffn": float(diff),
+            "what": "torch.bmm (vendor GEMM library), bf16 activations, one chunk per weight set per batched call"}
+
+
 def default_replicas(w):
     """Weight sets the chunks rotate through when --replicas is not given: at least 128, and at
     least 6 GiB of weights.  The persistent workgroups of the up kernel hold about 50 chunks in
@@ -325,6 +360,9 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
         e1.record()
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1) / dense_steps
+    library = None
+    if dense_steps > 0 and not sequential and w.wdtype == "bf16" and C % R == 0 and w.k <= 32:
+        library = library_dense(w, layers, x, buf.scores, y_dense, R, dense_steps)
     ffn_ms = (stage_us["up"] + stage_us["down"]) / 1e3
     if sequential:   # whole steps on both sides (router included): there is no per-kernel split here
         ffn_ms = ms_per_step
@@ -365,6 +403,9 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
         "dense_ffn_ms": dense_ms, "sparse_ffn_ms": ffn_ms,
         "dense_ffn_GBps": None if dense_ms is None else dense_bytes / (dense_ms * 1e-3) / 1e9,
         "speedup_vs_dense": None if dense_ms is None else dense_ms / ffn_ms,
+        "dense_library_gemm": None if library is None else dict(
+            library, speedup_of_sparse=library["ms"] / ffn_ms,
+            GBps=dense_bytes / (library["ms"] * 1e-3) / 1e9),
         "E_over_mean_active": w.E * C / max(n_active_sum, 1),
         "paper_context": "up to 3.67x end-to-end over dense decoding on Jetson Orin NX (another machine, Table 6)",
         "roofline": {"kernel": "up projection over the union (W_up%s rows of the active experts)"
@@ -417,11 +458,15 @@ def run_all(args):
                     rec = run(args, name, gated=gated, warm=warm, **kw)
                     f.write(json.dumps(rec) + "\n")
                     f.flush()
-                    print("%-18s %-6s %-4s %8.1f GB/s  %5.1f %% of 8 TB/s  %8.2f us/chunk  speedup %s (bound %.2f)"
+                    lib = rec.get("dense_library_gemm")
+                    print("%-18s %-6s %-4s %8.1f GB/s  %5.1f %% of 8 TB/s  %8.2f us/chunk  speedup %s (bound %.2f)  "
+                          "vs library GEMM dense %s"
                           % (name, rec["config"]["expert_kind"], rec["config"]["mode"], rec["value"], rec["pct_hbm_peak"],
                              rec["us_per_chunk"],
                              "-" if rec["speedup_vs_dense"] is None else "%.2f" % rec["speedup_vs_dense"],
-                             rec["E_over_mean_active"]), file=sys.stderr, flush=True)
+                             rec["E_over_mean_active"],
+                             "-" if not lib else "%.2f (%.0f GB/s)" % (lib["speedup_of_sparse"], lib["GBps"])),
+                          file=sys.stderr, flush=True)
                     torch.cuda.empty_cache()
 
 

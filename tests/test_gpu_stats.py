@@ -131,3 +131,30 @@ def test_statistics_of_the_router_masks_at_full_size():
     np.testing.assert_array_equal(gg[0], rr[0])
     np.testing.assert_array_equal(gg[1], rr[1])
     assert gg[2] == pytest.approx(rr[2], rel=1e-13)
+
+
+@pytest.mark.parametrize("name,n_chunks", [("spec_k8", 256), ("paper_tree_k32", 96)])
+def test_offload_simulation_on_union_lists_from_the_gpu(name, n_chunks):
+    """The expert-cache simulation driven by what the hot path produced: router and chunk union run
+    on the GPU (one layer, chunks in order), the lists are copied back, and the library's LRU
+    simulation (host code) must equal the oracle's on them for every capacity, chunk by chunk."""
+    from oracle import offload_sim as osim
+    w = wl.WORKLOADS[name].replace(n_chunks=n_chunks)
+    layers = wl.make_layers(w, 1, device="cuda")
+    x = wl.make_tokens(w, layers, device="cuda")
+    L = B.Layer.from_dict(layers, gain=False)
+    buf = B.Buffers(L, w.n_chunks, w.k)
+    B.blockffn_router(L, x, w.n_chunks, w.k, buf.scores, buf.token_mask)
+    B.blockffn_chunk_union(buf.token_mask, w.n_chunks, w.k, w.E, buf.union_mask, buf.active_idx, buf.n_active, buf.stats)
+    torch.cuda.synchronize()
+    idx, n_act = buf.active_idx.cpu().contiguous(), buf.n_active.cpu().contiguous()
+    assert int(n_act.min()) >= 0 and int(n_act.max()) <= w.E and int(n_act.sum()) > 0
+    for capacity in (0, 1, w.E // 8, w.E // 4, w.E // 2, w.E, w.E + 1):
+        loads = torch.full((w.n_chunks,), -1, dtype=torch.int64)
+        totals = torch.full((3,), -1, dtype=torch.int64)
+        B.blockffn_offload_sim(idx, n_act, w.E, capacity, loads, totals)
+        ref_loads, ref_totals = osim.lru_offload(idx.numpy(), n_act.numpy(), capacity)
+        np.testing.assert_array_equal(loads.numpy(), ref_loads)
+        np.testing.assert_array_equal(totals.numpy(), ref_totals)
+    # a cache that holds every expert loads each expert of the stream once
+    assert int(totals[1]) == len(set(idx.numpy()[idx.numpy() >= 0].tolist()))
