@@ -60,6 +60,9 @@ def parse():
     p.add_argument("--sequential", action="store_true",
                    help="enqueue the chunks one after the other (one chunk per launch), as a layer stack does: "
                         "with --workload stack_decode_k8 --chunks 24 --replicas 24 a step is a 24-layer decode step")
+    p.add_argument("--graph", action="store_true",
+                   help="with --sequential: capture the step's launches once as a HIP graph (kernel nodes only) and "
+                        "replay it per step")
     p.add_argument("--dense-steps", type=int, default=3)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--extras", action="store_true",
@@ -251,7 +254,7 @@ def default_replicas(w):
 
 
 def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=None, dense_steps=None, warm=False,
-        with_cpu=False, with_extras=False):
+        with_cpu=False, with_extras=False, graph=False):
     """One workload: generates it, times `steps` steps, returns the record."""
     import numpy as np
     import torch
@@ -295,10 +298,23 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
             B.blockffn_sparse_ffn(Lc, x[t0_:t1_], buf.scores[t0_:t1_], buf.token_mask[t0_:t1_], buf.active_idx[c:c + 1],
                                   buf.n_active[c:c + 1], 1, k, buf.y[t0_:t1_], buf.workspace)
 
+    use_graph, graph = graph, None
+    if sequential and use_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_sequential()                      # everything the calls set up lazily happens before capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step_sequential()
+
     def step(ev=None):
         if sequential:
             if ev: ev[0].record()
-            step_sequential()
+            if graph is not None: graph.replay()
+            else: step_sequential()
             if ev:
                 for e in ev[1:]: e.record()
             return
@@ -353,6 +369,11 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
     if dense_steps > 0:
         dense_step()
         torch.cuda.synchronize()
+        if graph is not None:      # the dense stack replayed as a graph as well
+            dense_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(dense_graph):
+                dense_step()
+            dense_step = dense_graph.replay
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(dense_steps):
@@ -390,11 +411,13 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
         "config": {"workload": "%s: d=%d E=%d d_e=%d %s experts, k=%d x %d chunks, sigma=%.2f, %d weight sets (%.2f GB)%s%s"
                                % (w.name, w.d, w.E, w.d_e, "gated" if w.gated else "swish", k, C, w.sigma, R,
                                   R * w.E * w.expert_bytes / 1e9,
-                                  ", chunks enqueued one after the other" if sequential else "",
+                                  (", chunks enqueued one after the other" + (" (replayed as a HIP graph)" if graph is not None else ""))
+                                  if sequential else "",
                                   ", WARM: one weight set for every chunk, served largely by the caches (not an HBM figure)"
                                   if warm and C > 1 else ""),
                    "name": w.name, "expert_kind": "gated" if w.gated else "swish",
-                   "replicas": R, "sequential": sequential, "mode": "warm" if warm and C > 1 else "cold"},
+                   "replicas": R, "sequential": sequential, "graph": graph is not None,
+                   "mode": "warm" if warm and C > 1 else "cold"},
         "us_per_chunk": ms_per_step * 1e3 / C,
         "tokens_per_s": w.n_tok / (ms_per_step * 1e-3),
         "pct_hbm_peak": 100.0 * active_bytes / (ms_per_step * 1e-3) / HBM_PEAK,
@@ -437,6 +460,7 @@ ALL_RUNS = [
     ("spec_k8", dict()),
     ("tree_k32", dict(steps=5, dense_steps=2)),
     ("stack_decode_k8", dict(chunks=24, replicas=24, sequential=True)),
+    ("stack_decode_k8", dict(chunks=24, replicas=24, sequential=True, graph=True)),
     ("stack_prefill_512", dict(chunks=8, replicas=8, steps=10, dense_steps=2)),
     ("paper_ar_k1", dict()),
     ("paper_tree_k32", dict(steps=10, dense_steps=2)),
@@ -495,7 +519,7 @@ def main():
         run_all(args)
     out = run(args, args.workload, gated=False if args.swish else None, replicas=args.replicas,
               sequential=args.sequential, chunks=args.chunks, with_cpu=not args.no_cpu_baseline,
-              with_extras=args.extras)
+              with_extras=args.extras, graph=args.graph)
     print(json.dumps(out))
 
 

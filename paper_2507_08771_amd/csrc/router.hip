@@ -8,7 +8,7 @@
 // bf16 pieces that add up to the fp32 value exactly, and the matrix cores do the contraction.
 // router_kernel (fp32 weights, and launches of tens of tiles, where blockIdx.y spreads the expert
 // groups over workgroups; a handful of tiles take router_expert_kernel, one workgroup per
-// expert): vector ALUs.  Each lane keeps its 8 columns of the 8 tokens in
+// expert and share of the tile's tokens): vector ALUs.  Each lane keeps its 8 columns of the 8 tokens in
 // registers (64 VGPRs) and walks over the experts: one 128-bit load of a W_router row segment
 // feeds 64 fp32 FMAs; partial sums of 8 experts x 8 tokens are reduced across the wave with a
 // 63-step reduce-scatter (lane q ends with entry q).
@@ -180,32 +180,37 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
 }
 
 // A handful of token tiles (one chunk walking through a layer stack): one workgroup per (tile,
-// expert), so that E workgroups pull the router matrix instead of E / 8.  Each thread takes 8
-// columns of the expert's row and of the tile's tokens; the partial sums meet by wave reduction
-// and a four-entry LDS step.  Writes A^0 (+ bias) into `scores`; router_finish_kernel normalises.
-template <typename WT>
+// expert, share of the tile's tokens), so that E or more workgroups pull the router matrix instead
+// of E / 8.  Each thread takes 8 columns of the expert's row and of its tokens; the partial sums
+// meet by wave reduction and a four-entry LDS step.  What a workgroup has to pull is mostly the
+// tile's x (64 KiB for 8 tokens at d = 2048, against 4 KiB of W_router), and a CU takes in about
+// 20 GB/s: with the tile's tokens dealt over gridDim.z workgroups each pulls its share only (a
+// pre-activation belongs to one token and one expert, so nothing crosses workgroups).  Writes A^0
+// (+ bias) into `scores`; router_finish_kernel normalises.  TPW: tokens per workgroup.
+template <typename WT, int TPW>
 __global__ __launch_bounds__(kThreads) void router_expert_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                                  const float *__restrict__ x, int k,
                                                                  int tiles_per_chunk, float *__restrict__ scores) {
-  __shared__ float part[4][kTok];
+  __shared__ float part[4][TPW];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t c = blockIdx.x / tiles_per_chunk;
-  const int t0 = (int)(blockIdx.x % tiles_per_chunk) * kTok;
-  const int nt = min(kTok, k - t0);
+  const int t0 = (int)(blockIdx.x % tiles_per_chunk) * kTok + (int)blockIdx.z * TPW;
+  const int nt = min(TPW, k - t0);
+  if (nt <= 0) return;   // uniform over the workgroup
   const int64_t tok0 = c * (int64_t)k + t0;
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int d = L.d, E = L.E, e = blockIdx.y;
   const size_t w_row = ((size_t)layer * E + e) * d;
-  float acc[kTok];
+  float acc[TPW];
 #pragma unroll
-  for (int t = 0; t < kTok; ++t) acc[t] = 0.0f;
+  for (int t = 0; t < TPW; ++t) acc[t] = 0.0f;
   for (int cb = 0; cb < d; cb += kColsPerBlock) {
     const int col = cb + tid * 8;
     if (col < d) {
       float w[8];
       load8<WT>(L.w_router, w_row + col, w);
 #pragma unroll
-      for (int t = 0; t < kTok; ++t) {
+      for (int t = 0; t < TPW; ++t) {
         if (t < nt) {
           const float4 *p = reinterpret_cast<const float4 *>(x + (tok0 + t) * d + col);
           const float4 a = p[0], b = p[1];
@@ -218,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void router_expert_kernel(LayerView L, co
     }
   }
 #pragma unroll
-  for (int t = 0; t < kTok; ++t) {
+  for (int t = 0; t < TPW; ++t) {
     const float v = wave_sum(acc[t]);
     if (lane == 0) part[wave][t] = v;
   }
@@ -404,11 +409,16 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
     // few token tiles: spread the experts (or, with many tiles and experts, groups of 8 of them)
     // over workgroups, then normalise
     if (blocks * L.E <= 4096) {
-      dim3 grid((unsigned)blocks, (unsigned)L.E);
-      if (wdtype == BLOCKFFN_BF16)
-        hipLaunchKernelGGL((router_expert_kernel<bf16_t>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores);
-      else
-        hipLaunchKernelGGL((router_expert_kernel<float>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores);
+      // tokens of a tile per workgroup: as few as keep the launch within about two workgroups per CU
+      const int64_t wgs = blocks * L.E;
+      const int tpw = wgs * 4 <= 2 * num_cus() ? 2 : (wgs * 2 <= 2 * num_cus() ? 4 : 8);
+      dim3 grid((unsigned)blocks, (unsigned)L.E, (unsigned)(kTok / tpw));
+#define BLOCKFFN_ROUTER_EXPERT(WT)                                                                                  \
+  if (tpw == 2) hipLaunchKernelGGL((router_expert_kernel<WT, 2>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores); \
+  else if (tpw == 4) hipLaunchKernelGGL((router_expert_kernel<WT, 4>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores); \
+  else hipLaunchKernelGGL((router_expert_kernel<WT, 8>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores)
+      if (wdtype == BLOCKFFN_BF16) { BLOCKFFN_ROUTER_EXPERT(bf16_t); } else { BLOCKFFN_ROUTER_EXPERT(float); }
+#undef BLOCKFFN_ROUTER_EXPERT
     } else {
       dim3 grid((unsigned)blocks, (unsigned)n_groups);
       if (wdtype == BLOCKFFN_BF16)

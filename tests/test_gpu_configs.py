@@ -146,3 +146,40 @@ def test_stack_decode_24_layers_chained():
         x = (z * (rms0 / z.pow(2).mean(dim=1, keepdim=True).sqrt())).contiguous()
     print("pre-activations inside the guard band over 24 layers:", unguarded)
     assert unguarded < 8
+
+
+def test_layer_stack_replayed_as_a_graph():
+    """The launches of a few layers (router, union, FFN per layer, one k = 8 chunk) captured once as
+    a graph of kernel nodes and replayed: every replay, with eager work and synchronisations of
+    the program's own between them, must give the bits of the eager run."""
+    w = wl.WORKLOADS["stack_decode_k8"]
+    NL = 4
+    layers = wl.make_layers(w, NL, device="cuda")
+    L = B.Layer.from_dict(layers, gain=False)
+    xs = [wl.make_tokens(w, {n: (None if t is None else t[l:l + 1]) for n, t in layers.items()}, device="cuda", seed=50 + l)
+          for l in range(NL)]
+    bufs = [B.Buffers(L, 1, w.k) for _ in range(NL)]
+    cls = [torch.tensor([l], dtype=torch.int32, device="cuda") for l in range(NL)]
+
+    def run_layers():
+        for l in range(NL):
+            B.forward_chunks(L, xs[l], bufs[l], cls[l])
+
+    run_layers()
+    torch.cuda.synchronize()
+    want = [(b.y.clone(), b.scores.clone(), b.active_idx.clone(), b.stats.clone()) for b in bufs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_layers()
+    for rep in range(3):
+        for b in bufs:
+            b.y.fill_(float("nan"))
+            b.workspace.fill_(rep)            # eager work between the replays, on the buffers the graph uses
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l, b in enumerate(bufs):
+            assert torch.equal(b.y, want[l][0]), (rep, l)
+            assert torch.equal(b.scores, want[l][1]) and torch.equal(b.active_idx, want[l][2])
+        # the counts are added to on every run (the capture itself launches nothing)
+        assert torch.equal(bufs[0].stats, want[0][3] * (rep + 2))
