@@ -60,6 +60,9 @@ def parse():
     p.add_argument("--sequential", action="store_true",
                    help="enqueue the chunks one after the other (one chunk per launch), as a layer stack does: "
                         "with --workload stack_decode_k8 --chunks 24 --replicas 24 a step is a 24-layer decode step")
+    p.add_argument("--fused", action="store_true",
+                   help="with --sequential: one blockffn_forward_chunks call per layer instead of the three calls "
+                        "(three launches per layer instead of six)")
     p.add_argument("--graph", action="store_true",
                    help="with --sequential: capture the step's launches once as a HIP graph (kernel nodes only) and "
                         "replay it per step")
@@ -254,7 +257,7 @@ def default_replicas(w):
 
 
 def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=None, dense_steps=None, warm=False,
-        with_cpu=False, with_extras=False, graph=False):
+        with_cpu=False, with_extras=False, graph=False, fused=False):
     """One workload: generates it, times `steps` steps, returns the record."""
     import numpy as np
     import torch
@@ -292,6 +295,11 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
         for c in range(C):
             t0_, t1_ = c * k, (c + 1) * k
             Lc = views[layer_of[c]]
+            if fused:
+                B.blockffn_forward_chunks(Lc, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_],
+                                          buf.union_mask[c:c + 1], buf.active_idx[c:c + 1], buf.n_active[c:c + 1],
+                                          buf.stats, buf.y[t0_:t1_], buf.workspace)
+                continue
             B.blockffn_router(Lc, x[t0_:t1_], 1, k, buf.scores[t0_:t1_], buf.token_mask[t0_:t1_])
             B.blockffn_chunk_union(buf.token_mask[t0_:t1_], 1, k, L.E, buf.union_mask[c:c + 1], buf.active_idx[c:c + 1],
                                    buf.n_active[c:c + 1], buf.stats)
@@ -411,12 +419,13 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
         "config": {"workload": "%s: d=%d E=%d d_e=%d %s experts, k=%d x %d chunks, sigma=%.2f, %d weight sets (%.2f GB)%s%s"
                                % (w.name, w.d, w.E, w.d_e, "gated" if w.gated else "swish", k, C, w.sigma, R,
                                   R * w.E * w.expert_bytes / 1e9,
-                                  (", chunks enqueued one after the other" + (" (replayed as a HIP graph)" if graph is not None else ""))
+                                  (", chunks enqueued one after the other" + (", one fused call per layer" if fused else "")
+                                   + (" (replayed as a HIP graph)" if graph is not None else ""))
                                   if sequential else "",
                                   ", WARM: one weight set for every chunk, served largely by the caches (not an HBM figure)"
                                   if warm and C > 1 else ""),
                    "name": w.name, "expert_kind": "gated" if w.gated else "swish",
-                   "replicas": R, "sequential": sequential, "graph": graph is not None,
+                   "replicas": R, "sequential": sequential, "graph": graph is not None, "fused": bool(fused and sequential),
                    "mode": "warm" if warm and C > 1 else "cold"},
         "us_per_chunk": ms_per_step * 1e3 / C,
         "tokens_per_s": w.n_tok / (ms_per_step * 1e-3),
@@ -461,6 +470,7 @@ ALL_RUNS = [
     ("tree_k32", dict(steps=5, dense_steps=2)),
     ("stack_decode_k8", dict(chunks=24, replicas=24, sequential=True)),
     ("stack_decode_k8", dict(chunks=24, replicas=24, sequential=True, graph=True)),
+    ("stack_decode_k8", dict(chunks=24, replicas=24, sequential=True, graph=True, fused=True)),
     ("stack_prefill_512", dict(chunks=8, replicas=8, steps=10, dense_steps=2)),
     ("paper_ar_k1", dict()),
     ("paper_tree_k32", dict(steps=10, dense_steps=2)),
@@ -519,7 +529,7 @@ def main():
         run_all(args)
     out = run(args, args.workload, gated=False if args.swish else None, replicas=args.replicas,
               sequential=args.sequential, chunks=args.chunks, with_cpu=not args.no_cpu_baseline,
-              with_extras=args.extras, graph=args.graph)
+              with_extras=args.extras, graph=args.graph, fused=args.fused)
     print(json.dumps(out))
 
 

@@ -118,6 +118,19 @@ int blockffn_dense_ffn(const blockffn_layer *layer, const int32_t *chunk_layer, 
                        const float *scores, int64_t n_chunks, int32_t k, float *y,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* Router, chunk union and chunk-sparse FFN in one call (Eq. 3 and Sec. 3.3, the whole path of a
+ * layer): exactly what blockffn_router, blockffn_chunk_union and blockffn_sparse_ffn compute when
+ * called in that order on one stream with these arguments - every output (scores, token_mask,
+ * union_mask, active_idx, n_active, stats added to, y) has the same bits.  For a handful of chunks
+ * of up to 8 tokens (one chunk walking through a model's layers, where the time goes to launches
+ * and their round trips to memory) the layer is three launches instead of six; every other shape
+ * runs the three stages as they are.  Arguments, workspace and error codes as for those calls. */
+int blockffn_forward_chunks(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
+                            int64_t n_chunks, int32_t k, float *scores, uint64_t *token_mask,
+                            uint64_t *union_mask, int32_t *active_idx, int32_t *n_active,
+                            int64_t *stats, float *y, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
 /* blockffn_sparse_ffn for callers that cannot allocate device memory and so have no workspace to
  * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, kernels and results as blockffn_sparse_ffn; the workspace is a static device array of

@@ -27,7 +27,7 @@ EXPORTS = ("blockffn_router", "blockffn_chunk_union", "blockffn_sparse_ffn", "bl
            "blockffn_version", "blockffn_cls_sweep", "blockffn_reuse_ratio", "blockffn_router_preact",
            "blockffn_router_losses", "blockffn_losses_workspace_bytes", "blockffn_offload_sim",
            "blockffn_sparse_ffn_static", "blockffn_stream_read",
-           "blockffn_force_generic")
+           "blockffn_force_generic", "blockffn_forward_chunks")
 
 
 class BlockffnLayer(ctypes.Structure):
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.blockffn_offload_sim.restype = ctypes.c_int
         L.blockffn_cls_sweep.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
         L.blockffn_reuse_ratio.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
+        L.blockffn_forward_chunks.argtypes = [lp, vp, vp, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.blockffn_forward_chunks.restype = ctypes.c_int
         L.blockffn_force_generic.argtypes = [ctypes.c_int]
         L.blockffn_force_generic.restype = ctypes.c_int
         L.blockffn_stream_read.argtypes = [vp, sz, i32, vp, vp]
@@ -265,6 +267,16 @@ class Buffers:
         self.y = torch.empty((T, layer.d), dtype=torch.float32, device=dev)
         nbytes = max(blockffn_workspace_bytes(layer, n_chunks, k), 256)
         self.workspace = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+
+
+def blockffn_forward_chunks(layer: Layer, x: torch.Tensor, n_chunks: int, k: int, scores, token_mask, union_mask,
+                            active_idx, n_active, stats, y, workspace: torch.Tensor, chunk_layer=None, stream=None):
+    """Router, chunk union and chunk-sparse FFN as ONE call of the library (three launches for a
+    handful of short chunks, the three stages as they are otherwise)."""
+    _check(lib().blockffn_forward_chunks(layer.ref(), _p(chunk_layer), _p(x), n_chunks, k, _p(scores), _p(token_mask),
+                                         _p(union_mask), _p(active_idx), _p(n_active), _p(stats), _p(y), _p(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "blockffn_forward_chunks")
 
 
 def forward_chunks(layer: Layer, x: torch.Tensor, buf: Buffers, chunk_layer=None, stream=None):

@@ -268,6 +268,44 @@ int blockffn_sparse_ffn(const blockffn_layer *layer, const int32_t *chunk_layer,
                     k, y, workspace, workspace_bytes, stream);
 }
 
+int blockffn_forward_chunks(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x, int64_t n_chunks,
+                            int32_t k, float *scores, uint64_t *token_mask, uint64_t *union_mask, int32_t *active_idx,
+                            int32_t *n_active, int64_t *stats, float *y, void *workspace, size_t workspace_bytes,
+                            void *stream) {
+  LayerView v;
+  int rc = check_layer(layer, v);
+  if (rc != BLOCKFFN_OK) return rc;
+  rc = check_chunks(n_chunks, k);
+  if (rc != BLOCKFFN_OK) return rc;
+  const bool fused = n_chunks > 0 && !force_generic() && few_routed_supported(v, layer->wdtype, n_chunks, k);
+  if (!fused) {   // the three stages one after the other; each checks its own arguments
+    rc = blockffn_router(layer, chunk_layer, x, n_chunks, k, scores, token_mask, stream);
+    if (rc != BLOCKFFN_OK) return rc;
+    rc = blockffn_chunk_union(token_mask, n_chunks, k, layer->n_experts, union_mask, active_idx, n_active, stats, stream);
+    if (rc != BLOCKFFN_OK) return rc;
+    return blockffn_sparse_ffn(layer, chunk_layer, x, scores, token_mask, active_idx, n_active, n_chunks, k, y, workspace,
+                               workspace_bytes, stream);
+  }
+  if (x == nullptr || scores == nullptr || token_mask == nullptr || union_mask == nullptr || active_idx == nullptr ||
+      n_active == nullptr || y == nullptr)
+    return BLOCKFFN_ERR_INVALID;
+  if (!aligned(x, 16) || !aligned(scores, 4) || !aligned(token_mask, 8) || !aligned(union_mask, 8) ||
+      !aligned(active_idx, 4) || !aligned(n_active, 4) || !aligned(stats, 8) || !aligned(y, 16) ||
+      !aligned(chunk_layer, 4))
+    return BLOCKFFN_ERR_INVALID;
+  const bool gated = layer->expert_kind == BLOCKFFN_EXPERT_GATED;
+  if (workspace == nullptr || !aligned(workspace, 256)) return BLOCKFFN_ERR_INVALID;
+  if (workspace_bytes < workspace_need(v, layer->wdtype, gated, n_chunks, k)) return BLOCKFFN_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t err = launch_router_preact_few(v, layer->wdtype, chunk_layer, x, n_chunks, k,
+                                            few_preact_buffer(v, n_chunks, k, workspace), s);
+  if (err == hipSuccess)
+    err = launch_up_few_routed(v, gated, chunk_layer, x, n_chunks, k, workspace, scores, token_mask, union_mask,
+                               active_idx, n_active, stats, s);
+  if (err == hipSuccess) err = launch_down_stream(v, chunk_layer, active_idx, n_active, n_chunks, k, workspace, y, s);
+  return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
+}
+
 int blockffn_sparse_ffn_static(const blockffn_layer *layer, const int32_t *chunk_layer, const float *x,
                                const float *scores, const uint64_t *token_mask, const int32_t *active_idx,
                                const int32_t *n_active, int64_t n_chunks, int32_t k, float *y, void *stream) {
@@ -330,6 +368,6 @@ const char *blockffn_strerror(int code) {
   }
 }
 
-int blockffn_version(void) { return 101; }
+int blockffn_version(void) { return 102; }
 
 }  // extern "C"

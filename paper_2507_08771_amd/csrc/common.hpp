@@ -198,6 +198,20 @@ hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, co
                               const int32_t *n_active, int64_t n_chunks, int k, const void *ws, float *y,
                               hipStream_t s);
 
+// A few chunks of up to 8 tokens as three launches instead of six (blockffn_forward_chunks): the
+// router's per-expert kernel writes A^0 into the workspace, the up projection redoes the routing
+// from it in every workgroup and writes the router's and the union's outputs, the down projection
+// follows as usual.
+bool router_few(const LayerView &L, int64_t n_chunks, int k);
+hipError_t launch_router_preact_few(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
+                                    int64_t n_chunks, int k, float *preact, hipStream_t s);
+float *few_preact_buffer(const LayerView &L, int64_t n_chunks, int k, void *ws);
+hipError_t launch_up_few_routed(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *x,
+                                int64_t n_chunks, int k, void *ws, float *scores, uint64_t *token_mask,
+                                uint64_t *union_mask, int32_t *active_idx, int32_t *n_active, int64_t *stats,
+                                hipStream_t s);
+bool few_routed_supported(const LayerView &L, int wdtype, int64_t n_chunks, int k);
+
 // Flat list of the active experts in groups of `group` consecutive slots: items[i] = chunk * E +
 // first slot of the group, full groups first, then the chunks' shorter last groups, longest first;
 // total[0] = its length (n_active == nullptr: every chunk has E slots), total[16 .. 19] = 0 (a

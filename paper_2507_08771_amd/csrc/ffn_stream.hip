@@ -716,11 +716,26 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 // 16-row tile of one item; its four waves split the contraction, each keeps its quarter of the
 // chunk's split x in registers (no LDS fill, no barrier before the stream starts) and the four
 // partial tiles meet in LDS once at the end.  k <= 8 only; FW = d / 128 fragments per wave.
-template <int NM, int FW>
+// ROUTE: the launch also stands in for the router's normalising pass and for the chunk union.  It
+// is given the pre-activations A^0 (+ bias) of the chunk's tokens instead of scores, masks and
+// lists; every workgroup redoes the chunk's routing from them (8 tokens x N_e values: masks,
+// RMSNorm, union, the expert of its slot - the arithmetic of router_finish_kernel and
+// chunk_union_kernel, so the same bits) and the workgroup of slot 0, tile 0 writes the outputs the
+// two kernels would have written.  One round trip to memory for 2 KiB in place of the two loads
+// of the list entry, and two launches fewer per layer.
+struct RouteOut {
+  const float *preact;            // A^0 [token][N_e]
+  float *scores;                  // what blockffn_router and blockffn_chunk_union write
+  uint64_t *token_mask, *union_mask;
+  int32_t *active_idx, *n_active;
+  unsigned long long *stats;      // or nullptr
+};
+
+template <int NM, int FW, bool ROUTE>
 __global__ __launch_bounds__(kThreads) void up_split_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ n_active, int k, uint16_t *__restrict__ midB) {
+    const int32_t *__restrict__ n_active, int k, uint16_t *__restrict__ midB, RouteOut ro) {
   __shared__ float red[4][NM][4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4, n = lane & 15;
@@ -731,22 +746,125 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   const int code = blockIdx.x / tiles, rt = blockIdx.x % tiles;
   const int64_t c = code / E;
   const int s = code - (int)c * E;
+  const int tok = n & 7, half = n >> 3;
+  // score and mask word of this lane's token, for the epilogue (wave 0)
+  float f = 0.0f;
+  uint64_t mword = ~0ull;
   int e = s;
-  if (active_idx) {
-    e = active_idx[c * E + s];
-    if (s >= n_active[c]) return;
+  if constexpr (ROUTE) {
+    __shared__ uint64_t tmask_s[8][kMaxMaskWords];
+    __shared__ float rms_s[8];
+    const bool writer = s == 0 && rt == 0;
+    const int W = L.W;
+    const int layer_r = clamp_layer(chunk_layer, c, L.n_layers);
+    for (int t = wave; t < k; t += 4) {   // k <= 8: lanes run over the experts of one mask word at a time
+      const int64_t tk = c * k + t;
+      float a1[kMaxMaskWords];
+      float sumsq = 0.0f;
+#pragma unroll
+      for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+        a1[wd] = 0.0f;
+        if (wd < W) {
+          const int i = wd * 64 + lane;
+          const float a0 = i < E ? ro.preact[tk * E + i] : 0.0f;
+          const bool active = (i < E) && (a0 > 0.0f);
+          const uint64_t word = __ballot(active);
+          if (lane == 0) {
+            tmask_s[t][wd] = word;
+            if (writer) ro.token_mask[tk * W + wd] = word;
+          }
+          a1[wd] = active ? a0 : 0.0f;
+          sumsq = fmaf(a1[wd], a1[wd], sumsq);
+        }
+      }
+      const float ms = wave_sum(sumsq) / (float)E;
+      const float rms = sqrtf(ms + L.eps);
+      if (lane == 0) rms_s[t] = rms;
+      if (writer) {
+#pragma unroll
+        for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+          const int i = wd * 64 + lane;
+          if (wd < W && i < E) {
+            const float gn = L.g_rms ? L.g_rms[(size_t)layer_r * E + i] : 1.0f;
+            ro.scores[tk * E + i] = a1[wd] > 0.0f ? gn * a1[wd] / rms : 0.0f;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    uint64_t U[kMaxMaskWords];
+    int n_act = 0;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      U[wd] = 0;
+      if (wd < W) {
+        for (int t = 0; t < k; ++t) U[wd] |= tmask_s[t][wd];
+        n_act += __popcll(U[wd]);
+      }
+    }
+    if (writer && wave == 0) {   // Union(x), its ascending list, the counts (chunk_union_kernel's outputs)
+      int base = 0;
+#pragma unroll
+      for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+        if (wd < W) {
+          const uint64_t u = U[wd];
+          if (lane == 0) ro.union_mask[c * W + wd] = u;
+          const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(u >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)u, 0));
+          if ((u >> lane) & 1) ro.active_idx[c * E + base + below] = wd * 64 + lane;
+          base += __popcll(u);
+        }
+      }
+      for (int sl = base + lane; sl < E; sl += kWave) ro.active_idx[c * E + sl] = -1;
+      if (lane == 0) {
+        ro.n_active[c] = base;
+        if (ro.stats) {
+          long long tok_active = 0;
+          for (int t = 0; t < k; ++t)
+            for (int wd = 0; wd < W; ++wd) tok_active += __popcll(tmask_s[t][wd]);
+          atomicAdd(&ro.stats[0], (unsigned long long)((long long)k * E - tok_active));
+          atomicAdd(&ro.stats[1], (unsigned long long)(E - base));
+        }
+      }
+    }
+    if (s >= n_act) return;   // uniform over the workgroup
+    // the expert of slot s: the s-th set bit of the union
+    int left = s;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      if (wd < W && left >= 0) {
+        const int pc = __popcll(U[wd]);
+        if (left < pc) {
+          uint64_t u = U[wd];
+          for (int i = 0; i < left; ++i) u &= u - 1;
+          e = wd * 64 + __builtin_ctzll(u);
+          left = -1;
+        } else {
+          left -= pc;
+        }
+      }
+    }
+    if (wave == 0 && tok < k) {
+      const int64_t tk = c * k + tok;
+      mword = tmask_s[tok][e >> 6];
+      const float a0 = ro.preact[tk * E + e];
+      const float a1v = a0 > 0.0f ? a0 : 0.0f;
+      const float gn = L.g_rms ? L.g_rms[(size_t)layer_r * E + e] : 1.0f;
+      f = a1v > 0.0f ? gn * a1v / rms_s[tok] : 0.0f;
+    }
+  } else {
+    if (active_idx) {
+      e = active_idx[c * E + s];
+      if (s >= n_active[c]) return;
+    }
   }
   // a list entry outside [0, E) is an empty slot: zeros in mid (a valid expert is streamed in its place)
   const bool e_ok = (unsigned)e < (unsigned)E;
   e = min(max(e, 0), E - 1);
   const int layer = clamp_layer(chunk_layer, c, L.n_layers);
   const int kq0 = wave * (d / 4);
-  const int tok = n & 7, half = n >> 3;
-  // score and mask word of this lane's token, for the epilogue (wave 0): requested first, so that
-  // they are back before the weights instead of costing a round trip after them
-  float f = 0.0f;
-  uint64_t mword = ~0ull;
-  if (wave == 0 && tok < k) {
+  // score and mask word for the epilogue: requested first, so that they are back before the
+  // weights instead of costing a round trip after them
+  if (!ROUTE && wave == 0 && tok < k) {
     const int64_t t = c * k + tok;
     if (token_mask) mword = token_mask[t * L.W + (e >> 6)];
     f = scores[t * E + e];
@@ -1092,8 +1210,8 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
     // few chunks: one workgroup per (item, 16-row tile)
     const dim3 grid((unsigned)(max_items * (L.d_e / 16)));
 #define BLOCKFFN_SPLIT(nm, fw)                                                                             \
-  hipLaunchKernelGGL((up_split_kernel<nm, fw>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, scores, token_mask, \
-                     active_idx, n_active, k, w.midB)
+  hipLaunchKernelGGL((up_split_kernel<nm, fw, false>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, scores, token_mask, \
+                     active_idx, n_active, k, w.midB, RouteOut{})
     if (L.d == 2048) { if (gated) BLOCKFFN_SPLIT(2, 16); else BLOCKFFN_SPLIT(1, 16); }
     else { if (gated) BLOCKFFN_SPLIT(2, 8); else BLOCKFFN_SPLIT(1, 8); }
 #undef BLOCKFFN_SPLIT
@@ -1140,6 +1258,35 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   BLOCKFFN_CASE(4, 2, 1) BLOCKFFN_CASE(4, 2, 2) BLOCKFFN_CASE(4, 2, 4)
 #undef BLOCKFFN_CASE
   return hipErrorInvalidValue;
+}
+
+bool few_routed_supported(const LayerView &L, int wdtype, int64_t n_chunks, int k) {
+  return stream_supported(L, wdtype, k) && few_chunks(L, n_chunks, k) && router_few(L, n_chunks, k) &&
+         (size_t)n_chunks * k * L.E * sizeof(float) <= xs_bytes(L, n_chunks, k);
+}
+
+float *few_preact_buffer(const LayerView &L, int64_t n_chunks, int k, void *ws) {
+  return reinterpret_cast<float *>(carve_stream(L, n_chunks, k, ws).xS);   // the split x of larger launches lives here
+}
+
+hipError_t launch_up_few_routed(const LayerView &L, bool gated, const int32_t *chunk_layer, const float *x,
+                                int64_t n_chunks, int k, void *ws, float *scores, uint64_t *token_mask,
+                                uint64_t *union_mask, int32_t *active_idx, int32_t *n_active, int64_t *stats,
+                                hipStream_t s) {
+  if (n_chunks <= 0) return hipSuccess;
+  if (!few_chunks(L, n_chunks, k) || (size_t)n_chunks * k * L.E * sizeof(float) > xs_bytes(L, n_chunks, k))
+    return hipErrorInvalidValue;
+  StreamWs w = carve_stream(L, n_chunks, k, ws);
+  RouteOut ro{reinterpret_cast<const float *>(w.xS), scores, token_mask, union_mask, active_idx, n_active,
+              reinterpret_cast<unsigned long long *>(stats)};
+  const dim3 grid((unsigned)(n_chunks * L.E * (L.d_e / 16)));
+#define BLOCKFFN_SPLIT(nm, fw)                                                                                 \
+  hipLaunchKernelGGL((up_split_kernel<nm, fw, true>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, nullptr, nullptr, \
+                     nullptr, nullptr, k, w.midB, ro)
+  if (L.d == 2048) { if (gated) BLOCKFFN_SPLIT(2, 16); else BLOCKFFN_SPLIT(1, 16); }
+  else { if (gated) BLOCKFFN_SPLIT(2, 8); else BLOCKFFN_SPLIT(1, 8); }
+#undef BLOCKFFN_SPLIT
+  return hipGetLastError();
 }
 
 hipError_t launch_down_stream(const LayerView &L, const int32_t *chunk_layer, const int32_t *active_idx,

@@ -396,6 +396,31 @@ __global__ __launch_bounds__(kThreads) void router_finish_kernel(LayerView L, co
 
 }  // namespace
 
+// Whether launch_router takes its few-tile path with one workgroup per expert for this launch.
+bool router_few(const LayerView &L, int64_t n_chunks, int k) {
+  const int64_t blocks = n_chunks * ((k + kTok - 1) / kTok);
+  return blocks > 0 && blocks * 2 <= 256 && (L.E + 7) / 8 > 1 && blocks * L.E <= 4096;
+}
+
+// First half of that path alone: A^0 (+ bias) into `preact` [token][E], nothing else.
+hipError_t launch_router_preact_few(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
+                                    int64_t n_chunks, int k, float *preact, hipStream_t s) {
+  if (!router_few(L, n_chunks, k)) return hipErrorInvalidValue;
+  const int tiles = (k + kTok - 1) / kTok;
+  const int64_t blocks = n_chunks * tiles;
+  dim3 block(kThreads);
+  const int64_t wgs = blocks * L.E;
+  const int tpw = wgs * 4 <= 2 * num_cus() ? 2 : (wgs * 2 <= 2 * num_cus() ? 4 : 8);
+  dim3 grid((unsigned)blocks, (unsigned)L.E, (unsigned)(kTok / tpw));
+#define BLOCKFFN_ROUTER_EXPERT(WT)                                                                                  \
+  if (tpw == 2) hipLaunchKernelGGL((router_expert_kernel<WT, 2>), grid, block, 0, s, L, chunk_layer, x, k, tiles, preact); \
+  else if (tpw == 4) hipLaunchKernelGGL((router_expert_kernel<WT, 4>), grid, block, 0, s, L, chunk_layer, x, k, tiles, preact); \
+  else hipLaunchKernelGGL((router_expert_kernel<WT, 8>), grid, block, 0, s, L, chunk_layer, x, k, tiles, preact)
+  if (wdtype == BLOCKFFN_BF16) { BLOCKFFN_ROUTER_EXPERT(bf16_t); } else { BLOCKFFN_ROUTER_EXPERT(float); }
+#undef BLOCKFFN_ROUTER_EXPERT
+  return hipGetLastError();
+}
+
 hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_layer, const float *x,
                          int64_t n_chunks, int k, float *scores, uint64_t *token_mask, float *preact,
                          hipStream_t s) {
@@ -409,16 +434,8 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
     // few token tiles: spread the experts (or, with many tiles and experts, groups of 8 of them)
     // over workgroups, then normalise
     if (blocks * L.E <= 4096) {
-      // tokens of a tile per workgroup: as few as keep the launch within about two workgroups per CU
-      const int64_t wgs = blocks * L.E;
-      const int tpw = wgs * 4 <= 2 * num_cus() ? 2 : (wgs * 2 <= 2 * num_cus() ? 4 : 8);
-      dim3 grid((unsigned)blocks, (unsigned)L.E, (unsigned)(kTok / tpw));
-#define BLOCKFFN_ROUTER_EXPERT(WT)                                                                                  \
-  if (tpw == 2) hipLaunchKernelGGL((router_expert_kernel<WT, 2>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores); \
-  else if (tpw == 4) hipLaunchKernelGGL((router_expert_kernel<WT, 4>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores); \
-  else hipLaunchKernelGGL((router_expert_kernel<WT, 8>), grid, block, 0, s, L, chunk_layer, x, k, tiles, scores)
-      if (wdtype == BLOCKFFN_BF16) { BLOCKFFN_ROUTER_EXPERT(bf16_t); } else { BLOCKFFN_ROUTER_EXPERT(float); }
-#undef BLOCKFFN_ROUTER_EXPERT
+      const hipError_t e = launch_router_preact_few(L, wdtype, chunk_layer, x, n_chunks, k, scores, s);
+      if (e != hipSuccess) return e;
     } else {
       dim3 grid((unsigned)blocks, (unsigned)n_groups);
       if (wdtype == BLOCKFFN_BF16)

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert set(B.EXPORTS) <= set(names)
     for n in names:
         assert hasattr(lib, n), n
-    assert lib.blockffn_version() == 101
+    assert lib.blockffn_version() == 102
 
 
 def test_binding_has_the_same_names():
@@ -141,6 +141,24 @@ def test_static_scratch_entry_point_argument_checks():
         assert lib.blockffn_workspace_bytes(ctypes.byref(big), n_chunks, k) <= B.STATIC_SCRATCH_BYTES
     text = open(os.path.join(ROOT, "include", "blockffn.h")).read()
     assert re.search(r"#define\s+BLOCKFFN_STATIC_SCRATCH_BYTES\s+\(128u << 20\)", text)
+
+
+def test_forward_chunks_argument_checks():
+    lib = B.lib()
+    lay = layer()
+    f = lambda n_chunks=1, k=8, x=FAKE, scores=FAKE, mask=FAKE, union=FAKE, idx=FAKE, n_act=FAKE, y=FAKE, ws=FAKE, \
+        nbytes=1 << 30, l=lay: lib.blockffn_forward_chunks(ctypes.byref(l), None, x, n_chunks, k, scores, mask, union,
+                                                           idx, n_act, None, y, ws, nbytes, None)
+    assert f(n_chunks=0) == B.OK
+    assert lib.blockffn_forward_chunks(None, None, FAKE, 1, 8, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, FAKE, 1 << 30,
+                                       None) == B.ERR_INVALID
+    for kw in (dict(x=None), dict(scores=None), dict(mask=None), dict(union=None), dict(idx=None), dict(n_act=None),
+               dict(y=None), dict(ws=None), dict(k=0), dict(n_chunks=-1), dict(ws=ctypes.c_void_p(0x10010))):
+        assert f(**kw) == B.ERR_INVALID, kw
+    assert f(k=513) == B.ERR_UNSUPPORTED
+    assert f(nbytes=256) == B.ERR_WORKSPACE
+    # a shape that runs the three stages as they are is checked by them
+    assert f(n_chunks=4096, x=None) == B.ERR_INVALID
 
 
 def test_force_generic_modes():

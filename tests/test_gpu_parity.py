@@ -486,3 +486,47 @@ def test_few_chunks(d, E, d_e, k, C, gated):
     B.blockffn_sparse_ffn(L, xd, buf.scores, buf.token_mask, buf.active_idx, buf.n_active, C, k, y3, buf.workspace)
     torch.cuda.synchronize()
     assert torch.equal(y3, y1)
+
+
+@pytest.mark.parametrize("d,E,d_e,k,C,gated,n_layers", [
+    (2048, 64, 256, 8, 1, True, 1),      # one chunk of the layer-stack shape
+    (2048, 64, 128, 5, 3, False, 3),     # Eq. 2 experts, ragged chunk, three weight sets
+    (1024, 32, 64, 1, 9, True, 2),       # single tokens
+    (2048, 128, 128, 8, 2, True, 1),     # two mask words
+    (1024, 130, 64, 7, 3, False, 1),     # three mask words, the last one nearly empty
+    (1024, 16, 256, 3, 40, True, 1),     # many chunks of few experts
+])
+def test_forward_chunks_in_three_launches(d, E, d_e, k, C, gated, n_layers):
+    """blockffn_forward_chunks on a handful of short chunks (router per expert, an up projection
+    that redoes the routing in every workgroup and writes the router's and the union's outputs,
+    the down projection) against blockffn_router + blockffn_chunk_union + blockffn_sparse_ffn:
+    every output must have the same bits; and against the oracle."""
+    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.3, seed=E + k + C)
+    layers = wl.make_layers(w, n_layers, gain=True)
+    cl = wl.make_chunk_layer(w, n_layers) if n_layers > 1 else None
+    x = wl.make_tokens(w, layers, cl)
+    if C > 1:
+        x[k:2 * k] = 0.0        # chunk 1: no expert active (the bias is negative)
+    ref = pu.run_oracle(layers, x, w.k, cl, eps=1e-3, use_gain=True)
+    three = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k, cl, eps=1e-3, use_gain=True)   # the three calls
+    pu.assert_integers_equal(three, ref)
+    L = three["_layer"]
+    buf = B.Buffers(L, C, k)
+    for t in (buf.scores, buf.y):
+        t.fill_(float("nan"))
+    for t in (buf.token_mask, buf.union_mask, buf.active_idx, buf.n_active):
+        t.fill_(-7)
+    buf.workspace.fill_(0xff)
+    cld = None if cl is None else cl.cuda().to(torch.int32)
+    for rep in range(2):
+        B.blockffn_forward_chunks(L, x.cuda(), C, k, buf.scores, buf.token_mask, buf.union_mask, buf.active_idx,
+                                  buf.n_active, buf.stats, buf.y, buf.workspace, cld)
+    torch.cuda.synchronize()
+    for name in ("scores", "token_mask", "union_mask", "active_idx", "n_active", "y"):
+        got = getattr(buf, name).cpu().numpy()
+        if name in ("token_mask", "union_mask"):
+            got = got.view(np.uint64)
+        np.testing.assert_array_equal(got, three[name], err_msg=name)
+    np.testing.assert_array_equal(buf.stats.cpu().numpy(), 2 * three["stats"])     # two calls, counts are added to
+    if C > 1:
+        assert three["n_active"][1] == 0 and np.all(three["y"][k:2 * k] == 0)
