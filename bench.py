@@ -390,7 +390,7 @@ def run(args, name, gated=None, replicas=0, sequential=False, chunks=0, steps=No
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1) / dense_steps
     library = None
-    if dense_steps > 0 and not sequential and w.wdtype == "bf16" and C % R == 0 and w.k <= 32:
+    if dense_steps > 0 and not sequential and w.wdtype == "bf16" and C % R == 0 and w.k <= 32 and R >= 32:   # cold only
         library = library_dense(w, layers, x, buf.scores, y_dense, R, dense_steps)
     ffn_ms = (stage_us["up"] + stage_us["down"]) / 1e3
     if sequential:   # whole steps on both sides (router included): there is no per-kernel split here
