@@ -19,8 +19,8 @@ stream, the roofline of the dominant kernel, and the CPU oracle timed on a bound
 `--all` also runs every measured configuration (single-token decode, k = 8, k = 32 trees, the
 24-layer decode stack and the 512-token prefill), each with gated and with Eq. 2 experts, each
 cold (chunks rotating through distinct weight sets) and warm (one weight set, cache assisted),
-and appends one JSON record per run to gpurun_out/bench_all.jsonl; the line printed at the
-end is still the default one.
+and appends one JSON record per run to a JSONL file (--all-out); the line printed at the end is
+still the default one.
 """
 
 from __future__ import annotations
@@ -78,7 +78,9 @@ def parse():
                    help="HBM bytes per launch of the dominant kernel from rocprofv3 counters, if known")
     p.add_argument("--all", action="store_true",
                    help="also run every configuration (gated and Eq. 2 experts, cold and warm) and append one "
-                        "JSON record each to gpurun_out/bench_all.jsonl")
+                        "JSON record each to the file --all-out names")
+    p.add_argument("--all-out", default=os.path.join("gpurun_out", "bench_all.jsonl"),
+                   help="JSONL file the records of --all are appended to (relative to this script)")
     p.add_argument("--no-ceiling", action="store_true", help="skip the read-stream ceiling measurement")
     p.add_argument("--ceiling-gib", type=int, default=8, help="size of the buffer the read-stream ceiling is measured on")
     return p.parse_args()
@@ -480,7 +482,7 @@ ALL_RUNS = [
 def run_all(args):
     import torch
 
-    path = os.path.join(ROOT, "gpurun_out", "bench_all.jsonl")
+    path = os.path.join(ROOT, args.all_out)
     os.makedirs(os.path.dirname(path), exist_ok=True)
     with open(path, "a") as f:
         for name, kw in ALL_RUNS:

@@ -495,6 +495,9 @@ def test_few_chunks(d, E, d_e, k, C, gated):
     (2048, 128, 128, 8, 2, True, 1),     # two mask words
     (1024, 130, 64, 7, 3, False, 1),     # three mask words, the last one nearly empty
     (1024, 16, 256, 3, 40, True, 1),     # many chunks of few experts
+    (1024, 32, 128, 8, 80, True, 2),     # too many (chunk, slot) pairs for the short path: the three stages as they are
+    (2048, 64, 128, 16, 2, False, 1),    # chunks of more than 8 tokens: likewise
+    (512, 8, 64, 4, 3, True, 1),         # a hidden size and an expert count outside the short path
 ])
 def test_forward_chunks_in_three_launches(d, E, d_e, k, C, gated, n_layers):
     """blockffn_forward_chunks on a handful of short chunks (router per expert, an up projection
