@@ -205,11 +205,26 @@ def cpu_baseline(w, layers, x, chunk_layer, n_sample, expert_bytes):
         active += int(r["n_active"].sum())
     dt = time.perf_counter() - t0
     n = len(order)
+    # the oracle's dense pass (every expert evaluated) on a quarter of the sample: the CPU's own
+    # sparse / dense ratio, to set beside the GPU's
+    n_dense, dt_dense, left = 0, 0.0, max(1, n // 4)
+    for L, xc in work:
+        if left <= 0:
+            break
+        take = min(left, xc.shape[0] // w.k)
+        xd = xc[:take * w.k]
+        sc, _ = oracle.router(L, xd)
+        t0 = time.perf_counter()
+        oracle.dense_ffn(L, xd, sc)
+        dt_dense += time.perf_counter() - t0
+        n_dense += take
+        left -= take
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": active * expert_bytes / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "sample": "%d of %d chunks (router + union + chunk-sparse FFN in fp64, gcc -O3 -march=native -fopenmp), "
-                      "%.1f s" % (n, w.n_chunks, dt),
-            "us_per_chunk": dt / n * 1e6}
+                      "%.1f s; dense FFN on %d of them, %.1f s" % (n, w.n_chunks, dt, n_dense, dt_dense),
+            "us_per_chunk": dt / n * 1e6, "dense_us_per_chunk": dt_dense / n_dense * 1e6,
+            "speedup_vs_dense": (dt_dense / n_dense) / (dt / n)}
 
 
 def library_dense(w, layers, x, scores, y_ours, R, steps):

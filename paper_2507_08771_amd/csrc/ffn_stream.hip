@@ -723,6 +723,17 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 // chunk_union_kernel, so the same bits) and the workgroup of slot 0, tile 0 writes the outputs the
 // two kernels would have written.  One round trip to memory for 2 KiB in place of the two loads
 // of the list entry, and two launches fewer per layer.
+// The value lane (src_bytes / 4) holds (ds_bpermute; every lane names its source).
+__device__ __forceinline__ float lane_from(float v, int src_bytes) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(src_bytes, __float_as_int(v)));
+}
+__device__ __forceinline__ uint4 lanes_from(uint4 v, int src_bytes) {
+  return make_uint4((uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)v.x),
+                    (uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)v.y),
+                    (uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)v.z),
+                    (uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)v.w));
+}
+
 struct RouteOut {
   const float *preact;            // A^0 [token][N_e]
   float *scores;                  // what blockffn_router and blockffn_chunk_union write
@@ -870,21 +881,30 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
     f = scores[t * E + e];
   }
 
+  // What bounds this launch is how fast a CU's memory pipeline takes requests in, and that goes by
+  // groups of four consecutive lanes: four lanes reading 64 contiguous bytes are one request where
+  // four lanes reading 16 bytes of four rows (the matrix core's operand order: lane = 16 g + row)
+  // are four.  So every load is issued with the lanes in memory order (lane = 4 row + g: a row's
+  // 64 bytes by four neighbours) and the registers are put into operand order by a cross-lane
+  // permutation once they are back (ds_bpermute: lane 16 g + row reads lane 4 row + g).
   uint4 a[NM][FW];
 #pragma unroll
   for (int m = 0; m < NM; ++m) {
     const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
-    const uint16_t *row = w + (((size_t)layer * E + e) * d_e + rt * 16 + r) * d + kq0 + g * 8;
+    const uint16_t *row = w + (((size_t)layer * E + e) * d_e + rt * 16 + (lane >> 2)) * d + kq0 + (lane & 3) * 8;
 #pragma unroll
     for (int i = 0; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row + i * 32);
   }
+  const int a_src = (4 * r + g) * 4;   // byte address of the source lane for ds_bpermute
   // x of this wave's quarter of the contraction.  Fragment column n carries token n & 7, its hi
-  // part for n < 8 and its lo part for n >= 8, so lanes n and n + 8 need the same 8 floats: each
-  // loads one half (4 floats), splits it, and the two exchange what the other needs.
-  const float *xrow = x + (c * k + min(tok, k - 1)) * d + kq0 + g * 8 + half * 4;
+  // part for n < 8 and its lo part for n >= 8: lane (g, half, token) needs floats 8 g + 4 half .. + 3
+  // of the token's 32 per K-step, splits them, and lanes n and n + 8 exchange what the other needs.
+  // Loaded in memory order as well: lane = 8 token + piece, a token's 128 bytes by eight neighbours.
+  const float *xrow = x + (c * k + min(lane >> 3, k - 1)) * d + kq0 + (lane & 7) * 4;
   float4 xv[FW];
 #pragma unroll
   for (int i = 0; i < FW; ++i) xv[i] = *reinterpret_cast<const float4 *>(xrow + i * 32);
+  const int x_src = (8 * tok + 2 * g + half) * 4;
   // every load of this wave is in flight before anything waits
   __builtin_amdgcn_sched_barrier(0);
   f32x4 acc[NM];
@@ -892,7 +912,10 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < FW; ++i) {
-    const float v[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+#pragma unroll
+    for (int m = 0; m < NM; ++m) a[m][i] = lanes_from(a[m][i], a_src);
+    const float v[4] = {lane_from(xv[i].x, x_src), lane_from(xv[i].y, x_src), lane_from(xv[i].z, x_src),
+                        lane_from(xv[i].w, x_src)};
     uint32_t hi[4], lo[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
