@@ -58,10 +58,28 @@ __device__ __forceinline__ void load8<bf16_t>(const void *base, size_t idx, floa
   w[6] = bf16_lo(v.w); w[7] = bf16_hi(v.w);
 }
 
+// v of another lane of the same row of 16, chosen by a DPP control word (a VALU operand modifier:
+// no trip through the LDS pipeline as a shuffle takes).
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the wave, the same bits in every lane: within a row of 16 by four DPP steps (lane ^ 1,
+// lane ^ 2, the mirror lane of the half row, the mirror lane of the row: after each step the lanes
+// that were combined hold the same value, a + b and b + a being the same), then the four rows in a
+// fixed order.  A dozen VALU instructions where six shuffles cost six LDS round trips one after
+// the other, which is what the short, latency-bound launches spend their time on.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+  v += dpp_lane<0xB1>(v);    // quad_perm [1, 0, 3, 2]
+  v += dpp_lane<0x4E>(v);    // quad_perm [2, 3, 0, 1]
+  v += dpp_lane<0x141>(v);   // row_half_mirror
+  v += dpp_lane<0x140>(v);   // row_mirror
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return (r0 + r1) + (r2 + r3);
 }
 
 __device__ __forceinline__ uint64_t wave_or(uint64_t v) {

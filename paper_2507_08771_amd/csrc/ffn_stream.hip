@@ -711,22 +711,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 
 // ------------------------------------------------------------------------------------------------ up, few chunks
 
-// Small launches (e.g. a single chunk walking through a layer stack) do not have enough (chunk,
-// slot) items to occupy the chip with one workgroup per item.  Here one workgroup takes one
-// 16-row tile of one item; its four waves split the contraction, each keeps its quarter of the
-// chunk's split x in registers (no LDS fill, no barrier before the stream starts) and the four
-// partial tiles meet in LDS once at the end.  k <= 8 only; FW = d / 128 fragments per wave.
-// ROUTE: the launch also stands in for the router's normalising pass and for the chunk union.  It
-// is given the pre-activations A^0 (+ bias) of the chunk's tokens instead of scores, masks and
-// lists; every workgroup redoes the chunk's routing from them (8 tokens x N_e values: masks,
-// RMSNorm, union, the expert of its slot - the arithmetic of router_finish_kernel and
-// chunk_union_kernel, so the same bits) and the workgroup of slot 0, tile 0 writes the outputs the
-// two kernels would have written.  One round trip to memory for 2 KiB in place of the two loads
-// of the list entry, and two launches fewer per layer.
 // The value lane (src_bytes / 4) holds (ds_bpermute; every lane names its source).
-__device__ __forceinline__ float lane_from(float v, int src_bytes) {
-  return __int_as_float(__builtin_amdgcn_ds_bpermute(src_bytes, __float_as_int(v)));
-}
 __device__ __forceinline__ uint4 lanes_from(uint4 v, int src_bytes) {
   return make_uint4((uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)v.x),
                     (uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)v.y),
@@ -742,69 +727,123 @@ struct RouteOut {
   unsigned long long *stats;      // or nullptr
 };
 
+// Small launches (e.g. a single chunk walking through a layer stack) do not have enough (chunk,
+// slot) items to occupy the chip with one workgroup per item.  Here one workgroup takes one
+// 16-row tile of one item; its four waves split the contraction, each keeps its quarter of the
+// chunk's split x in registers (no LDS fill, no barrier before the stream starts) and the four
+// partial tiles meet in LDS once at the end.  k <= 8 only; FW = d / 128 fragments per wave.
+// ROUTE: the launch also stands in for the router's normalising pass and for the chunk union.  It
+// is given the pre-activations A^0 (+ bias) of the chunk's tokens instead of scores, masks and
+// lists; every workgroup redoes the chunk's routing from them (8 tokens x N_e values: masks,
+// RMSNorm, union, the expert of its slot - the arithmetic of router_finish_kernel and
+// chunk_union_kernel, so the same bits) and the workgroup of slot 0, tile 0 writes the outputs the
+// two kernels would have written.  One round trip to memory for 2 KiB in place of the two loads
+// of the list entry, and two launches fewer per layer.
+// Items are (chunk, slot, tile) in that order and workgroup b takes items b, b + gridDim.x, ...: the
+// grid covers every item, except for a single chunk, where it stops at the two workgroups per CU
+// that can be resident (the hardware would run the rest after them anyway); the items of a
+// workgroup then share the chunk, and with it the routing and the x registers.  Order of the
+// requests: A^0 (or the list entry) first, then x, which depends on nothing and arrives while the
+// routing is worked out, then the weights (loads return in the order they were issued, so
+// nothing that is waited for early may stand behind a long burst).
 template <int NM, int FW, bool ROUTE>
 __global__ __launch_bounds__(kThreads) void up_split_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
-    const int32_t *__restrict__ n_active, int k, uint16_t *__restrict__ midB, RouteOut ro) {
+    const int32_t *__restrict__ n_active, int k, uint16_t *__restrict__ midB, RouteOut ro, int total) {
   __shared__ float red[4][NM][4][64];
+  __shared__ uint64_t tmask_s[8][kMaxMaskWords];   // ROUTE: the tokens' masks and RMS
+  __shared__ float rms_s[8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4, n = lane & 15;
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int tiles = d_e / 16;
-  // the grid covers every (chunk, slot, tile); slots at or above n_active leave at once (no item
-  // list here: it would add a launch and two dependent loads to a path that is latency bound)
-  const int code = blockIdx.x / tiles, rt = blockIdx.x % tiles;
-  const int64_t c = code / E;
-  const int s = code - (int)c * E;
   const int tok = n & 7, half = n >> 3;
-  // score and mask word of this lane's token, for the epilogue (wave 0)
-  float f = 0.0f;
-  uint64_t mword = ~0ull;
-  int e = s;
+  int item = blockIdx.x;   // below `total`: the grid is never larger
+  const int64_t c = item / (E * tiles);
+  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  const int kq0 = wave * (d / 4);
+
+  // ---- what the first item's expert depends on is requested first
+  int n_act = E;
+  int e_first = item / tiles - (int)c * E;
+  [[maybe_unused]] float a0v[2][kMaxMaskWords];   // ROUTE: A^0 of tokens wave and wave + 4
   if constexpr (ROUTE) {
-    __shared__ uint64_t tmask_s[8][kMaxMaskWords];
-    __shared__ float rms_s[8];
-    const bool writer = s == 0 && rt == 0;
-    const int W = L.W;
-    const int layer_r = clamp_layer(chunk_layer, c, L.n_layers);
-    for (int t = wave; t < k; t += 4) {   // k <= 8: lanes run over the experts of one mask word at a time
-      const int64_t tk = c * k + t;
-      float a1[kMaxMaskWords];
-      float sumsq = 0.0f;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int t = wave + 4 * it;
 #pragma unroll
       for (int wd = 0; wd < kMaxMaskWords; ++wd) {
-        a1[wd] = 0.0f;
-        if (wd < W) {
-          const int i = wd * 64 + lane;
-          const float a0 = i < E ? ro.preact[tk * E + i] : 0.0f;
-          const bool active = (i < E) && (a0 > 0.0f);
-          const uint64_t word = __ballot(active);
-          if (lane == 0) {
-            tmask_s[t][wd] = word;
-            if (writer) ro.token_mask[tk * W + wd] = word;
-          }
-          a1[wd] = active ? a0 : 0.0f;
-          sumsq = fmaf(a1[wd], a1[wd], sumsq);
-        }
+        const int i = wd * 64 + lane;
+        a0v[it][wd] = (t < k && wd < L.W && i < E) ? ro.preact[(c * k + t) * E + i] : 0.0f;
       }
-      const float ms = wave_sum(sumsq) / (float)E;
-      const float rms = sqrtf(ms + L.eps);
-      if (lane == 0) rms_s[t] = rms;
-      if (writer) {
+    }
+  } else if (active_idx) {
+    n_act = n_active[c];
+    e_first = active_idx[c * E + e_first];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- x of this wave's quarter of the contraction.  Fragment column n carries token n & 7, its
+  // hi part for n < 8 and its lo part for n >= 8: lane (g, half, token) needs floats 8 g + 4 half
+  // .. + 3 of the token's 32 per K-step, splits them, and lanes n and n + 8 exchange what the other
+  // needs.  What bounds this launch is how fast a CU's memory pipeline takes requests in, and that
+  // goes by groups of four consecutive lanes: four lanes reading 64 contiguous bytes are one
+  // request where four lanes reading 16 bytes of four rows (the matrix core's operand order) are
+  // four.  So every load is issued with the lanes in memory order (here lane = 8 token + piece, a
+  // token's 128 bytes by eight neighbours) and the registers are put into operand order by a
+  // cross-lane permutation once they are back (ds_bpermute).
+  const float *xrow = x + (c * k + min(lane >> 3, k - 1)) * d + kq0 + (lane & 7) * 4;
+  uint4 bfrag[FW];   // x as loaded, then (in place) the B operand of every K-step, kept for later items
+#pragma unroll
+  for (int i = 0; i < FW; ++i) bfrag[i] = *reinterpret_cast<const uint4 *>(xrow + i * 32);
+  const int x_src = (8 * tok + 2 * g + half) * 4;   // byte address of the source lane
+  __builtin_amdgcn_sched_barrier(0);
+
+  [[maybe_unused]] uint64_t U[kMaxMaskWords];
+  if constexpr (ROUTE) {
+    const bool writer = blockIdx.x % (E * tiles) == 0;   // the workgroup of the chunk's slot 0, tile 0
+    const int W = L.W;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {   // k <= 8: lanes run over the experts of one mask word at a time
+      const int t = wave + 4 * it;
+      if (t < k) {                     // uniform over the wave
+        const int64_t tk = c * k + t;
+        float a1[kMaxMaskWords];
+        float sumsq = 0.0f;
 #pragma unroll
         for (int wd = 0; wd < kMaxMaskWords; ++wd) {
-          const int i = wd * 64 + lane;
-          if (wd < W && i < E) {
-            const float gn = L.g_rms ? L.g_rms[(size_t)layer_r * E + i] : 1.0f;
-            ro.scores[tk * E + i] = a1[wd] > 0.0f ? gn * a1[wd] / rms : 0.0f;
+          a1[wd] = 0.0f;
+          if (wd < W) {
+            const int i = wd * 64 + lane;
+            const float a0 = a0v[it][wd];
+            const bool active = (i < E) && (a0 > 0.0f);
+            const uint64_t word = __ballot(active);
+            if (lane == 0) {
+              tmask_s[t][wd] = word;
+              if (writer) ro.token_mask[tk * W + wd] = word;
+            }
+            a1[wd] = active ? a0 : 0.0f;
+            sumsq = fmaf(a1[wd], a1[wd], sumsq);
+          }
+        }
+        const float ms = wave_sum(sumsq) / (float)E;
+        const float rms = sqrtf(ms + L.eps);
+        if (lane == 0) rms_s[t] = rms;
+        if (writer) {
+#pragma unroll
+          for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+            const int i = wd * 64 + lane;
+            if (wd < W && i < E) {
+              const float gn = L.g_rms ? L.g_rms[(size_t)layer * E + i] : 1.0f;
+              ro.scores[tk * E + i] = a1[wd] > 0.0f ? gn * a1[wd] / rms : 0.0f;
+            }
           }
         }
       }
     }
     __syncthreads();
-    uint64_t U[kMaxMaskWords];
-    int n_act = 0;
+    n_act = 0;
 #pragma unroll
     for (int wd = 0; wd < kMaxMaskWords; ++wd) {
       U[wd] = 0;
@@ -837,127 +876,124 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
         }
       }
     }
-    if (s >= n_act) return;   // uniform over the workgroup
-    // the expert of slot s: the s-th set bit of the union
-    int left = s;
+  }   // tmask_s and rms_s are only read from here on
+
+  const int a_src = (4 * r + g) * 4;
+  for (bool first = true; item < total; item += gridDim.x, first = false) {
+    const int code = item / tiles, rt = item - code * tiles;
+    const int s = code - (int)c * E;   // a workgroup with several items has them all in chunk c
+    if (s >= n_act) break;             // uniform over the workgroup; later items have later slots
+    // score and mask word of this lane's token, for the epilogue (wave 0)
+    float f = 0.0f;
+    uint64_t mword = ~0ull;
+    int e = s;
+    if constexpr (ROUTE) {
+      // the expert of slot s: the s-th set bit of the union
+      int left = s;
 #pragma unroll
-    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
-      if (wd < W && left >= 0) {
-        const int pc = __popcll(U[wd]);
-        if (left < pc) {
-          uint64_t u = U[wd];
-          for (int i = 0; i < left; ++i) u &= u - 1;
-          e = wd * 64 + __builtin_ctzll(u);
-          left = -1;
-        } else {
-          left -= pc;
+      for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+        if (wd < L.W && left >= 0) {
+          const int pc = __popcll(U[wd]);
+          if (left < pc) {   // lane l asks whether bit l is the one with `left` set bits below it
+            const uint64_t u = U[wd];
+            const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(u >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)u, 0));
+            e = wd * 64 + __builtin_ctzll(__ballot(((u >> lane) & 1) && below == left));
+            left = -1;
+          } else {
+            left -= pc;
+          }
         }
       }
+      if (wave == 0 && tok < k) {
+        const int64_t tk = c * k + tok;
+        mword = tmask_s[tok][e >> 6];
+        const float a0 = ro.preact[tk * E + e];
+        const float a1v = a0 > 0.0f ? a0 : 0.0f;
+        const float gn = L.g_rms ? L.g_rms[(size_t)layer * E + e] : 1.0f;
+        f = a1v > 0.0f ? gn * a1v / rms_s[tok] : 0.0f;
+      }
+    } else if (active_idx) {
+      e = first ? e_first : active_idx[c * E + s];
     }
-    if (wave == 0 && tok < k) {
-      const int64_t tk = c * k + tok;
-      mword = tmask_s[tok][e >> 6];
-      const float a0 = ro.preact[tk * E + e];
-      const float a1v = a0 > 0.0f ? a0 : 0.0f;
-      const float gn = L.g_rms ? L.g_rms[(size_t)layer_r * E + e] : 1.0f;
-      f = a1v > 0.0f ? gn * a1v / rms_s[tok] : 0.0f;
+    // a list entry outside [0, E) is an empty slot: zeros in mid (a valid expert is streamed in its place)
+    const bool e_ok = (unsigned)e < (unsigned)E;
+    e = min(max(e, 0), E - 1);
+    // score and mask word for the epilogue: requested before the weights, so that they are back
+    // before them instead of costing a round trip after them
+    if (!ROUTE && wave == 0 && tok < k) {
+      const int64_t t = c * k + tok;
+      if (token_mask) mword = token_mask[t * L.W + (e >> 6)];
+      f = scores[t * E + e];
     }
-  } else {
-    if (active_idx) {
-      e = active_idx[c * E + s];
-      if (s >= n_active[c]) return;
-    }
-  }
-  // a list entry outside [0, E) is an empty slot: zeros in mid (a valid expert is streamed in its place)
-  const bool e_ok = (unsigned)e < (unsigned)E;
-  e = min(max(e, 0), E - 1);
-  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
-  const int kq0 = wave * (d / 4);
-  // score and mask word for the epilogue: requested first, so that they are back before the
-  // weights instead of costing a round trip after them
-  if (!ROUTE && wave == 0 && tok < k) {
-    const int64_t t = c * k + tok;
-    if (token_mask) mword = token_mask[t * L.W + (e >> 6)];
-    f = scores[t * E + e];
-  }
 
-  // What bounds this launch is how fast a CU's memory pipeline takes requests in, and that goes by
-  // groups of four consecutive lanes: four lanes reading 64 contiguous bytes are one request where
-  // four lanes reading 16 bytes of four rows (the matrix core's operand order: lane = 16 g + row)
-  // are four.  So every load is issued with the lanes in memory order (lane = 4 row + g: a row's
-  // 64 bytes by four neighbours) and the registers are put into operand order by a cross-lane
-  // permutation once they are back (ds_bpermute: lane 16 g + row reads lane 4 row + g).
-  uint4 a[NM][FW];
+    // the weights, in memory order as well: lane = 4 row + g, a row's 64 bytes by four neighbours;
+    // lane 16 g + row of the operand reads lane 4 row + g
+    uint4 a[NM][FW];
 #pragma unroll
-  for (int m = 0; m < NM; ++m) {
-    const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
-    const uint16_t *row = w + (((size_t)layer * E + e) * d_e + rt * 16 + (lane >> 2)) * d + kq0 + (lane & 3) * 8;
+    for (int m = 0; m < NM; ++m) {
+      const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
+      const uint16_t *row = w + (((size_t)layer * E + e) * d_e + rt * 16 + (lane >> 2)) * d + kq0 + (lane & 3) * 8;
 #pragma unroll
-    for (int i = 0; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row + i * 32);
-  }
-  const int a_src = (4 * r + g) * 4;   // byte address of the source lane for ds_bpermute
-  // x of this wave's quarter of the contraction.  Fragment column n carries token n & 7, its hi
-  // part for n < 8 and its lo part for n >= 8: lane (g, half, token) needs floats 8 g + 4 half .. + 3
-  // of the token's 32 per K-step, splits them, and lanes n and n + 8 exchange what the other needs.
-  // Loaded in memory order as well: lane = 8 token + piece, a token's 128 bytes by eight neighbours.
-  const float *xrow = x + (c * k + min(lane >> 3, k - 1)) * d + kq0 + (lane & 7) * 4;
-  float4 xv[FW];
-#pragma unroll
-  for (int i = 0; i < FW; ++i) xv[i] = *reinterpret_cast<const float4 *>(xrow + i * 32);
-  const int x_src = (8 * tok + 2 * g + half) * 4;
-  // every load of this wave is in flight before anything waits
-  __builtin_amdgcn_sched_barrier(0);
-  f32x4 acc[NM];
-#pragma unroll
-  for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int i = 0; i < FW; ++i) {
-#pragma unroll
-    for (int m = 0; m < NM; ++m) a[m][i] = lanes_from(a[m][i], a_src);
-    const float v[4] = {lane_from(xv[i].x, x_src), lane_from(xv[i].y, x_src), lane_from(xv[i].z, x_src),
-                        lane_from(xv[i].w, x_src)};
-    uint32_t hi[4], lo[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      split_bf16(v[q], hi[q], lo[q]);
-      if (tok >= k) hi[q] = lo[q] = 0u;
+      for (int i = 0; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row + i * 32);
     }
-    const uint32_t hw0 = hi[0] | hi[1] << 16, hw1 = hi[2] | hi[3] << 16;
-    const uint32_t lw0 = lo[0] | lo[1] << 16, lw1 = lo[2] | lo[3] << 16;
-    // lane n < 8 keeps its hi words and sends its lo words; lane n + 8 does the opposite
-    const uint32_t r0 = __shfl_xor(half ? hw0 : lw0, 8, kWave);
-    const uint32_t r1 = __shfl_xor(half ? hw1 : lw1, 8, kWave);
-    const uint4 b = half ? make_uint4(r0, r1, lw0, lw1) : make_uint4(hw0, hw1, r0, r1);
+    // every load of this wave is in flight before anything waits
+    __builtin_amdgcn_sched_barrier(0);
+    if (first) {   // x came back long ago
 #pragma unroll
-    for (int m = 0; m < NM; ++m) acc[m] = mfma16(a[m][i], b, acc[m]);
-  }
+      for (int i = 0; i < FW; ++i) {
+        const uint4 xb = lanes_from(bfrag[i], x_src);
+        const float v[4] = {__uint_as_float(xb.x), __uint_as_float(xb.y), __uint_as_float(xb.z), __uint_as_float(xb.w)};
+        uint32_t hi[4], lo[4];
 #pragma unroll
-  for (int m = 0; m < NM; ++m)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) red[wave][m][q][lane] = acc[m][q];
-  __syncthreads();
-  if (wave != 0) return;
-
-  const bool on = e_ok && tok < k && ((mword >> (e & 63)) & 1);
-  uint32_t packed[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    float u = (red[0][0][q][lane] + red[1][0][q][lane]) + (red[2][0][q][lane] + red[3][0][q][lane]);
-    u += __shfl_xor(u, 8, kWave);
-    float h;
-    if (NM == 2) {
-      float gt = (red[0][NM - 1][q][lane] + red[1][NM - 1][q][lane]) + (red[2][NM - 1][q][lane] + red[3][NM - 1][q][lane]);
-      gt += __shfl_xor(gt, 8, kWave);
-      h = swish(gt) * u;
-    } else {
-      h = swish(u);
+        for (int q = 0; q < 4; ++q) {
+          split_bf16(v[q], hi[q], lo[q]);
+          if (tok >= k) hi[q] = lo[q] = 0u;
+        }
+        const uint32_t hw0 = hi[0] | hi[1] << 16, hw1 = hi[2] | hi[3] << 16;
+        const uint32_t lw0 = lo[0] | lo[1] << 16, lw1 = lo[2] | lo[3] << 16;
+        // lane n < 8 keeps its hi words and sends its lo words; lane n + 8 does the opposite
+        const uint32_t r0 = __shfl_xor(half ? hw0 : lw0, 8, kWave);
+        const uint32_t r1 = __shfl_xor(half ? hw1 : lw1, 8, kWave);
+        bfrag[i] = half ? make_uint4(r0, r1, lw0, lw1) : make_uint4(hw0, hw1, r0, r1);
+      }
     }
-    uint32_t hi, lo;
-    split_bf16(on ? f * h : 0.0f, hi, lo);
-    packed[q] = n < 8 ? hi : lo;
+    f32x4 acc[NM];
+#pragma unroll
+    for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < FW; ++i) {
+#pragma unroll
+      for (int m = 0; m < NM; ++m) acc[m] = mfma16(lanes_from(a[m][i], a_src), bfrag[i], acc[m]);
+    }
+    if (!first) __syncthreads();   // wave 0 has read the previous item's partial tiles
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) red[wave][m][q][lane] = acc[m][q];
+    __syncthreads();
+    if (wave == 0) {
+      const bool on = e_ok && tok < k && ((mword >> (e & 63)) & 1);
+      uint32_t packed[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float u = (red[0][0][q][lane] + red[1][0][q][lane]) + (red[2][0][q][lane] + red[3][0][q][lane]);
+        u += __shfl_xor(u, 8, kWave);
+        float h;
+        if (NM == 2) {
+          float gt = (red[0][NM - 1][q][lane] + red[1][NM - 1][q][lane]) + (red[2][NM - 1][q][lane] + red[3][NM - 1][q][lane]);
+          gt += __shfl_xor(gt, 8, kWave);
+          h = swish(gt) * u;
+        } else {
+          h = swish(u);
+        }
+        uint32_t hi, lo;
+        split_bf16(on ? f * h : 0.0f, hi, lo);
+        packed[q] = n < 8 ? hi : lo;
+      }
+      *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rt, g, n) =
+          make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+    }
   }
-  *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rt, g, n) =
-      make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
 }
 
 // ------------------------------------------------------------------------------------------------ down
@@ -1208,6 +1244,10 @@ hipError_t launch_worklist(const int32_t *n_active, int64_t n_chunks, int E, int
   return hipGetLastError();
 }
 
+// Workgroups of up_split_kernel: one per item; for a single chunk no more than the two per CU
+// that can be resident (its workgroups then loop over their items, all of the one chunk).
+static int split_grid(int64_t n_chunks, int total) { return n_chunks == 1 ? std::min(total, 2 * num_cus()) : total; }
+
 bool stream_supported(const LayerView &L, int wdtype, int k) {
   return wdtype == BLOCKFFN_BF16 && k <= 32 && L.d % 512 == 0 &&
          (L.d_e == 64 || L.d_e == 128 || L.d_e == 256);
@@ -1231,10 +1271,11 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   const int64_t max_items = n_chunks * L.E;
   if (few_chunks(L, n_chunks, k)) {
     // few chunks: one workgroup per (item, 16-row tile)
-    const dim3 grid((unsigned)(max_items * (L.d_e / 16)));
+    const int total = (int)(max_items * (L.d_e / 16));
+    const dim3 grid((unsigned)split_grid(n_chunks, total));
 #define BLOCKFFN_SPLIT(nm, fw)                                                                             \
   hipLaunchKernelGGL((up_split_kernel<nm, fw, false>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, scores, token_mask, \
-                     active_idx, n_active, k, w.midB, RouteOut{})
+                     active_idx, n_active, k, w.midB, RouteOut{}, total)
     if (L.d == 2048) { if (gated) BLOCKFFN_SPLIT(2, 16); else BLOCKFFN_SPLIT(1, 16); }
     else { if (gated) BLOCKFFN_SPLIT(2, 8); else BLOCKFFN_SPLIT(1, 8); }
 #undef BLOCKFFN_SPLIT
@@ -1302,10 +1343,11 @@ hipError_t launch_up_few_routed(const LayerView &L, bool gated, const int32_t *c
   StreamWs w = carve_stream(L, n_chunks, k, ws);
   RouteOut ro{reinterpret_cast<const float *>(w.xS), scores, token_mask, union_mask, active_idx, n_active,
               reinterpret_cast<unsigned long long *>(stats)};
-  const dim3 grid((unsigned)(n_chunks * L.E * (L.d_e / 16)));
+  const int total = (int)(n_chunks * L.E * (L.d_e / 16));
+  const dim3 grid((unsigned)split_grid(n_chunks, total));
 #define BLOCKFFN_SPLIT(nm, fw)                                                                                 \
   hipLaunchKernelGGL((up_split_kernel<nm, fw, true>), grid, dim3(kThreads), 0, s, L, chunk_layer, x, nullptr, nullptr, \
-                     nullptr, nullptr, k, w.midB, ro)
+                     nullptr, nullptr, k, w.midB, ro, total)
   if (L.d == 2048) { if (gated) BLOCKFFN_SPLIT(2, 16); else BLOCKFFN_SPLIT(1, 16); }
   else { if (gated) BLOCKFFN_SPLIT(2, 8); else BLOCKFFN_SPLIT(1, 8); }
 #undef BLOCKFFN_SPLIT
