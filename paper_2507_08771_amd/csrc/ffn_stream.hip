@@ -1156,6 +1156,133 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   }
 }
 
+// The same (chunk, column block, split of the slots) decomposition for a handful of chunks of at
+// most 8 tokens, where a workgroup has three or four slots and the launch is over in a few
+// microseconds: a ring that asks for one slot while it works on the one before pays a trip to
+// memory per slot, one after the other.  Here everything a workgroup needs is asked for at once -
+// the chunk's list (count and entries together, neither waiting for the other), then mid and the
+// weights of up to kFewSlots slots (more than that in further rounds) - and waited for once.
+// Weights are requested with the lanes in memory order (lane = 4 row + g: the 64 bytes a row
+// gives to a fragment by four neighbouring lanes) and permuted into operand order in registers,
+// as in up_split_kernel.  Slots and K-steps are added in the order of down_stream_kernel: the
+// same bits.
+constexpr int kFewSlots = 4;
+
+// One round of NS slots starting at slot s0.  No branch around any load or matrix instruction: at
+// a join the compiler's counted waits collapse to "wait for everything", which puts the slots'
+// trips to memory back one after the other; hence one instantiation per number of slots.
+template <int KSD, int MW, int NS>
+__device__ __forceinline__ void down_few_round(const LayerView &L, int layer, const int (&ent)[kMaxMaskWords], int s0,
+                                               int col0, const uint4 *__restrict__ mid_c,
+                                               uint4 (&midS)[kFewSlots][KSD * 64], f32x4 (&acc)[MW]) {
+  constexpr int kFrag = KSD * MW;        // weight fragments per slot and wave
+  constexpr int kStage = KSD * 64;       // uint4 of mid per slot
+  constexpr int kPerThread = (kStage + kThreads - 1) / kThreads;
+  constexpr int d_e = KSD * 32;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int a_src = (4 * (lane & 15) + (lane >> 4)) * 4;   // ds_bpermute: lane 16 g + row reads lane 4 row + g
+  // mid first: it is waited for first, and loads come back in the order they were asked for
+  uint4 m[NS][kPerThread];
+#pragma unroll
+  for (int j = 0; j < NS; ++j)
+#pragma unroll
+    for (int q = 0; q < kPerThread; ++q)
+      m[j][q] = mid_c[(size_t)(s0 + j) * kStage + min(tid + q * kThreads, kStage - 1)];
+  __builtin_amdgcn_sched_barrier(0);
+  uint4 w[NS][kFrag];
+#pragma unroll
+  for (int j = 0; j < NS; ++j) {
+    const int sl = s0 + j;
+    int e = 0;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      const int v = __builtin_amdgcn_readlane(ent[wd], sl & 63);
+      e = (sl >> 6) == wd ? v : e;
+    }
+    e = min(max(e, 0), L.E - 1);
+    const size_t row = ((size_t)layer * L.E + e) * L.d + col0 + (lane >> 2);
+    const char *p = static_cast<const char *>(L.w_down) + row * (d_e * 2) + (lane & 3) * 16;
+#pragma unroll
+    for (int f = 0; f < kFrag; ++f)
+      w[j][f] = *reinterpret_cast<const uint4 *>(p + (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)(f % KSD) * 64);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < NS; ++j)
+#pragma unroll
+    for (int q = 0; q < kPerThread; ++q) {
+      const int idx = tid + q * kThreads;
+      if (idx < kStage) midS[j][idx] = m[j][q];
+    }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < NS; ++j)
+#pragma unroll
+    for (int f = 0; f < kFrag; ++f)
+      acc[f / KSD] = mfma16(lanes_from(w[j][f], a_src), midS[j][(f % KSD) * 64 + lane], acc[f / KSD]);
+}
+
+template <int KSD, int MW>
+__global__ __launch_bounds__(kThreads, 2) void down_few_kernel(
+    LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
+    const int32_t *__restrict__ n_active, int64_t n_chunks, int k, int col_blocks, int splits,
+    const uint16_t *__restrict__ midB, float *__restrict__ out, size_t split_stride) {
+  constexpr int d_e = KSD * 32;
+  __shared__ uint4 midS[kFewSlots][KSD * 64];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4;
+  const int E = L.E, d = L.d;
+  const int per_chunk = col_blocks * splits;
+  const int64_t c = blockIdx.x / per_chunk;
+  if (c >= n_chunks) return;
+  const int within = (int)(blockIdx.x % per_chunk);
+  const int sp = within % splits;
+  const int col0 = (within / splits) * (4 * MW * 16) + wave * (MW * 16);
+  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
+  // the chunk's list: lane l holds entries l, l + 64, ...
+  int n_act = E;
+  int ent[kMaxMaskWords];
+#pragma unroll
+  for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+    const int i = wd * 64 + lane;
+    ent[wd] = i;
+    if (active_idx && i < E) ent[wd] = active_idx[c * E + i];
+  }
+  if (active_idx) n_act = min(max(n_active[c], 0), E);
+  const int s_lo = (int)((int64_t)n_act * sp / splits), s_hi = (int)((int64_t)n_act * (sp + 1) / splits);
+  float *y = out + (size_t)sp * split_stride;
+  const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * 16 * d_e);
+
+  f32x4 acc[MW];
+#pragma unroll
+  for (int a = 0; a < MW; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int s0 = s_lo; s0 < s_hi; s0 += kFewSlots) {   // uniform over the workgroup
+    if (s0 != s_lo) __syncthreads();                  // every wave has read the round before out of midS
+    switch (min(kFewSlots, s_hi - s0)) {
+      case 1: down_few_round<KSD, MW, 1>(L, layer, ent, s0, col0, mid_c, midS, acc); break;
+      case 2: down_few_round<KSD, MW, 2>(L, layer, ent, s0, col0, mid_c, midS, acc); break;
+      case 3: down_few_round<KSD, MW, 3>(L, layer, ent, s0, col0, mid_c, midS, acc); break;
+      default: down_few_round<KSD, MW, 4>(L, layer, ent, s0, col0, mid_c, midS, acc); break;
+    }
+  }
+
+  const int n = lane & 15, t = n & 7;
+  const bool writer = n < 8 && t < k;
+#pragma unroll
+  for (int tile = 0; tile < MW; ++tile) {
+    float4 v;
+    float *vp = reinterpret_cast<float *>(&v);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float a = acc[tile][j];
+      vp[j] = a + __shfl_xor(a, 8, kWave);
+    }
+    if (writer) *reinterpret_cast<float4 *>(y + (c * k + t) * d + col0 + tile * 16 + 4 * g) = v;
+  }
+}
+
 template <int NB, int NM, int RT>
 hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
@@ -1220,10 +1347,16 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
   }
   constexpr int MW = 8 / KSD;
   const int col_blocks = L.d / (4 * MW * 16);
-  const int64_t grid = down_grid_chunks(n_chunks) * col_blocks * splits;
-  hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
-                     active_idx, n_active, n_chunks, k, col_blocks, splits, midB, tok_bits, zero16, splits > 1 ? part : y,
-                     stride);
+  if (NB == 1 && splits > 1 && !down_by_xcd(n_chunks)) {   // a handful of short chunks: everything asked for at once
+    const int64_t grid = n_chunks * col_blocks * splits;
+    hipLaunchKernelGGL((down_few_kernel<KSD, MW>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer, active_idx,
+                       n_active, n_chunks, k, col_blocks, splits, midB, part, stride);
+  } else {
+    const int64_t grid = down_grid_chunks(n_chunks) * col_blocks * splits;
+    hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
+                       active_idx, n_active, n_chunks, k, col_blocks, splits, midB, tok_bits, zero16,
+                       splits > 1 ? part : y, stride);
+  }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || splits == 1) return err;
   const size_t n4 = stride / 4;
