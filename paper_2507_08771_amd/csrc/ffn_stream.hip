@@ -996,6 +996,271 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   }
 }
 
+// ------------------------------------------------------------------------------------------------ up, one chunk
+
+// One chunk alone on the chip (a decode step walking through a layer stack).  What bounds its up
+// projection is what the busiest CU has to take in: with one workgroup per (slot, 16-row tile)
+// some CUs get two of them, each with its own copy of x.  Here one workgroup of eight waves per CU
+// takes an equal share of the union's rows - `per` groups of four consecutive neurons, up to two
+// 16-row tiles, wave = (tile, quarter of the contraction) - and reads x once: every wave loads
+// half of its quarter and turns it into B operands in LDS, where all waves read them from.  The routing is
+// redone by every workgroup as in up_split_kernel<.., ROUTE> (one token per wave), workgroup 0
+// writes the router's and the union's outputs.  The partial sums of the four quarters are added in
+// up_split_kernel's order: the same bits.
+constexpr int kChipThreads = 512;
+constexpr int kChipQuads = 8;   // groups of four rows per workgroup and round (two tiles)
+
+template <int NM, int FW>
+__global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
+                                                               const float *__restrict__ x, int k,
+                                                               uint16_t *__restrict__ midB, RouteOut ro) {
+  extern __shared__ uint4 xS[];   // [quarter][K-step][lane]: the B operands of the whole contraction
+  __shared__ float red[8][NM][4][64];
+  __shared__ float pre_s[8][kMaxExperts];            // A^0 of the chunk's tokens
+  __shared__ uint64_t tmask_s[8][kMaxMaskWords];
+  __shared__ float rms_s[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = wave >> 2, kq = wave & 3;
+  const int g = lane >> 4, n = lane & 15;
+  const int E = L.E, d = L.d, d_e = L.d_e, W = L.W;
+  const int tok = n & 7, half = n >> 3;
+  const int layer = clamp_layer(chunk_layer, 0, L.n_layers);
+  const bool writer = blockIdx.x == 0;
+
+  // ---- A^0 of token `wave`, then x: this wave's half of its quarter (both in memory order).
+  // Up to the first matrix instruction no load stands under a branch (an index out of range is
+  // clamped and the value dropped): where paths with different loads in flight join, the
+  // compiler's counted waits turn into waits for nearly everything, x included, long before x is
+  // needed.  What only workgroup 0 does for the chunk (the router's and the union's outputs)
+  // comes at the very end for the same reason.
+  float a0v[kMaxMaskWords];   // values past the last expert are dropped where they are used
+#pragma unroll
+  for (int wd = 0; wd < kMaxMaskWords; ++wd)
+    a0v[wd] = ro.preact[(size_t)min(wave, k - 1) * E + min(wd * 64 + lane, E - 1)];
+  __builtin_amdgcn_sched_barrier(0);
+  constexpr int FH = FW / 2;
+  const float *xrow = x + (size_t)min(lane >> 3, k - 1) * d + kq * (d / 4) + (lane & 7) * 4;
+  uint4 xraw[FH];
+#pragma unroll
+  for (int i = 0; i < FH; ++i) xraw[i] = *reinterpret_cast<const uint4 *>(xrow + (tile * FH + i) * 32);
+  const int x_src = (8 * tok + 2 * g + half) * 4;
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- routing of token `wave`
+  if (wave < k) {   // uniform over the wave
+    const int t = wave;
+    float a1[kMaxMaskWords];
+    float sumsq = 0.0f;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      a1[wd] = 0.0f;
+      if (wd < W) {
+        const int i = wd * 64 + lane;
+        const float a0 = i < E ? a0v[wd] : 0.0f;
+        const bool active = a0 > 0.0f;
+        const uint64_t word = __ballot(active);
+        if (i < E) pre_s[t][i] = a0;
+        if (lane == 0) tmask_s[t][wd] = word;
+        a1[wd] = active ? a0 : 0.0f;
+        sumsq = fmaf(a1[wd], a1[wd], sumsq);
+      }
+    }
+    const float ms = wave_sum(sumsq) / (float)E;
+    const float rms = sqrtf(ms + L.eps);
+    if (lane == 0) rms_s[t] = rms;
+  }
+  __syncthreads();   // the tokens' masks, RMS and A^0 are in LDS
+
+  // ---- Union(x)
+  uint64_t U[kMaxMaskWords];
+  int n_act = 0;
+#pragma unroll
+  for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+    U[wd] = 0;
+    if (wd < W) {
+      for (int t = 0; t < k; ++t) U[wd] |= tmask_s[t][wd];
+      n_act += __popcll(U[wd]);
+    }
+  }
+  // the expert of slot sl: the sl-th set bit of the union (lane l asks whether bit l is that one)
+  auto slot_expert = [&](int sl) {
+    int e = 0, left = sl;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      if (wd < W) {
+        const uint64_t u = U[wd];
+        const int pc = __popcll(u);
+        const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(u >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)u, 0));
+        const uint64_t hit = __ballot(((u >> lane) & 1) && below == left);
+        if (left >= 0 && left < pc) e = wd * 64 + __builtin_ctzll(hit | (1ull << 63));
+        left = left < pc ? -1 : left - pc;
+      }
+    }
+    return e;
+  };
+
+  // Union(x), its ascending list and the counts (chunk_union_kernel's outputs), by one wave
+  auto write_union = [&]() {
+    int base = 0;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+      if (wd < W) {
+        const uint64_t u = U[wd];
+        if (lane == 0) ro.union_mask[wd] = u;
+        const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(u >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)u, 0));
+        if ((u >> lane) & 1) ro.active_idx[base + below] = wd * 64 + lane;
+        base += __popcll(u);
+      }
+    }
+    for (int sl = base + lane; sl < E; sl += kWave) ro.active_idx[sl] = -1;
+    if (lane == 0) {
+      ro.n_active[0] = base;
+      if (ro.stats) {
+        long long tok_active = 0;
+        for (int t = 0; t < k; ++t)
+          for (int wd = 0; wd < W; ++wd) tok_active += __popcll(tmask_s[t][wd]);
+        atomicAdd(&ro.stats[0], (unsigned long long)((long long)k * E - tok_active));
+        atomicAdd(&ro.stats[1], (unsigned long long)(E - base));
+      }
+    }
+  };
+
+  // ---- this workgroup's share of the union's rows, in groups of four
+  const int qshift = __builtin_ctz(d_e / 4);                 // groups per slot: 16, 32 or 64
+  const int Q = n_act << qshift;
+  const int per = (Q + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int q_lo = blockIdx.x * per, q_hi = min(Q, q_lo + per);
+  const int a_src = (4 * (lane & 15) + g) * 4;
+  // Rounds of up to kChipQuads groups (one round unless per > 8).  No branch stands around a load
+  // or a matrix instruction (the compiler's counted waits would collapse at the join): a tile or a
+  // group past the end asks for the last group's rows again and stores nothing.  In the first
+  // round x is turned into B operands and exchanged while the weights are on their way, between
+  // the two halves of the weight requests (all of them first would not leave the registers).
+  for (int q0 = q_lo; q0 < q_hi; q0 += kChipQuads) {   // uniform over the workgroup
+    const bool first = q0 == q_lo;
+    // a round's groups lie in at most two slots
+    const int sa = q0 >> qshift;
+    const int ea = slot_expert(sa), eb = slot_expert(min(sa + 1, n_act - 1));
+    // lane (row = lane >> 2) when loading and lane (n, g) in the epilogue both sit in group g of
+    // the wave's tile
+    const int quad = q0 + 4 * tile + g;
+    const bool valid = quad < q_hi;
+    const int qc = min(quad, q_hi - 1);
+    const int slot = qc >> qshift, j0 = (qc - (slot << qshift)) * 4;
+    const int e = slot == sa ? ea : eb;
+    // the gain of the lane's expert (epilogue): asked for ahead of the weights; without a gain
+    // vector x stands in as an address and the value is dropped
+    const float *gp = L.g_rms ? L.g_rms + (size_t)layer * E + e : x;
+    const float gn_ld = *gp;
+    const uint16_t *row[NM];
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
+      row[m] = w + (((size_t)layer * E + e) * d_e + j0 + ((lane >> 2) & 3)) * d + kq * (d / 4) + (lane & 3) * 8;
+    }
+    uint4 a[NM][FW];
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+#pragma unroll
+      for (int i = 0; i < FH; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row[m] + i * 32);
+    __builtin_amdgcn_sched_barrier(0);
+    if (first) {
+      // this wave's half of x as B operands, into LDS for the other tile's wave of the same quarter
+#pragma unroll
+      for (int i = 0; i < FH; ++i) {
+        const uint4 xb = lanes_from(xraw[i], x_src);
+        const float v[4] = {__uint_as_float(xb.x), __uint_as_float(xb.y), __uint_as_float(xb.z), __uint_as_float(xb.w)};
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          split_bf16(v[q], hi[q], lo[q]);
+          if (tok >= k) hi[q] = lo[q] = 0u;
+        }
+        const uint32_t hw0 = hi[0] | hi[1] << 16, hw1 = hi[2] | hi[3] << 16;
+        const uint32_t lw0 = lo[0] | lo[1] << 16, lw1 = lo[2] | lo[3] << 16;
+        // lane n < 8 keeps its hi words and sends its lo words; lane n + 8 does the opposite
+        const uint32_t r0 = __shfl_xor(half ? hw0 : lw0, 8, kWave);
+        const uint32_t r1 = __shfl_xor(half ? hw1 : lw1, 8, kWave);
+        xS[(kq * FW + tile * FH + i) * 64 + lane] = half ? make_uint4(r0, r1, lw0, lw1) : make_uint4(hw0, hw1, r0, r1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+#pragma unroll
+      for (int i = FH; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row[m] + i * 32);
+    __builtin_amdgcn_sched_barrier(0);
+    if (first) __syncthreads();   // every B operand of the contraction is in LDS
+    // score and mask bit of this lane's token, for the epilogue
+    float f = 0.0f;
+    bool on = false;
+    if (kq == 0 && tok < k) {
+      const float a0 = pre_s[tok][e];
+      const float a1v = a0 > 0.0f ? a0 : 0.0f;
+      const float gn = L.g_rms ? gn_ld : 1.0f;
+      f = a1v > 0.0f ? gn * a1v / rms_s[tok] : 0.0f;
+      on = (tmask_s[tok][e >> 6] >> (e & 63)) & 1;
+    }
+    f32x4 acc[NM];
+#pragma unroll
+    for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < FW; ++i) {
+#pragma unroll
+      for (int m = 0; m < NM; ++m) acc[m] = mfma16(lanes_from(a[m][i], a_src), xS[(kq * FW + i) * 64 + lane], acc[m]);
+    }
+    if (!first) __syncthreads();   // the epilogue waves have read the previous round's partial tiles
+#pragma unroll
+    for (int m = 0; m < NM; ++m)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) red[wave][m][q][lane] = acc[m][q];
+    __syncthreads();
+    if (kq == 0) {   // uniform over the wave
+      const int w0 = tile * 4;
+      uint32_t packed[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float u = (red[w0][0][q][lane] + red[w0 + 1][0][q][lane]) + (red[w0 + 2][0][q][lane] + red[w0 + 3][0][q][lane]);
+        u += __shfl_xor(u, 8, kWave);
+        float h;
+        if (NM == 2) {
+          float gt = (red[w0][NM - 1][q][lane] + red[w0 + 1][NM - 1][q][lane]) +
+                     (red[w0 + 2][NM - 1][q][lane] + red[w0 + 3][NM - 1][q][lane]);
+          gt += __shfl_xor(gt, 8, kWave);
+          h = swish(gt) * u;
+        } else {
+          h = swish(u);
+        }
+        uint32_t hi, lo;
+        split_bf16(on ? f * h : 0.0f, hi, lo);
+        packed[q] = n < 8 ? hi : lo;
+      }
+      if (valid)
+        *mid_entry(midB, (size_t)slot * (d_e / 32), j0 >> 4, (j0 >> 2) & 3, n) =
+            make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+    }
+  }
+  if (writer) {   // the chunk's outputs of the router (wave t: token t) and of the union
+    if (wave < k) {
+      const int t = wave;
+#pragma unroll
+      for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+        const int i = wd * 64 + lane;
+        if (wd < W) {
+          if (lane == 0) ro.token_mask[(size_t)t * W + wd] = tmask_s[t][wd];
+          if (i < E) {
+            const float a0 = pre_s[t][i];
+            const float a1v = a0 > 0.0f ? a0 : 0.0f;
+            const float gn = L.g_rms ? L.g_rms[(size_t)layer * E + i] : 1.0f;
+            ro.scores[(size_t)t * E + i] = a1v > 0.0f ? gn * a1v / rms_s[t] : 0.0f;
+          }
+        }
+      }
+    }
+    if (wave == 0) write_union();
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ down
 
 // KSD = d_e / 32 K-steps per slot, MW row tiles (16 output columns each) per wave, RING loads in
@@ -1476,6 +1741,25 @@ hipError_t launch_up_few_routed(const LayerView &L, bool gated, const int32_t *c
   StreamWs w = carve_stream(L, n_chunks, k, ws);
   RouteOut ro{reinterpret_cast<const float *>(w.xS), scores, token_mask, union_mask, active_idx, n_active,
               reinterpret_cast<unsigned long long *>(stats)};
+  if (n_chunks == 1) {   // one workgroup per CU, equal shares of the union's rows
+    const int fw = L.d / 128;
+    const size_t lds = (size_t)4 * fw * 64 * sizeof(uint4);
+#define BLOCKFFN_CHIP(nm, fw_)                                                                                  \
+  {                                                                                                             \
+    static PerDeviceOnce lds_limit;                                                                             \
+    auto kern = up_chip_kernel<nm, fw_>;                                                                        \
+    const hipError_t e = lds_limit.run([&] {                                                                    \
+      return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                 (int)lds);                                                                     \
+    });                                                                                                         \
+    if (e != hipSuccess) return e;                                                                              \
+    hipLaunchKernelGGL(kern, dim3((unsigned)num_cus()), dim3(kChipThreads), lds, s, L, chunk_layer, x, k, w.midB, ro); \
+  }
+    if (fw == 16) { if (gated) BLOCKFFN_CHIP(2, 16) else BLOCKFFN_CHIP(1, 16) }
+    else { if (gated) BLOCKFFN_CHIP(2, 8) else BLOCKFFN_CHIP(1, 8) }
+#undef BLOCKFFN_CHIP
+    return hipGetLastError();
+  }
   const int total = (int)(n_chunks * L.E * (L.d_e / 16));
   const dim3 grid((unsigned)split_grid(n_chunks, total));
 #define BLOCKFFN_SPLIT(nm, fw)                                                                                 \

@@ -488,25 +488,32 @@ def test_few_chunks(d, E, d_e, k, C, gated):
     assert torch.equal(y3, y1)
 
 
-@pytest.mark.parametrize("d,E,d_e,k,C,gated,n_layers", [
-    (2048, 64, 256, 8, 1, True, 1),      # one chunk of the layer-stack shape
-    (2048, 64, 128, 5, 3, False, 3),     # Eq. 2 experts, ragged chunk, three weight sets
-    (1024, 32, 64, 1, 9, True, 2),       # single tokens
-    (2048, 128, 128, 8, 2, True, 1),     # two mask words
-    (1024, 130, 64, 7, 3, False, 1),     # three mask words, the last one nearly empty
-    (1024, 16, 256, 3, 40, True, 1),     # many chunks of few experts
-    (1024, 32, 128, 8, 80, True, 2),     # too many (chunk, slot) pairs for the short path: the three stages as they are
-    (2048, 64, 128, 16, 2, False, 1),    # chunks of more than 8 tokens: likewise
-    (512, 8, 64, 4, 3, True, 1),         # a hidden size and an expert count outside the short path
+@pytest.mark.parametrize("d,E,d_e,k,C,gated,n_layers,p_active", [
+    (2048, 64, 256, 8, 1, True, 1, 0.2),      # one chunk of the layer-stack shape: a workgroup per CU, equal shares of rows
+    (2048, 64, 256, 8, 1, True, 1, 0.6),      # the same with most experts in the union: two rounds per workgroup
+    (2048, 64, 256, 8, 1, False, 1, 0.02),    # ... with hardly any: most workgroups without rows
+    (1024, 32, 64, 3, 1, False, 1, 0.2),      # one chunk, half the hidden size, ragged, Eq. 2 experts, 16 row groups per slot
+    (2048, 130, 128, 8, 1, True, 2, 0.2),     # one chunk, three mask words, the second of two weight sets
+    (2048, 64, 128, 5, 3, False, 3, 0.2),     # Eq. 2 experts, ragged chunk, three weight sets
+    (1024, 32, 64, 1, 9, True, 2, 0.2),       # single tokens
+    (2048, 128, 128, 8, 2, True, 1, 0.2),     # two mask words
+    (1024, 130, 64, 7, 3, False, 1, 0.2),     # three mask words, the last one nearly empty
+    (1024, 16, 256, 3, 40, True, 1, 0.2),     # many chunks of few experts
+    (1024, 32, 128, 8, 80, True, 2, 0.2),     # too many (chunk, slot) pairs for the short path: the three stages as they are
+    (2048, 64, 128, 16, 2, False, 1, 0.2),    # chunks of more than 8 tokens: likewise
+    (512, 8, 64, 4, 3, True, 1, 0.2),         # a hidden size and an expert count outside the short path
 ])
-def test_forward_chunks_in_three_launches(d, E, d_e, k, C, gated, n_layers):
+def test_forward_chunks_in_three_launches(d, E, d_e, k, C, gated, n_layers, p_active):
     """blockffn_forward_chunks on a handful of short chunks (router per expert, an up projection
     that redoes the routing in every workgroup and writes the router's and the union's outputs,
     the down projection) against blockffn_router + blockffn_chunk_union + blockffn_sparse_ffn:
     every output must have the same bits; and against the oracle."""
-    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.3, seed=E + k + C)
+    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.3, seed=E + k + C,
+                    p_active=p_active)
     layers = wl.make_layers(w, n_layers, gain=True)
     cl = wl.make_chunk_layer(w, n_layers) if n_layers > 1 else None
+    if cl is not None and C == 1:
+        cl[:] = n_layers - 1    # the single chunk takes the last weight set
     x = wl.make_tokens(w, layers, cl)
     if C > 1:
         x[k:2 * k] = 0.0        # chunk 1: no expert active (the bias is negative)
