@@ -1078,7 +1078,8 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
   for (int wd = 0; wd < kMaxMaskWords; ++wd) {
     U[wd] = 0;
     if (wd < W) {
-      for (int t = 0; t < k; ++t) U[wd] |= tmask_s[t][wd];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) U[wd] |= tmask_s[min(t, k - 1)][wd];   // eight reads in flight; a token past the end repeats the last
       n_act += __popcll(U[wd]);
     }
   }
@@ -1128,7 +1129,9 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
   // ---- this workgroup's share of the union's rows, in groups of four
   const int qshift = __builtin_ctz(d_e / 4);                 // groups per slot: 16, 32 or 64
   const int Q = n_act << qshift;
-  const int per = (Q + (int)gridDim.x - 1) / (int)gridDim.x;
+  // ceil(Q / workgroups) by a float division: exact for these sizes (Q <= 2^14, a quotient that
+  // is not an integer is at least 1 / 1024 away from one) and a fifth of the integer sequence
+  const int per = (int)ceilf((float)Q / (float)gridDim.x);
   const int q_lo = blockIdx.x * per, q_hi = min(Q, q_lo + per);
   const int a_src = (4 * (lane & 15) + g) * 4;
   // Rounds of up to kChipQuads groups (one round unless per > 8).  No branch stands around a load
