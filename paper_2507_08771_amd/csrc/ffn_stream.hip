@@ -1010,10 +1010,11 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
 constexpr int kChipThreads = 512;
 constexpr int kChipQuads = 8;   // groups of four rows per workgroup and round (two tiles)
 
-template <int NM, int FW>
-__global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
-                                                               const float *__restrict__ x, int k,
-                                                               uint16_t *__restrict__ midB, RouteOut ro) {
+template <int NM, int FW, bool ROUTE>
+__global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
+    LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x,
+    const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
+    const int32_t *__restrict__ n_active, int k, uint16_t *__restrict__ midB, RouteOut ro) {
   extern __shared__ uint4 xS[];   // [quarter][K-step][lane]: the B operands of the whole contraction
   __shared__ float red[8][NM][4][64];
   __shared__ float pre_s[8][kMaxExperts];            // A^0 of the chunk's tokens
@@ -1033,10 +1034,24 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
   // compiler's counted waits turn into waits for nearly everything, x included, long before x is
   // needed.  What only workgroup 0 does for the chunk (the router's and the union's outputs)
   // comes at the very end for the same reason.
-  float a0v[kMaxMaskWords];   // values past the last expert are dropped where they are used
+  // Without ROUTE the chunk's list takes the place of A^0: its count and its entries together
+  // (lane l holds entries l, l + 64, ...); with no list (every expert, the dense pass) x stands in
+  // as an address and the values are dropped.
+  [[maybe_unused]] float a0v[kMaxMaskWords];   // values past the last expert are dropped where they are used
+  [[maybe_unused]] int ent[kMaxMaskWords];
+  [[maybe_unused]] int n_list = 0;
+  if constexpr (ROUTE) {
 #pragma unroll
-  for (int wd = 0; wd < kMaxMaskWords; ++wd)
-    a0v[wd] = ro.preact[(size_t)min(wave, k - 1) * E + min(wd * 64 + lane, E - 1)];
+    for (int wd = 0; wd < kMaxMaskWords; ++wd)
+      a0v[wd] = ro.preact[(size_t)min(wave, k - 1) * E + min(wd * 64 + lane, E - 1)];
+  } else {
+    const int32_t *lp = active_idx ? active_idx : reinterpret_cast<const int32_t *>(x);
+    const int32_t *np = active_idx ? n_active : reinterpret_cast<const int32_t *>(x);
+    const int span = active_idx ? E - 1 : 0;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd) ent[wd] = lp[min(wd * 64 + lane, span)];
+    n_list = np[0];
+  }
   __builtin_amdgcn_sched_barrier(0);
   constexpr int FH = FW / 2;
   const float *xrow = x + (size_t)min(lane >> 3, k - 1) * d + kq * (d / 4) + (lane & 7) * 4;
@@ -1047,7 +1062,7 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- routing of token `wave`
-  if (wave < k) {   // uniform over the wave
+  if (ROUTE && wave < k) {   // uniform over the wave
     const int t = wave;
     float a1[kMaxMaskWords];
     float sumsq = 0.0f;
@@ -1069,23 +1084,38 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
     const float rms = sqrtf(ms + L.eps);
     if (lane == 0) rms_s[t] = rms;
   }
-  __syncthreads();   // the tokens' masks, RMS and A^0 are in LDS
+  if constexpr (ROUTE) __syncthreads();   // the tokens' masks, RMS and A^0 are in LDS
 
   // ---- Union(x)
-  uint64_t U[kMaxMaskWords];
+  [[maybe_unused]] uint64_t U[kMaxMaskWords];
   int n_act = 0;
+  if constexpr (!ROUTE) {
+    n_act = active_idx ? min(max(n_list, 0), E) : E;
+#pragma unroll
+    for (int wd = 0; wd < kMaxMaskWords; ++wd)
+      if (!active_idx) ent[wd] = wd * 64 + lane;
+  }
 #pragma unroll
   for (int wd = 0; wd < kMaxMaskWords; ++wd) {
     U[wd] = 0;
-    if (wd < W) {
+    if (ROUTE && wd < W) {
 #pragma unroll
       for (int t = 0; t < 8; ++t) U[wd] |= tmask_s[min(t, k - 1)][wd];   // eight reads in flight; a token past the end repeats the last
       n_act += __popcll(U[wd]);
     }
   }
-  // the expert of slot sl: the sl-th set bit of the union (lane l asks whether bit l is that one)
+  // the expert of slot sl: the sl-th set bit of the union (lane l asks whether bit l is that
+  // one), or the list's entry as it stands (an entry outside [0, N_e) is an empty slot)
   auto slot_expert = [&](int sl) {
     int e = 0, left = sl;
+    if constexpr (!ROUTE) {
+#pragma unroll
+      for (int wd = 0; wd < kMaxMaskWords; ++wd) {
+        const int v = __builtin_amdgcn_readlane(ent[wd], sl & 63);
+        e = (sl >> 6) == wd ? v : e;
+      }
+      return e;
+    }
 #pragma unroll
     for (int wd = 0; wd < kMaxMaskWords; ++wd) {
       if (wd < W) {
@@ -1150,11 +1180,23 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
     const bool valid = quad < q_hi;
     const int qc = min(quad, q_hi - 1);
     const int slot = qc >> qshift, j0 = (qc - (slot << qshift)) * 4;
-    const int e = slot == sa ? ea : eb;
-    // the gain of the lane's expert (epilogue): asked for ahead of the weights; without a gain
-    // vector x stands in as an address and the value is dropped
-    const float *gp = L.g_rms ? L.g_rms + (size_t)layer * E + e : x;
-    const float gn_ld = *gp;
+    const int e_raw = slot == sa ? ea : eb;
+    const bool e_ok = (unsigned)e_raw < (unsigned)E;   // always, with ROUTE
+    const int e = min(max(e_raw, 0), E - 1);
+    // what the epilogue needs of the lane's expert and token, asked for ahead of the weights: the
+    // gain (ROUTE), or the score and the mask word; where a vector is absent x stands in as an
+    // address and the value is dropped
+    [[maybe_unused]] float gn_ld = 1.0f, f_ld = 0.0f;
+    [[maybe_unused]] uint64_t m_ld = ~0ull;
+    if constexpr (ROUTE) {
+      const float *gp = L.g_rms ? L.g_rms + (size_t)layer * E + e : x;
+      gn_ld = *gp;
+    } else {
+      const int tk = min(tok, k - 1);
+      f_ld = scores[(size_t)tk * E + e];
+      const uint64_t *mp = token_mask ? token_mask + (size_t)tk * W + (e >> 6) : reinterpret_cast<const uint64_t *>(x);
+      m_ld = *mp;
+    }
     const uint16_t *row[NM];
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
@@ -1198,11 +1240,16 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
     float f = 0.0f;
     bool on = false;
     if (kq == 0 && tok < k) {
-      const float a0 = pre_s[tok][e];
-      const float a1v = a0 > 0.0f ? a0 : 0.0f;
-      const float gn = L.g_rms ? gn_ld : 1.0f;
-      f = a1v > 0.0f ? gn * a1v / rms_s[tok] : 0.0f;
-      on = (tmask_s[tok][e >> 6] >> (e & 63)) & 1;
+      if constexpr (ROUTE) {
+        const float a0 = pre_s[tok][e];
+        const float a1v = a0 > 0.0f ? a0 : 0.0f;
+        const float gn = L.g_rms ? gn_ld : 1.0f;
+        f = a1v > 0.0f ? gn * a1v / rms_s[tok] : 0.0f;
+        on = (tmask_s[tok][e >> 6] >> (e & 63)) & 1;
+      } else {
+        f = f_ld;
+        on = e_ok && (token_mask ? (m_ld >> (e & 63)) & 1 : true);
+      }
     }
     f32x4 acc[NM];
 #pragma unroll
@@ -1243,7 +1290,7 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(LayerView L, cons
             make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
     }
   }
-  if (writer) {   // the chunk's outputs of the router (wave t: token t) and of the union
+  if (ROUTE && writer) {   // the chunk's outputs of the router (wave t: token t) and of the union
     if (wave < k) {
       const int t = wave;
 #pragma unroll
@@ -1671,6 +1718,26 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   const int NB = b_frags(k), RT = L.d_e / 64;
   const int64_t max_items = n_chunks * L.E;
   if (few_chunks(L, n_chunks, k)) {
+    if (n_chunks == 1) {   // one workgroup per CU, equal shares of the listed experts' rows
+      const int fw = L.d / 128;
+      const size_t lds = (size_t)4 * fw * 64 * sizeof(uint4);
+#define BLOCKFFN_CHIP(nm, fw_)                                                                                  \
+  {                                                                                                             \
+    static PerDeviceOnce lds_limit;                                                                             \
+    auto kern = up_chip_kernel<nm, fw_, false>;                                                                 \
+    const hipError_t e = lds_limit.run([&] {                                                                    \
+      return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                 (int)lds);                                                                     \
+    });                                                                                                         \
+    if (e != hipSuccess) return e;                                                                              \
+    hipLaunchKernelGGL(kern, dim3((unsigned)num_cus()), dim3(kChipThreads), lds, s, L, chunk_layer, x, scores,  \
+                       token_mask, active_idx, n_active, k, w.midB, RouteOut{});                                \
+  }
+      if (fw == 16) { if (gated) BLOCKFFN_CHIP(2, 16) else BLOCKFFN_CHIP(1, 16) }
+      else { if (gated) BLOCKFFN_CHIP(2, 8) else BLOCKFFN_CHIP(1, 8) }
+#undef BLOCKFFN_CHIP
+      return hipGetLastError();
+    }
     // few chunks: one workgroup per (item, 16-row tile)
     const int total = (int)(max_items * (L.d_e / 16));
     const dim3 grid((unsigned)split_grid(n_chunks, total));
@@ -1750,13 +1817,14 @@ hipError_t launch_up_few_routed(const LayerView &L, bool gated, const int32_t *c
 #define BLOCKFFN_CHIP(nm, fw_)                                                                                  \
   {                                                                                                             \
     static PerDeviceOnce lds_limit;                                                                             \
-    auto kern = up_chip_kernel<nm, fw_>;                                                                        \
+    auto kern = up_chip_kernel<nm, fw_, true>;                                                                  \
     const hipError_t e = lds_limit.run([&] {                                                                    \
       return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                  (int)lds);                                                                     \
     });                                                                                                         \
     if (e != hipSuccess) return e;                                                                              \
-    hipLaunchKernelGGL(kern, dim3((unsigned)num_cus()), dim3(kChipThreads), lds, s, L, chunk_layer, x, k, w.midB, ro); \
+    hipLaunchKernelGGL(kern, dim3((unsigned)num_cus()), dim3(kChipThreads), lds, s, L, chunk_layer, x, nullptr, nullptr, \
+                       nullptr, nullptr, k, w.midB, ro);                                                        \
   }
     if (fw == 16) { if (gated) BLOCKFFN_CHIP(2, 16) else BLOCKFFN_CHIP(1, 16) }
     else { if (gated) BLOCKFFN_CHIP(2, 8) else BLOCKFFN_CHIP(1, 8) }
