@@ -370,6 +370,8 @@ def test_large_chunk_rows_of_few_terms(seed, gated, p_active, sigma):
 
 
 @pytest.mark.parametrize("d,E,d_e,k,C", [(2048, 64, 128, 8, 3),     # few chunks: one workgroup per (slot, row tile)
+                                         (2048, 64, 256, 8, 1),     # one chunk: one workgroup per CU, shares of rows
+                                         (1024, 130, 64, 5, 1),     # ... three list words, 16 row groups per slot
                                          (1024, 32, 128, 8, 80),    # the persistent up kernel
                                          (2048, 64, 128, 32, 3),    # double-buffered up kernel, items of several slots
                                          (2048, 64, 256, 24, 3),    # single-buffer kernel at k > 8
@@ -441,6 +443,7 @@ def test_work_list_of_many_chunks():
 
 @pytest.mark.parametrize("d,E,d_e,k,C,gated", [
     (2048, 64, 256, 8, 1, True),     # one chunk of the layer-stack shape: 8 slot splits of the down projection
+    (1024, 70, 128, 3, 1, False),    # one ragged chunk, two list words, Eq. 2 experts, half the hidden size
     (2048, 64, 128, 5, 3, False),    # Eq. 2 experts, ragged chunk
     (1024, 32, 64, 1, 9, True),      # single tokens, four row tiles per wave in the down items
     (2048, 128, 128, 8, 2, True),    # two mask words
