@@ -295,10 +295,11 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   constexpr int KC = 2048 / NB;   // contraction elements per LDS fill
   constexpr int NA = acc_tiles(NB);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 15, g = lane >> 4;
+  const int lsrc = line_src(lane);
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int total = *total_ptr;
   const size_t row_bytes = (size_t)d * 2;
+  const size_t rows8 = 8 * row_bytes;   // from the line of rows 0-7 to the line of rows 8-15
 
   // A list entry outside [0, E) (an invalid input) is an empty slot: the kernel streams a valid
   // expert in its place (the index is clamped) and writes zeros to mid, as if no token had it.
@@ -320,8 +321,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   // per-lane byte pointer to the first fragment of (layer, expert, tile rr, matrix m)
   auto tile_ptr = [&](int layer, int e, int rr, int m) -> const char * {
     const char *w = static_cast<const char *>(m == 0 ? L.w_up : L.w_gate);
-    const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + r;
-    return w + row * row_bytes + g * 16;
+    const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + line_row(lane);
+    return w + row * row_bytes + line_byte(lane);
   };
 
   uint4 ring[kRing];
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
   {
     const char *p = tile_ptr(layer, e, 0, 0);
 #pragma unroll
-    for (int i = 0; i < kRing; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + i * 64);
+    for (int i = 0; i < kRing; ++i) ring[i] = load_stream(p + (i & 1) * rows8 + (i >> 1) * 128);
   }
 
   while (true) {
@@ -438,13 +439,18 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
               pf_valid = true;
             }
 #pragma unroll
-            for (int i = 0; i < kRing; ++i) {
+            for (int i = 0; i < kRing; i += 2) {   // a line: two K-steps
+              uint4 f[2];
+              line_operands(ring[i], ring[i + 1], lsrc, f[0], f[1]);
 #pragma unroll
-              for (int bf = 0; bf < NB; ++bf) {
-                const uint4 b = xB[(size_t)((kb * kRing + i) * NB + bf) * 64 + lane];
-                acc[rr][m][acc_of(NB, bf)] = mfma16(ring[i], b, acc[rr][m][acc_of(NB, bf)]);
-              }
-              ring[i] = *reinterpret_cast<const uint4 *>(nxt + i * 64);   // nxt is always a valid tile
+              for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int bf = 0; bf < NB; ++bf) {
+                  const uint4 b = xB[(size_t)((kb * kRing + i + h) * NB + bf) * 64 + lane];
+                  acc[rr][m][acc_of(NB, bf)] = mfma16(f[h], b, acc[rr][m][acc_of(NB, bf)]);
+                }
+              ring[i] = load_stream(nxt + (i >> 1) * 128);   // nxt is always a valid tile
+              ring[i + 1] = load_stream(nxt + rows8 + (i >> 1) * 128);
             }
           }
         }
@@ -488,10 +494,11 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   constexpr int NA = acc_tiles(NB);
   extern __shared__ uint4 xB[];           // [2][K-step][NB][64 lanes]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 15, g = lane >> 4;
+  const int lsrc = line_src(lane);
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int total = *total_ptr;
   const size_t row_bytes = (size_t)d * 2;
+  const size_t rows8 = 8 * row_bytes;   // from the line of rows 0-7 to the line of rows 8-15
   const int nkc = d / KB;
 
   auto slot_expert = [&](int64_t c, int s) {
@@ -509,8 +516,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   auto tile_ptr = [&](int layer, int e, int t) -> const char * {
     const int rr = t / NM, m = t % NM;
     const char *w = static_cast<const char *>(m == 0 ? L.w_up : L.w_gate);
-    const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + r;
-    return w + row * row_bytes + g * 16;
+    const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + line_row(lane);
+    return w + row * row_bytes + line_byte(lane);
   };
   // The experts of an item's slots are kept as bytes of one word (E <= 256): indexed by a run-time
   // slot, an array of them is moved to scratch memory by the compiler, and the load from there
@@ -632,7 +639,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 #pragma unroll
   for (int h = 0; h < kRing / FPT; ++h) {
 #pragma unroll
-    for (int i = 0; i < FPT; ++i) ring[h * FPT + i] = *reinterpret_cast<const uint4 *>(cu_ptr + i * 64);
+    for (int i = 0; i < FPT; ++i) ring[h * FPT + i] = load_stream(cu_ptr + (i & 1) * rows8 + (i >> 1) * 128);
     cu_advance();
   }
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");   // the fill is older than the ring's loads
@@ -670,13 +677,18 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
             constexpr int kHalves = kRing / FPT;   // tiles the ring holds
             const int r0 = kHalves == 1 ? 0 : ((rr * NM + m) % kHalves) * FPT;
 #pragma unroll
-            for (int i = 0; i < FPT; ++i) {
+            for (int i = 0; i < FPT; i += 2) {   // a line: two K-steps
+              uint4 f[2];
+              line_operands(ring[r0 + i], ring[r0 + i + 1], lsrc, f[0], f[1]);
 #pragma unroll
-              for (int bf = 0; bf < NB; ++bf) {
-                const uint4 b = xb[(i * NB + bf) * 64 + lane];
-                acc[sl][rr][m][acc_of(NB, bf)] = mfma16(ring[r0 + i], b, acc[sl][rr][m][acc_of(NB, bf)]);
-              }
-              ring[r0 + i] = *reinterpret_cast<const uint4 *>(cu_ptr + i * 64);
+              for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int bf = 0; bf < NB; ++bf) {
+                  const uint4 b = xb[((i + h) * NB + bf) * 64 + lane];
+                  acc[sl][rr][m][acc_of(NB, bf)] = mfma16(f[h], b, acc[sl][rr][m][acc_of(NB, bf)]);
+                }
+              ring[r0 + i] = load_stream(cu_ptr + (i >> 1) * 128);
+              ring[r0 + i + 1] = load_stream(cu_ptr + rows8 + (i >> 1) * 128);
               // keep the refill here: left alone, the scheduler moves the loads of a tile together and
               // this kernel loses 10 % (the single-buffer kernel, oddly, is 1-5 % better left alone)
               __builtin_amdgcn_sched_barrier(0);
@@ -755,7 +767,7 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
   __shared__ uint64_t tmask_s[8][kMaxMaskWords];   // ROUTE: the tokens' masks and RMS
   __shared__ float rms_s[8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 15, g = lane >> 4, n = lane & 15;
+  const int g = lane >> 4, n = lane & 15;
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int tiles = d_e / 16;
   const int tok = n & 7, half = n >> 3;
@@ -878,7 +890,7 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
     }
   }   // tmask_s and rms_s are only read from here on
 
-  const int a_src = (4 * r + g) * 4;
+  const int lsrc = line_src(lane);
   for (bool first = true; item < total; item += gridDim.x, first = false) {
     const int code = item / tiles, rt = item - code * tiles;
     const int s = code - (int)c * E;   // a workgroup with several items has them all in chunk c
@@ -926,15 +938,15 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
       f = scores[t * E + e];
     }
 
-    // the weights, in memory order as well: lane = 4 row + g, a row's 64 bytes by four neighbours;
-    // lane 16 g + row of the operand reads lane 4 row + g
+    // the weights: whole lines, non-temporal (load_stream): a[m][2 p] is line p of the tile's rows
+    // 0-7, a[m][2 p + 1] of rows 8-15, lane = 8 row + piece
     uint4 a[NM][FW];
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
-      const uint16_t *row = w + (((size_t)layer * E + e) * d_e + rt * 16 + (lane >> 2)) * d + kq0 + (lane & 3) * 8;
+      const char *w = static_cast<const char *>(m == 0 ? L.w_up : L.w_gate);
+      const char *row = w + ((((size_t)layer * E + e) * d_e + rt * 16 + line_row(lane)) * d + kq0) * 2 + line_byte(lane);
 #pragma unroll
-      for (int i = 0; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row + i * 32);
+      for (int i = 0; i < FW; ++i) a[m][i] = load_stream(row + (size_t)(i & 1) * 8 * d * 2 + (i >> 1) * 128);
     }
     // every load of this wave is in flight before anything waits
     __builtin_amdgcn_sched_barrier(0);
@@ -961,9 +973,14 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
 #pragma unroll
     for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < FW; ++i) {
+    for (int i = 0; i < FW; i += 2) {   // a line: two K-steps
 #pragma unroll
-      for (int m = 0; m < NM; ++m) acc[m] = mfma16(lanes_from(a[m][i], a_src), bfrag[i], acc[m]);
+      for (int m = 0; m < NM; ++m) {
+        uint4 f0, f1;
+        line_operands(a[m][i], a[m][i + 1], lsrc, f0, f1);
+        acc[m] = mfma16(f0, bfrag[i], acc[m]);
+        acc[m] = mfma16(f1, bfrag[i + 1], acc[m]);
+      }
     }
     if (!first) __syncthreads();   // wave 0 has read the previous item's partial tiles
 #pragma unroll
@@ -1163,7 +1180,7 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
   // is not an integer is at least 1 / 1024 away from one) and a fifth of the integer sequence
   const int per = (int)ceilf((float)Q / (float)gridDim.x);
   const int q_lo = blockIdx.x * per, q_hi = min(Q, q_lo + per);
-  const int a_src = (4 * (lane & 15) + g) * 4;
+  const int lsrc = line_src(lane);
   // Rounds of up to kChipQuads groups (one round unless per > 8).  No branch stands around a load
   // or a matrix instruction (the compiler's counted waits would collapse at the join): a tile or a
   // group past the end asks for the last group's rows again and stores nothing.  In the first
@@ -1174,13 +1191,18 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
     // a round's groups lie in at most two slots
     const int sa = q0 >> qshift;
     const int ea = slot_expert(sa), eb = slot_expert(min(sa + 1, n_act - 1));
-    // lane (row = lane >> 2) when loading and lane (n, g) in the epilogue both sit in group g of
-    // the wave's tile
-    const int quad = q0 + 4 * tile + g;
-    const bool valid = quad < q_hi;
-    const int qc = min(quad, q_hi - 1);
-    const int slot = qc >> qshift, j0 = (qc - (slot << qshift)) * 4;
-    const int e_raw = slot == sa ? ea : eb;
+    // group `quad` of the round (a group past the end asks for the last one's rows again and stores
+    // nothing): its slot, its first neuron there, its expert as listed
+    auto group_of = [&](int quad, int &slot, int &j0, int &e_raw) {
+      const int qc = min(q0 + quad, q_hi - 1);
+      slot = qc >> qshift;
+      j0 = (qc - (slot << qshift)) * 4;
+      e_raw = slot == sa ? ea : eb;
+    };
+    // lane (n, g) of the epilogue sits in group g of the wave's tile
+    const bool valid = q0 + 4 * tile + g < q_hi;
+    int slot, j0, e_raw;
+    group_of(4 * tile + g, slot, j0, e_raw);
     const bool e_ok = (unsigned)e_raw < (unsigned)E;   // always, with ROUTE
     const int e = min(max(e_raw, 0), E - 1);
     // what the epilogue needs of the lane's expert and token, asked for ahead of the weights: the
@@ -1197,17 +1219,25 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
       const uint64_t *mp = token_mask ? token_mask + (size_t)tk * W + (e >> 6) : reinterpret_cast<const uint64_t *>(x);
       m_ld = *mp;
     }
-    const uint16_t *row[NM];
+    // the weights: whole lines, non-temporal (load_stream): a[m][2 p] is line p of the tile's rows
+    // 0-7 (groups 0 and 1), a[m][2 p + 1] of rows 8-15 (groups 2 and 3), lane = 8 row + piece
+    const char *row[NM][2];
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      const uint16_t *w = static_cast<const uint16_t *>(m == 0 ? L.w_up : L.w_gate);
-      row[m] = w + (((size_t)layer * E + e) * d_e + j0 + ((lane >> 2) & 3)) * d + kq * (d / 4) + (lane & 3) * 8;
+    for (int hh = 0; hh < 2; ++hh) {
+      int sl_l, j_l, e_l;
+      group_of(4 * tile + 2 * hh + (lane >> 5), sl_l, j_l, e_l);
+      e_l = min(max(e_l, 0), E - 1);
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        const char *w = static_cast<const char *>(m == 0 ? L.w_up : L.w_gate);
+        row[m][hh] = w + ((((size_t)layer * E + e_l) * d_e + j_l + ((lane >> 3) & 3)) * d + kq * (d / 4)) * 2 + line_byte(lane);
+      }
     }
     uint4 a[NM][FW];
 #pragma unroll
     for (int m = 0; m < NM; ++m)
 #pragma unroll
-      for (int i = 0; i < FH; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row[m] + i * 32);
+      for (int i = 0; i < FH; ++i) a[m][i] = load_stream(row[m][i & 1] + (i >> 1) * 128);
     __builtin_amdgcn_sched_barrier(0);
     if (first) {
       // this wave's half of x as B operands, into LDS for the other tile's wave of the same quarter
@@ -1233,7 +1263,7 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
 #pragma unroll
     for (int m = 0; m < NM; ++m)
 #pragma unroll
-      for (int i = FH; i < FW; ++i) a[m][i] = *reinterpret_cast<const uint4 *>(row[m] + i * 32);
+      for (int i = FH; i < FW; ++i) a[m][i] = load_stream(row[m][i & 1] + (i >> 1) * 128);
     __builtin_amdgcn_sched_barrier(0);
     if (first) __syncthreads();   // every B operand of the contraction is in LDS
     // score and mask bit of this lane's token, for the epilogue
@@ -1255,9 +1285,14 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
 #pragma unroll
     for (int m = 0; m < NM; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < FW; ++i) {
+    for (int i = 0; i < FW; i += 2) {   // a line: two K-steps
 #pragma unroll
-      for (int m = 0; m < NM; ++m) acc[m] = mfma16(lanes_from(a[m][i], a_src), xS[(kq * FW + i) * 64 + lane], acc[m]);
+      for (int m = 0; m < NM; ++m) {
+        uint4 f0, f1;
+        line_operands(a[m][i], a[m][i + 1], lsrc, f0, f1);
+        acc[m] = mfma16(f0, xS[(kq * FW + i) * 64 + lane], acc[m]);
+        acc[m] = mfma16(f1, xS[(kq * FW + i + 1) * 64 + lane], acc[m]);
+      }
     }
     if (!first) __syncthreads();   // the epilogue waves have read the previous round's partial tiles
 #pragma unroll
@@ -1336,7 +1371,8 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   __shared__ uint4 midS[2][kStage];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 15, g = lane >> 4;
+  const int g = lane >> 4;
+  const int lsrc = line_src(lane);
   const int E = L.E, d = L.d;
   constexpr int d_e = KSD * 32;
   // Every workgroup of a chunk stages the chunk's whole mid (16 NB rows of d_e per slot): spread
@@ -1363,13 +1399,15 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     return min(max(e, 0), E - 1);
   };
   auto slot_ptr = [&](int e) -> const char * {
-    const size_t row = ((size_t)layer * E + e) * d + col0 + r;
-    return static_cast<const char *>(L.w_down) + row * (d_e * 2) + g * 16;
+    const size_t row = ((size_t)layer * E + e) * d + col0 + line_row(lane);
+    return static_cast<const char *>(L.w_down) + row * (d_e * 2) + line_byte(lane);
   };
-  // fragment f of a slot: row tile f / KSD, K-step f % KSD.  The K-steps of one row tile are
-  // consecutive so that the 64-byte halves of each 128-byte line are requested back to back
-  // (requested several loads apart they were fetched from the fabric twice).
-  auto frag_off = [&](int f) { return (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)(f % KSD) * 64; };
+  // Load f of a slot (two loads per 128-byte line, see load_stream): row tile f / KSD, line
+  // (f % KSD) / 2 of its rows, rows 0-7 for even f and rows 8-15 for odd f; the pair holds the A
+  // operands of K-steps f % KSD and f % KSD + 1.
+  auto frag_off = [&](int f) {
+    return (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)((f % KSD) >> 1) * 128 + (size_t)(f & 1) * 8 * d_e * 2;
+  };
 
   f32x4 acc[MW][NA];
 #pragma unroll
@@ -1383,7 +1421,7 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     {
       const char *p = slot_ptr(e);
 #pragma unroll
-      for (int i = 0; i < RING; ++i) ring[i] = *reinterpret_cast<const uint4 *>(p + frag_off(i));
+      for (int i = 0; i < RING; ++i) ring[i] = load_stream(p + frag_off(i));
     }
     const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NB * 16) * d_e);
     // B-operand order in LDS is [K-step][NB][lane = gg * 16 + n] of 8 bf16.  k <= 8: mid is stored
@@ -1432,15 +1470,22 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 #pragma unroll
       for (int tile = 0; tile < MW; ++tile) {
 #pragma unroll
-        for (int ks = 0; ks < KSD; ++ks) {
+        for (int ks = 0; ks < KSD; ks += 2) {   // a line: two K-steps
           const int f = tile * KSD + ks;
+          uint4 fr[2];
+          line_operands(ring[f % RING], ring[f % RING + 1], lsrc, fr[0], fr[1]);
 #pragma unroll
-          for (int bf = 0; bf < NB; ++bf)
-            acc[tile][acc_of(NB, bf)] =
-                mfma16(ring[f % RING], bS[(ks * NB + bf) * 64 + lane], acc[tile][acc_of(NB, bf)]);
-          const int fn = f + RING;
-          if (fn < kFrag) ring[f % RING] = *reinterpret_cast<const uint4 *>(cur + frag_off(fn));
-          else if (has_next) ring[f % RING] = *reinterpret_cast<const uint4 *>(nxt + frag_off(fn - kFrag));
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int bf = 0; bf < NB; ++bf)
+              acc[tile][acc_of(NB, bf)] =
+                  mfma16(fr[h], bS[((ks + h) * NB + bf) * 64 + lane], acc[tile][acc_of(NB, bf)]);
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int fn = f + h + RING;
+            if (fn < kFrag) ring[(f + h) % RING] = load_stream(cur + frag_off(fn));
+            else if (has_next) ring[(f + h) % RING] = load_stream(nxt + frag_off(fn - kFrag));
+          }
         }
       }
       // loads return in issue order: everything older than the weight loads issued since (at
@@ -1495,7 +1540,7 @@ __device__ __forceinline__ void down_few_round(const LayerView &L, int layer, co
   constexpr int kPerThread = (kStage + kThreads - 1) / kThreads;
   constexpr int d_e = KSD * 32;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int a_src = (4 * (lane & 15) + (lane >> 4)) * 4;   // ds_bpermute: lane 16 g + row reads lane 4 row + g
+  const int lsrc = line_src(lane);
   // mid first: it is waited for first, and loads come back in the order they were asked for
   uint4 m[NS][kPerThread];
 #pragma unroll
@@ -1515,11 +1560,14 @@ __device__ __forceinline__ void down_few_round(const LayerView &L, int layer, co
       e = (sl >> 6) == wd ? v : e;
     }
     e = min(max(e, 0), L.E - 1);
-    const size_t row = ((size_t)layer * L.E + e) * L.d + col0 + (lane >> 2);
-    const char *p = static_cast<const char *>(L.w_down) + row * (d_e * 2) + (lane & 3) * 16;
+    // whole lines, non-temporal (load_stream): load f = row tile f / KSD, line (f % KSD) / 2, rows
+    // 0-7 for even f and rows 8-15 for odd f, lane = 8 row + piece
+    const size_t row = ((size_t)layer * L.E + e) * L.d + col0 + line_row(lane);
+    const char *p = static_cast<const char *>(L.w_down) + row * (d_e * 2) + line_byte(lane);
 #pragma unroll
     for (int f = 0; f < kFrag; ++f)
-      w[j][f] = *reinterpret_cast<const uint4 *>(p + (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)(f % KSD) * 64);
+      w[j][f] = load_stream(p + (size_t)(f / KSD) * 16 * d_e * 2 + (size_t)((f % KSD) >> 1) * 128 +
+                            (size_t)(f & 1) * 8 * d_e * 2);
   }
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -1533,8 +1581,12 @@ __device__ __forceinline__ void down_few_round(const LayerView &L, int layer, co
 #pragma unroll
   for (int j = 0; j < NS; ++j)
 #pragma unroll
-    for (int f = 0; f < kFrag; ++f)
-      acc[f / KSD] = mfma16(lanes_from(w[j][f], a_src), midS[j][(f % KSD) * 64 + lane], acc[f / KSD]);
+    for (int f = 0; f < kFrag; f += 2) {   // a line: two K-steps
+      uint4 f0, f1;
+      line_operands(w[j][f], w[j][f + 1], lsrc, f0, f1);
+      acc[f / KSD] = mfma16(f0, midS[j][(f % KSD) * 64 + lane], acc[f / KSD]);
+      acc[f / KSD] = mfma16(f1, midS[j][(f % KSD + 1) * 64 + lane], acc[f / KSD]);
+    }
 }
 
 template <int KSD, int MW>

@@ -23,6 +23,52 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
+// ---- the weight stream: non-temporal loads of whole 128-byte lines
+//
+// Every weight byte is used once per launch, so nothing is gained by keeping it in the caches,
+// and a read stream of non-temporal loads runs at 7.1-7.2 TB/s on this chip where plain loads
+// reach 6.3-6.5 - provided a load instruction takes whole 128-byte lines (eight neighbouring
+// lanes per line).  With the 64-byte half lines of the matrix core's operand order (lane = 16 g +
+// row: 16 bytes of 16 rows per group of 16 lanes) non-temporal loads are slower than plain ones
+// (6.0 TB/s): the other half of a line is fetched again.  So a 16-row tile is requested as two
+// registers per line index: `lo8` = the line of rows 0-7, `hi8` = of rows 8-15, lane = 8 row +
+// piece, and the two A operands the line holds (K-steps 2p and 2p + 1: its first and second 64
+// bytes) are put together in registers: one ds_bpermute per dword brings, for its eight rows,
+// K-step 2p to the lanes of rows 0-7 and K-step 2p + 1 to the lanes of rows 8-15; a DPP move
+// (rotate by 8 within the 16 lanes of a row group, written to half of the lanes) then swaps
+// what sits in the wrong half between the two.  x, mid, scores and lists, which other
+// workgroups read again, keep plain loads.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const void *p) {
+  const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t *>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+// row within the first eight rows of a tile and byte offset within a line, of this lane's loads
+__device__ __forceinline__ int line_row(int lane) { return lane >> 3; }
+__device__ __forceinline__ int line_byte(int lane) { return (lane & 7) * 16; }
+// ds_bpermute address: the operand's lane (g, r) reads lane 8 (r & 7) + 4 (r >> 3) + g
+__device__ __forceinline__ int line_src(int lane) {
+  const int r = lane & 15, g = lane >> 4;
+  return ((r & 7) * 8 + 4 * (r >> 3) + g) * 4;
+}
+template <int BANKS>   // `src` rotated by 8 lanes within each group of 16, written to the 4-lane banks in BANKS; `old` elsewhere
+__device__ __forceinline__ uint32_t ror8_into(uint32_t old, uint32_t src) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, 0x128, 0xf, BANKS, false);
+}
+__device__ __forceinline__ void line_operands(uint4 lo8, uint4 hi8, int src_bytes, uint4 &f0, uint4 &f1) {
+  const uint32_t l[4] = {lo8.x, lo8.y, lo8.z, lo8.w}, h[4] = {hi8.x, hi8.y, hi8.z, hi8.w};
+  uint32_t a[4], b[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t dl = (uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)l[q]);   // rows 0-7: K-step 2p | 2p + 1
+    const uint32_t dh = (uint32_t)__builtin_amdgcn_ds_bpermute(src_bytes, (int)h[q]);   // rows 8-15: likewise
+    a[q] = ror8_into<0xc>(dl, dh);   // lanes of rows 8-15 take K-step 2p of rows 8-15
+    b[q] = ror8_into<0x3>(dh, dl);   // lanes of rows 0-7 take K-step 2p + 1 of rows 0-7
+  }
+  f0 = make_uint4(a[0], a[1], a[2], a[3]);
+  f1 = make_uint4(b[0], b[1], b[2], b[3]);
+}
+
 // x = hi + lo with hi = bf16(x) and lo = bf16(x - hi); 16-bit patterns in the low halves
 __device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
   hi = bf16_bits(x);
