@@ -188,40 +188,38 @@ __global__ __launch_bounds__(kThreads) void split_x_kernel(const float *__restri
 
 // ------------------------------------------------------------------------------------------------ up
 
-// Router score of this lane's token(s) for expert e, 0 where the mask bit is clear or the token is
-// past the chunk: what the epilogue multiplies with.  Requested when the slot starts (a load issued
-// in the epilogue would return behind the ring's and stop the stream for a memory round trip).
-// The loads are unconditional (a token past the chunk reads the chunk's last token) and nothing
-// is done with what they return until up_scores_finish(), just before the epilogue: a use here
-// would wait for the load, and with it for every weight load of the ring that is in flight.
-template <int NB>
-struct ScoreRaw {
-  float score[acc_tiles(NB)];
-  uint64_t mask[acc_tiles(NB)];
-};
-
-template <int NB>
-__device__ __forceinline__ void up_scores(ScoreRaw<NB> &raw, const LayerView &L, const float *__restrict__ scores,
-                                          const uint64_t *__restrict__ token_mask, int64_t c, int e, int k, int lane) {
-  const int n = lane & 15;
-#pragma unroll
-  for (int q = 0; q < acc_tiles(NB); ++q) {
-    const int t = min(NB == 1 ? (n & 7) : q * 16 + n, k - 1);
-    const int64_t tok = c * k + t;
-    raw.mask[q] = token_mask ? token_mask[tok * L.W + (e >> 6)] : ~0ull;
-    raw.score[q] = scores[tok * L.E + e];
+// Router scores and mask words of the slot's tokens for expert e: what the epilogue multiplies
+// with.  Requested when the slot starts (a load issued in the epilogue would return behind the
+// ring's and stop the stream for a memory round trip), by LDS-direct loads into an area of the
+// wave's own, [score, mask lo, mask hi][token]: loaded into registers they made the epilogue
+// start with a wait for "every load so far" (the compiler cannot count across the loops in
+// between), i.e. for the 16 loads of the ring, already refilled for the next slot - the ring
+// drained once per slot, 8 % of the kernel at k = 8.  The kernel waits for them itself (they are
+// older than the ring's loads, which return in order) and reads them from LDS.
+// The loads are unconditional: a token past the chunk reads the chunk's last token.
+__device__ __forceinline__ void request_scores(uint32_t (&area)[3][64], const LayerView &L,
+                                               const float *__restrict__ scores,
+                                               const uint64_t *__restrict__ token_mask, int64_t c, int e, int k, int lane) {
+  const int64_t tok = c * k + min(lane & 31, k - 1);
+  load_to_lds4(scores + tok * L.E + e, &area[0][0]);
+  if (token_mask) {   // uniform over the launch
+    const uint32_t *m = reinterpret_cast<const uint32_t *>(token_mask + tok * L.W + (e >> 6));
+    load_to_lds4(m, &area[1][0]);
+    load_to_lds4(m + 1, &area[2][0]);
   }
 }
 
+// 0 where the mask bit is clear, the token is past the chunk or the list entry was invalid
 template <int NB>
-__device__ __forceinline__ void up_scores_finish(float (&f_tok)[acc_tiles(NB)], const ScoreRaw<NB> &raw, int e, bool valid,
-                                                 int k, int lane) {
+__device__ __forceinline__ void read_scores(float (&f_tok)[acc_tiles(NB)], const uint32_t (&area)[3][64], bool has_mask,
+                                            int e, bool valid, int k, int lane) {
   const int n = lane & 15;
 #pragma unroll
   for (int q = 0; q < acc_tiles(NB); ++q) {
     const int t = NB == 1 ? (n & 7) : q * 16 + n;
-    const bool on = valid && t < k && ((raw.mask[q] >> (e & 63)) & 1);
-    f_tok[q] = on ? raw.score[q] : 0.0f;
+    const uint32_t word = has_mask ? area[1 + ((e >> 5) & 1)][t] : ~0u;
+    const bool on = valid && t < k && ((word >> (e & 31)) & 1);
+    f_tok[q] = on ? __uint_as_float(area[0][t]) : 0.0f;
   }
 }
 
@@ -272,9 +270,11 @@ __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_til
       const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
       if (NB == 1) {
         // fragment column n: hi for n < 8, lo of token n - 8 for n >= 8
-        *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rr * 4 + wave, g, n) = n < 8 ? vhi : vlo;
+        store_stream(mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rr * 4 + wave, g, n), n < 8 ? vhi : vlo);
       } else if (on) {
         uint16_t *row = midB + (((size_t)c * E + s) * (NB * 8) + q * 16 + n) * 2 * d_e + (rr * 4 + wave) * 16 + 4 * g;
+        // plain stores here: a wave's 8-byte pieces land in 16 different token rows, and partial
+        // lines written around the caches cost more than they save (tree_k32: up kernel + 5.6 %)
         *reinterpret_cast<uint2 *>(row) = vhi;
         *reinterpret_cast<uint2 *>(row + d_e) = vlo;
       }
@@ -292,6 +292,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
     int group, int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits) {
   extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
+  __shared__ uint32_t scoreS[2][4][3][64];   // [slot parity][wave]: see request_scores
+  int spar = 0;
   constexpr int KC = 2048 / NB;   // contraction elements per LDS fill
   constexpr int NA = acc_tiles(NB);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -378,8 +380,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
         for (int q = 0; q < NA; ++q) acc[a][m][q] = f32x4{0.f, 0.f, 0.f, 0.f};
     // the epilogue's scores are requested now: a load issued there would return behind the
     // ring's and stop the stream for a memory round trip
-    ScoreRaw<NB> raw;
-    up_scores<NB>(raw, L, scores, token_mask, c, e, k, lane);
+    request_scores(scoreS[spar][wave], L, scores, token_mask, c, e, k, lane);
 
     for (int kc0 = 0; kc0 < d; kc0 += KC) {
       const int kc_len = min(KC, d - kc0);
@@ -458,7 +459,10 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     }
 
     float f_tok[NA];
-    up_scores_finish<NB>(f_tok, raw, e, e_ok, k, lane);
+    // everything older than the ring's 16 loads has arrived, the scores among it
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");
+    read_scores<NB>(f_tok, scoreS[spar][wave], token_mask != nullptr, e, e_ok, k, lane);
+    spar ^= 1;
     up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits);
 
     if (!has_next) break;
@@ -1007,8 +1011,8 @@ __global__ __launch_bounds__(kThreads) void up_split_kernel(
         split_bf16(on ? f * h : 0.0f, hi, lo);
         packed[q] = n < 8 ? hi : lo;
       }
-      *mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rt, g, n) =
-          make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+      store_stream(mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rt, g, n),
+                   make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16));
     }
   }
 }
@@ -1321,8 +1325,8 @@ __global__ __launch_bounds__(kChipThreads) void up_chip_kernel(
         packed[q] = n < 8 ? hi : lo;
       }
       if (valid)
-        *mid_entry(midB, (size_t)slot * (d_e / 32), j0 >> 4, (j0 >> 2) & 3, n) =
-            make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16);
+        store_stream(mid_entry(midB, (size_t)slot * (d_e / 32), j0 >> 4, (j0 >> 2) & 3, n),
+                     make_uint2(packed[0] | packed[1] << 16, packed[2] | packed[3] << 16));
     }
   }
   if (ROUTE && writer) {   // the chunk's outputs of the router (wave t: token t) and of the union

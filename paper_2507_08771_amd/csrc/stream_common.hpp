@@ -43,6 +43,15 @@ __device__ __forceinline__ uint4 load_stream(const void *p) {
   const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t *>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+// 8 bytes of mid (k <= 8, where the 64 lanes of a store cover 512 contiguous bytes), written once
+// and read once by a later launch: a non-temporal store.  The few
+// stores of the up projection (0.4 % of its bytes at k = 8) cost 8 % of its time as plain stores
+// - the launch is a pure read stream but for them - and half of that as non-temporal ones.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_stream(uint2 *p, uint2 v) {
+  const u32x2_t w = {v.x, v.y};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t *>(p));
+}
 // row within the first eight rows of a tile and byte offset within a line, of this lane's loads
 __device__ __forceinline__ int line_row(int lane) { return lane >> 3; }
 __device__ __forceinline__ int line_byte(int lane) { return (lane & 7) * 16; }
