@@ -238,11 +238,12 @@ int blockffn_reuse_ratio(const uint64_t *token_mask, int64_t n_tok, int64_t seq_
 int blockffn_force_generic(int mode);
 
 /* Measurement helper (no step of the layer): reads `bytes` bytes (rounded down to 16) at buf with
- * plain 128-bit loads and nothing else, so that a benchmark can time what a pure read stream
- * reaches on this device and report the weight-streaming kernels against that measured ceiling
- * as well as against the nominal HBM peak.  buf: device memory, 16-byte aligned.  variant 0..3
+ * 128-bit loads and nothing else, so that a benchmark can time what a pure read stream reaches
+ * on this device and report the weight-streaming kernels against that measured ceiling as well
+ * as against the nominal HBM peak.  buf: device memory, 16-byte aligned.  variant 0..7: variant % 4
  * selects the tile a workgroup reads (1 MiB, 256 KiB, 256 KiB, 64 KiB) and the loads in flight per
- * lane (8, 8, 16, 16).  sink: 4 writable device bytes (written to in practice never). */
+ * lane (8, 8, 16, 16); 0..3 use plain loads, 4..7 non-temporal loads (what the weight streams
+ * use).  sink: 4 writable device bytes (written to in practice never). */
 int blockffn_stream_read(const void *buf, size_t bytes, int32_t variant, uint32_t *sink, void *stream);
 
 /* Bytes of workspace the two FFN entry points need for this shape (0 on invalid arguments). */

@@ -344,7 +344,7 @@ int blockffn_force_generic(int mode) {
 
 int blockffn_stream_read(const void *buf, size_t bytes, int32_t variant, uint32_t *sink, void *stream) {
   if (buf == nullptr || sink == nullptr || !aligned(buf, 16) || !aligned(sink, 4)) return BLOCKFFN_ERR_INVALID;
-  if (variant < 0 || variant > 3) return BLOCKFFN_ERR_INVALID;
+  if (variant < 0 || variant > 7) return BLOCKFFN_ERR_INVALID;
   hipError_t err = launch_stream_read(buf, bytes, variant, sink, static_cast<hipStream_t>(stream));
   return err == hipSuccess ? BLOCKFFN_OK : BLOCKFFN_ERR_LAUNCH;
 }

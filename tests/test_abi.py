@@ -167,7 +167,7 @@ def test_force_generic_modes():
         assert lib.blockffn_force_generic(mode) == B.OK
     assert lib.blockffn_force_generic(2) == B.ERR_INVALID and lib.blockffn_force_generic(-2) == B.ERR_INVALID
     assert lib.blockffn_stream_read(None, 1024, 0, FAKE, None) == B.ERR_INVALID
-    assert lib.blockffn_stream_read(FAKE, 1024, 4, FAKE, None) == B.ERR_INVALID
+    assert lib.blockffn_stream_read(FAKE, 1024, 8, FAKE, None) == B.ERR_INVALID
     assert lib.blockffn_stream_read(FAKE, 1024, 0, None, None) == B.ERR_INVALID
 
 
