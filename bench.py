@@ -267,10 +267,11 @@ def library_dense(w, layers, x, scores, y_ours, R, steps):
 def default_replicas(w):
     """Weight sets the chunks rotate through when --replicas is not given: at least 128, and at
     least 6 GiB of weights.  The persistent workgroups of the up kernel hold about 50 chunks in
-    flight at k = 8 (160 at k = 1): with fewer sets than that, two chunks in flight read the same
-    set and the second finds it in the caches (32 sets gave 81 % of the nominal peak, more than a
-    plain read stream reaches on the same box); from 64 sets on the k = 8 figure is flat at 92 to
-    95 % of the read-stream ceiling measured in the same run."""
+    flight at k = 8 (160 at k = 1).  With plain weight loads, fewer sets than that meant that two
+    chunks in flight read the same set and the second found it in the caches (32 sets gave more
+    than a plain read stream reaches on the same box; flat from 64 sets on).  The weight streams
+    are non-temporal loads now and the k = 8 figure is flat from 16 to 256 sets; the default is
+    kept."""
     set_bytes = w.E * w.expert_bytes
     return max(1, min(max(128, -(-(6 << 30) // set_bytes)), w.n_chunks))
 
