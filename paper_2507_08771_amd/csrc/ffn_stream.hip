@@ -1515,7 +1515,11 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
         const float a = acc[tile][q][j];
         vp[j] = NB == 1 ? a + __shfl_xor(a, 8, kWave) : a;
       }
-      if (writer) *reinterpret_cast<float4 *>(y + (c * k + t) * d + col0 + tile * 16 + 4 * g) = v;
+      if (writer) {
+        float4 *dst = reinterpret_cast<float4 *>(y + (c * k + t) * d + col0 + tile * 16 + 4 * g);
+        if (splits > 1) *dst = v;          // partial sums: the reduce kernel reads them right away
+        else store_stream(dst, v);
+      }
     }
   }
 }

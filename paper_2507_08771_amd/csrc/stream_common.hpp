@@ -52,6 +52,13 @@ __device__ __forceinline__ void store_stream(uint2 *p, uint2 v) {
   const u32x2_t w = {v.x, v.y};
   __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t *>(p));
 }
+// 16 bytes of y, written once per launch and not read by it: non-temporal as well (`spec_k8`:
+// streaming down kernel - 3.6 %).
+typedef float f32x4_nt_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_stream(float4 *p, float4 v) {
+  const f32x4_nt_t w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<f32x4_nt_t *>(p));
+}
 // row within the first eight rows of a tile and byte offset within a line, of this lane's loads
 __device__ __forceinline__ int line_row(int lane) { return lane >> 3; }
 __device__ __forceinline__ int line_byte(int lane) { return (lane & 7) * 16; }
