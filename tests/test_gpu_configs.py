@@ -183,3 +183,25 @@ def test_layer_stack_replayed_as_a_graph():
             assert torch.equal(b.scores, want[l][1]) and torch.equal(b.active_idx, want[l][2])
         # the counts are added to on every run (the capture itself launches nothing)
         assert torch.equal(bufs[0].stats, want[0][3] * (rep + 2))
+
+
+@pytest.mark.parametrize("variant", range(8))
+def test_read_stream_probe_runs_in_every_variant(variant):
+    """blockffn_stream_read (the benchmark's ceiling measurement): every launch shape, plain and
+    non-temporal loads, on a buffer whose size is no multiple of a tile; it only reads (the buffer
+    and the sink keep their contents), and a stream of 1 GiB must run at a rate that is a memory
+    rate at all (above 1 TB/s, below the 8 TB/s rating)."""
+    n = (1 << 30) + 4096 + 16
+    buf = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+    sink = torch.full((1,), 123, dtype=torch.int32, device="cuda")
+    B.blockffn_stream_read(buf, variant, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    B.blockffn_stream_read(buf, variant, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    rate = n / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    assert 1.0 < rate < 8.0, rate
+    assert int(sink.item()) == 123
+    assert int(buf[:4096].sum().item()) == 7 * 4096 and int(buf[-1].item()) == 7
