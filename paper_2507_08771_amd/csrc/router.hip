@@ -1,20 +1,23 @@
 // Router of the BlockFFN layer (Eq. 3): A^0 = W_router^T x + b, A^1 = ReLU(A^0),
 // A = RMSNorm(A^1), plus the per-token activation mask (bit set iff A^0 > 0).
 //
-// One workgroup (4 waves) takes a tile of up to 8 consecutive tokens of one chunk.  The sign of
-// A^0 decides a mask bit, so every product is an exact fp32 product and every sum is fp32.
+// The sign of A^0 decides a mask bit, so every product is an exact fp32 product and every sum is
+// fp32.
 //
-// router_mfma_kernel (bf16 weights, enough token tiles to fill the chip): x is carried as three
-// bf16 pieces that add up to the fp32 value exactly, and the matrix cores do the contraction.
+// router_mfma_kernel, router_mfma8_kernel (bf16 weights, enough tokens to fill the chip): x is
+// carried as three bf16 pieces that add up to the fp32 value exactly, and the matrix cores do the
+// contraction; a workgroup (4 waves) takes tiles of 16 tokens, or of 8 tokens of one chunk.
 // router_kernel (fp32 weights, and launches of tens of tiles, where blockIdx.y spreads the expert
 // groups over workgroups; a handful of tiles take router_expert_kernel, one workgroup per
-// expert and share of the tile's tokens): vector ALUs.  Each lane keeps its 8 columns of the 8 tokens in
-// registers (64 VGPRs) and walks over the experts: one 128-bit load of a W_router row segment
-// feeds 64 fp32 FMAs; partial sums of 8 experts x 8 tokens are reduced across the wave with a
-// 63-step reduce-scatter (lane q ends with entry q).
-// Both leave the four waves' partial sums in LDS for the same finishing step (bias, mask ballot,
-// RMSNorm, gain).
+// expert and share of the tile's tokens): vector ALUs, a workgroup per tile of up to 8 tokens of
+// one chunk.  Each lane keeps its 8 columns of the 8 tokens in registers (64 VGPRs) and walks
+// over the experts: one 128-bit load of a W_router row segment feeds 64 fp32 FMAs; partial sums
+// of 8 experts x 8 tokens are reduced across the wave with a 63-step reduce-scatter (lane q ends
+// with entry q).
+// All of them leave the four waves' partial sums in LDS for the same finishing step (bias, mask
+// ballot, RMSNorm, gain).
 #include "common.hpp"
+#include "stream_common.hpp"
 
 namespace blockffn {
 
@@ -48,16 +51,18 @@ __device__ __forceinline__ float reduce_scatter64(float (&v)[64], int lane) {
   return v[0];
 }
 
-// The four waves' partial sums part[wave][expert][token] of a tile of nt tokens starting at
-// token tok0 become A^0 (+ bias), the mask words and the RMSNorm'ed scores.  Each wave finishes
-// tokens wave, wave + 4: lanes run over experts, one mask word at a time.
-template <int ROWS>
-__device__ __forceinline__ void finish_tile(const LayerView &L, int layer, const float (&part)[4][ROWS][kTok],
-                                            int64_t tok0, int nt, float *__restrict__ scores,
+// The four waves' partial sums part[wave][expert][token] of a tile of NT tokens starting at token
+// tok0 become A^0 (+ bias), the mask words and the RMSNorm'ed scores, for the tokens whose bit is
+// set in `which` (all of them tokens of `layer`).  Each wave finishes tokens wave, wave + 4, ...:
+// lanes run over experts, one mask word at a time.
+template <int ROWS, int NT>
+__device__ __forceinline__ void finish_tile(const LayerView &L, int layer, const float (&part)[4][ROWS][NT],
+                                            int64_t tok0, uint32_t which, float *__restrict__ scores,
                                             uint64_t *__restrict__ token_mask, float *__restrict__ preact) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int E = L.E;
-  for (int t = wave; t < nt; t += 4) {
+  for (int t = wave; t < NT; t += 4) {
+    if (!((which >> t) & 1u)) continue;   // uniform over the wave
     const int64_t tok = tok0 + t;
     float a1[kMaxMaskWords];
     float sumsq = 0.0f;
@@ -176,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void router_kernel(LayerView L, const int
     return;
   }
 
-  finish_tile(L, layer, part, tok0, nt, scores, token_mask, preact);
+  finish_tile(L, layer, part, tok0, (1u << nt) - 1u, scores, token_mask, preact);
 }
 
 // A handful of token tiles (one chunk walking through a layer stack): one workgroup per (tile,
@@ -235,26 +240,205 @@ __global__ __launch_bounds__(kThreads) void router_expert_kernel(LayerView L, co
   }
 }
 
-// bf16 weights, many token tiles: the same contraction on the matrix cores without giving up
-// fp32 products.  An fp32 x is the exact sum of three bf16 numbers (24 significant bits in
-// three pieces of 8: h = bf16(x), m = bf16(x - h), l = x - h - m), and a bf16 piece times a bf16
-// weight is exact in fp32, so three MFMA columns per token accumulate in fp32 exactly the
-// products the vector ALUs would: only the order of the fp32 additions differs.  The sign of A^0
-// still decides the mask bit, and it is still backed by full fp32 products.
+// bf16 weights, many tokens: the same contraction on the matrix cores without giving up fp32
+// products.  An fp32 x is the exact sum of three bf16 numbers (24 significant bits in three
+// pieces of 8: h = bf16(x), m = bf16(x - h), l = x - h - m), and a bf16 piece times a bf16
+// weight is exact in fp32, so three MFMAs per 16 tokens (B operands: the 16 tokens' h, their m,
+// their l) accumulate in fp32 exactly the products the vector ALUs would: only the order of the
+// fp32 additions differs.  The sign of A^0 still decides the mask bit, and it is still backed by
+// full fp32 products.
 //
-// One workgroup = one tile of up to 8 tokens of one chunk; its four waves take the K-steps
-// (32 contraction elements) w, w + 4, ... .  Per K-step a wave loads RT fragments of W_router
-// (16 experts x 32 elements each), builds two B fragments from x in registers (columns 0-7: h of
-// tokens 0-7, 8-15: m, 16-23: l, 24-31: zero) and issues 2 * RT MFMAs.  KB K-steps are loaded
-// together so that their memory latency is paid once.  At the end h + m + l columns are added
-// inside the wave and the four waves meet in the LDS layout the finishing step reads.
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
+// Tiles of 16 tokens (the 16 columns of an MFMA) are cut from the launch's token stream
+// (tiles_per_chunk = 0: tile j holds tokens 16 j .. 16 j + 15 whatever chunks they belong to, so
+// that short chunks - k = 1: one token each - still fill the columns and pull the router matrix
+// once per 16 tokens) or from each chunk (tile j is tile j mod tiles_per_chunk of chunk
+// j / tiles_per_chunk; the launcher's choice when the chunks may be of different layers and k is
+// no multiple of 16).  A workgroup takes T consecutive tiles; its four waves take the pairs of
+// K-steps (64 contraction elements) w, w + 4, ... .  Per pair a wave loads RT tiles of W_router
+// (16 experts x 64 elements each) as whole 128-byte lines - 8 lanes per expert row, two registers
+// per tile, which a CU takes in nearly twice as fast as the 64-byte halves of operand order - and
+// rearranges them into the two K-steps' A operands in registers (line_operands); lane (n, g)
+// loads elements 8 g .. 8 g + 7 of token n of each K-step, splits them and issues 3 * RT MFMAs
+// per tile and K-step.  KP pairs are loaded together so that their memory latency is paid once.
+// At the end a lane adds its h, m and l sums and the four waves meet in the LDS layout the
+// finishing step reads.
+// The tokens of a workgroup may belong to chunks of different layers (different router
+// matrices): the workgroup then makes one pass per distinct layer, with the other tokens'
+// columns zero, and finishes after each pass the tokens of that layer.  A token's sums are the
+// same whatever its column and whoever shares its tile.
+constexpr int kTile = 16;   // tokens per tile of the MFMA kernel
 
-__device__ __forceinline__ uint32_t bf16_bits_of(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
+template <int RT, int KP, int T>
+__global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
+                                                               const float *__restrict__ x, int k, int64_t n_chunks,
+                                                               int tiles_per_chunk, float *__restrict__ scores,
+                                                               uint64_t *__restrict__ token_mask,
+                                                               float *__restrict__ preact) {
+  static_assert(T * kTile <= 32, "one bit per token of the workgroup");
+  __shared__ float part[T][4][RT * 16][kTile];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, g = lane >> 4;
+  const int lsrc = line_src(lane);
+  const int d = L.d, E = L.E;
+  const int64_t n_tok = n_chunks * k;
+  int64_t tile_tok0[T];   // first token of each tile
+  const float *xrow[T];
+  int lay[T];   // layer of this lane's token of each tile, -1 where the tile has no such token
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    const int64_t tile = (int64_t)blockIdx.x * T + tt;
+    int64_t c;
+    bool in;
+    if (tiles_per_chunk > 0) {
+      c = tile / tiles_per_chunk;
+      const int i0 = (int)(tile - c * tiles_per_chunk) * kTile;
+      tile_tok0[tt] = c * k + i0;
+      in = c < n_chunks && i0 + n < k;
+    } else {
+      tile_tok0[tt] = tile * kTile;
+      in = tile_tok0[tt] + n < n_tok;
+      c = (tile_tok0[tt] + n) / k;
+    }
+    xrow[tt] = x + (in ? tile_tok0[tt] + n : 0) * d;
+    lay[tt] = in ? clamp_layer(chunk_layer, c, L.n_layers) : -1;
+  }
+  // bit i: token i of the workgroup is still to do (lanes 0-15 hold tokens 0-15 of a tile)
+  uint32_t pend = 0;
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) pend |= (uint32_t)(__ballot(lay[tt] >= 0) & 0xffffu) << (tt * kTile);
+  const int n_pairs = (d + 63) / 64;
 
+  while (pend) {
+    // this pass: the layer of the first token still to do and every such token of the same layer
+    const int first = __builtin_ctz(pend);
+    int layer = 0;
+    int64_t t_first = 0;
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+      const int v = __builtin_amdgcn_readlane(lay[tt], first & (kTile - 1));
+      layer = (first / kTile == tt) ? v : layer;
+      t_first = (first / kTile == tt) ? tile_tok0[tt] + (first & (kTile - 1)) : t_first;
+    }
+    uint32_t act = 0;
+    bool tok_ok[T];
+    const float *xr[T];   // a lane without a token in this pass reads the first token's row again: no memory traffic of its own
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+      tok_ok[tt] = ((pend >> (tt * kTile + n)) & 1u) && lay[tt] == layer;
+      act |= (uint32_t)(__ballot(tok_ok[tt]) & 0xffffu) << (tt * kTile);
+      xr[tt] = tok_ok[tt] ? xrow[tt] : x + t_first * d;
+    }
+    pend &= ~act;
+    const uint16_t *wr = static_cast<const uint16_t *>(L.w_router) + (size_t)layer * E * d;
+
+    f32x4 acc[T][RT][3];   // sums of the h, m and l pieces
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc) acc[tt][rt][pc] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int p0 = wave; p0 < n_pairs; p0 += 4 * KP) {
+      uint4 a[KP][RT][2];            // per tile: the lines of experts 0-7 and of experts 8-15
+      float4 xa[KP][2][T], xb[KP][2][T];
+      bool xok[KP][2];
+      // No load sits under a condition (a branch around a load makes the compiler wait for every
+      // load before it at the join): past the end of a row (d is a multiple of 8: a lane's 8
+      // elements are all in or all out) a lane reads column 0 instead, of W_router - a finite weight
+      // times a zero piece of x adds nothing, and a weight that is not finite has spoilt its
+      // expert's sum at column 0 already - and of x, which is then replaced by zero.
+#pragma unroll
+      for (int u = 0; u < KP; ++u) {
+        const int pair = p0 + 4 * u;
+        const int wcol = pair * 64 + (lane & 7) * 8;
+        const int wc = wcol < d ? wcol : 0;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int row = min(rt * 16 + hh * 8 + line_row(lane), E - 1);   // rows at or above E repeat the last one; never read back
+            a[u][rt][hh] = *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + wc);
+          }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int col = (pair * 2 + h) * 32 + g * 8;
+          xok[u][h] = col < d;
+#pragma unroll
+          for (int tt = 0; tt < T; ++tt) {
+            const float4 *px = reinterpret_cast<const float4 *>(xr[tt] + (xok[u][h] ? col : 0));
+            xa[u][h][tt] = px[0];
+            xb[u][h][tt] = px[1];
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < KP; ++u) {
+        uint4 bh[2][T], bm[2][T], bl[2][T];   // B operands of the pair's two K-steps: the h, m and l pieces
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int tt = 0; tt < T; ++tt) {
+            const bool ok = tok_ok[tt] && xok[u][h];
+            const float xv[8] = {xa[u][h][tt].x, xa[u][h][tt].y, xa[u][h][tt].z, xa[u][h][tt].w,
+                                 xb[u][h][tt].x, xb[u][h][tt].y, xb[u][h][tt].z, xb[u][h][tt].w};
+            uint32_t hp[8], mp[8], lp[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              const float v = ok ? xv[q] : 0.0f;
+              hp[q] = bf16_bits(v);
+              const float r1 = v - __uint_as_float(hp[q] << 16);
+              mp[q] = bf16_bits(r1);
+              const float r2 = r1 - __uint_as_float(mp[q] << 16);
+              lp[q] = bf16_bits(r2);
+            }
+            bh[h][tt] = make_uint4(hp[0] | hp[1] << 16, hp[2] | hp[3] << 16, hp[4] | hp[5] << 16, hp[6] | hp[7] << 16);
+            bm[h][tt] = make_uint4(mp[0] | mp[1] << 16, mp[2] | mp[3] << 16, mp[4] | mp[5] << 16, mp[6] | mp[7] << 16);
+            bl[h][tt] = make_uint4(lp[0] | lp[1] << 16, lp[2] | lp[3] << 16, lp[4] | lp[5] << 16, lp[6] | lp[7] << 16);
+          }
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          uint4 f[2];   // A operands of the pair's two K-steps
+          line_operands(a[u][rt][0], a[u][rt][1], lsrc, f[0], f[1]);
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int tt = 0; tt < T; ++tt) {
+              acc[tt][rt][0] = mfma16(f[h], bh[h][tt], acc[tt][rt][0]);
+              acc[tt][rt][1] = mfma16(f[h], bm[h][tt], acc[tt][rt][1]);
+              acc[tt][rt][2] = mfma16(f[h], bl[h][tt], acc[tt][rt][2]);
+            }
+        }
+      }
+    }
+    // accumulator element q of lane (n, g) is expert rt * 16 + 4 * g + q, token n of the tile
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          part[tt][wave][rt * 16 + 4 * g + q][n] = (acc[tt][rt][0][q] + acc[tt][rt][1][q]) + acc[tt][rt][2][q];
+    __syncthreads();
+#pragma unroll
+    for (int tt = 0; tt < T; ++tt) {
+      const uint32_t which = (act >> (tt * kTile)) & 0xffffu;
+      if (which) finish_tile(L, layer, part[tt], tile_tok0[tt], which, scores, token_mask, preact);
+    }
+    if (pend) __syncthreads();   // the next pass writes part again
+  }
+}
+
+// Chunks of fewer than 16 tokens that may be of different layers: a 16-token tile would be part
+// empty, or span router matrices and take a pass per layer, and measured slower.  For them a
+// tile is up to 8 tokens of one chunk and a token's three pieces sit in two B fragments (columns
+// 0-7: h of tokens 0-7, 8-15: m; second fragment 0-7: l, rest zero), 2 * RT MFMAs per K-step.
+// The four waves take the K-steps w, w + 4, ... (KB of them loaded together), the weights are
+// loaded in operand order, and T tiles of one chunk share a pass over the matrix.  At the end
+// the h + m + l columns are added inside the wave.
 template <int RT, int KB, int T>
-__global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
+__global__ __launch_bounds__(kThreads) void router_mfma8_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
                                                                const float *__restrict__ x, int k,
                                                                int tiles_per_chunk, float *__restrict__ scores,
                                                                uint64_t *__restrict__ token_mask,
@@ -279,11 +463,11 @@ __global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, cons
   }
   const int n_ksteps = (d + 31) / 32;
 
-  f32x4_t acc[T][RT][2];
+  f32x4 acc[T][RT][2];
 #pragma unroll
   for (int tt = 0; tt < T; ++tt)
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) acc[tt][rt][0] = acc[tt][rt][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < RT; ++rt) acc[tt][rt][0] = acc[tt][rt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   for (int ks0 = wave; ks0 < n_ksteps; ks0 += 4 * KB) {
     uint4 a[KB][RT];
@@ -313,11 +497,11 @@ __global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, cons
         uint32_t p0[8], p1[8];   // this lane's piece for the first and for the second B fragment
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-          const uint32_t h = bf16_bits_of(xv[q]);
+          const uint32_t h = bf16_bits(xv[q]);
           const float r1 = xv[q] - __uint_as_float(h << 16);
-          const uint32_t m = bf16_bits_of(r1);
+          const uint32_t m = bf16_bits(r1);
           const float r2 = r1 - __uint_as_float(m << 16);
-          const uint32_t l = bf16_bits_of(r2);
+          const uint32_t l = bf16_bits(r2);
           p0[q] = tok_ok[tt] ? (n < 8 ? h : m) : 0u;
           p1[q] = (tok_ok[tt] && n < 8) ? l : 0u;
         }
@@ -326,9 +510,9 @@ __global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, cons
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
           acc[tt][rt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8_t, a[u][rt]), __builtin_bit_cast(bf16x8_t, b0), acc[tt][rt][0], 0, 0, 0);
+              __builtin_bit_cast(bf16x8, a[u][rt]), __builtin_bit_cast(bf16x8, b0), acc[tt][rt][0], 0, 0, 0);
           acc[tt][rt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8_t, a[u][rt]), __builtin_bit_cast(bf16x8_t, b1), acc[tt][rt][1], 0, 0, 0);
+              __builtin_bit_cast(bf16x8, a[u][rt]), __builtin_bit_cast(bf16x8, b1), acc[tt][rt][1], 0, 0, 0);
         }
       }
     }
@@ -349,7 +533,8 @@ __global__ __launch_bounds__(kThreads) void router_mfma_kernel(LayerView L, cons
 #pragma unroll
   for (int tt = 0; tt < T; ++tt) {
     const int t0 = (tile0 + tt) * kTok;
-    if (t0 < k) finish_tile(L, layer, part[tt], c * (int64_t)k + t0, min(kTok, k - t0), scores, token_mask, preact);
+    if (t0 < k)
+      finish_tile(L, layer, part[tt], c * (int64_t)k + t0, (1u << min(kTok, k - t0)) - 1u, scores, token_mask, preact);
   }
 }
 
@@ -455,18 +640,41 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
   dim3 grid((unsigned)blocks);
   if (wdtype == BLOCKFFN_BF16) {
     const int rt = (L.E + 15) / 16;
-#define BLOCKFFN_ROUTER(RT, KB, T)                                                                     \
-  hipLaunchKernelGGL((router_mfma_kernel<RT, KB, T>), dim3((unsigned)(n_chunks * ((tiles + T - 1) / T))), block, 0, \
+    const bool one_layer = chunk_layer == nullptr || L.n_layers == 1;
+    if (!one_layer && k < kTile) {
+      // short chunks of possibly different layers: tiles of 8 tokens of one chunk
+#define BLOCKFFN_ROUTER8(RT, KB, T)                                                                        \
+  hipLaunchKernelGGL((router_mfma8_kernel<RT, KB, T>), dim3((unsigned)(n_chunks * ((tiles + T - 1) / T))), block, 0, \
                      s, L, chunk_layer, x, k, tiles, scores, token_mask, preact)
-    // Every workgroup pulls the whole router matrix of its chunk's layer through its L1 (512 KiB at
-    // E = 128, d = 2048, against 64 KiB of x per 8 tokens): with several token tiles per chunk a
-    // workgroup takes 2 or 4 of them per pass over the matrix, as many as the accumulators allow.
-    // (only while that still leaves four workgroups per CU)
-    const bool multi = tiles >= 2 && blocks / 2 >= 1024, quad = tiles >= 4 && blocks / 4 >= 1024;
-    if (rt <= 1) { if (quad) BLOCKFFN_ROUTER(1, 4, 4); else if (multi) BLOCKFFN_ROUTER(1, 4, 2); else BLOCKFFN_ROUTER(1, 4, 1); }
-    else if (rt <= 2) { if (quad) BLOCKFFN_ROUTER(2, 2, 4); else if (multi) BLOCKFFN_ROUTER(2, 2, 2); else BLOCKFFN_ROUTER(2, 2, 1); }
-    else if (rt <= 4) { if (quad) BLOCKFFN_ROUTER(4, 1, 4); else if (multi) BLOCKFFN_ROUTER(4, 2, 2); else BLOCKFFN_ROUTER(4, 2, 1); }
-    else if (rt <= 8) { if (multi) BLOCKFFN_ROUTER(8, 1, 2); else BLOCKFFN_ROUTER(8, 2, 1); }
+      const bool multi = tiles >= 2 && blocks / 2 >= 1024;   // two tiles per pass while four workgroups per CU remain
+      if (rt <= 1) { if (multi) BLOCKFFN_ROUTER8(1, 4, 2); else BLOCKFFN_ROUTER8(1, 4, 1); }
+      else if (rt <= 2) { if (multi) BLOCKFFN_ROUTER8(2, 2, 2); else BLOCKFFN_ROUTER8(2, 2, 1); }
+      else if (rt <= 4) { if (multi) BLOCKFFN_ROUTER8(4, 2, 2); else BLOCKFFN_ROUTER8(4, 2, 1); }
+      else if (rt <= 8) { if (multi) BLOCKFFN_ROUTER8(8, 1, 2); else BLOCKFFN_ROUTER8(8, 2, 1); }
+      else BLOCKFFN_ROUTER8(16, 1, 1);
+#undef BLOCKFFN_ROUTER8
+      return hipGetLastError();
+    }
+    // Tiles of 16 tokens, of the token stream where every chunk is of the same layer for sure or
+    // where they are the chunks' own tiles anyway; else tiles of each chunk: a tile across chunks
+    // of different layers takes one pass over a router matrix per layer, one after the other.
+    const bool stream_tiles = one_layer || k % kTile == 0;
+    const int tiles16 = (k + kTile - 1) / kTile;
+    const int64_t n_tiles = stream_tiles ? (n_chunks * k + kTile - 1) / kTile : n_chunks * tiles16;
+    const int tpc = stream_tiles ? 0 : tiles16;
+#define BLOCKFFN_ROUTER(RT, KP, T)                                                                                 \
+  hipLaunchKernelGGL((router_mfma_kernel<RT, KP, T>), dim3((unsigned)((n_tiles + T - 1) / T)), block, 0, s, L, chunk_layer, \
+                     x, k, n_chunks, tpc, scores, token_mask, preact)
+    // Every workgroup pulls the whole router matrix of its tokens' layer through its L1 (512 KiB at
+    // E = 128, d = 2048, against 128 KiB of x per 16 tokens): up to 64 experts a workgroup takes 2
+    // tiles per pass over the matrix (the accumulators allow it), where tiles that follow each other
+    // are of one layer (for sure, or because the chunk has two) and the launch still has four
+    // workgroups per CU.
+    const bool two = (one_layer || tiles16 >= 2) && n_tiles / 2 >= 1024;
+    if (rt <= 1) { if (two) BLOCKFFN_ROUTER(1, 2, 2); else BLOCKFFN_ROUTER(1, 2, 1); }
+    else if (rt <= 2) { if (two) BLOCKFFN_ROUTER(2, 1, 2); else BLOCKFFN_ROUTER(2, 1, 1); }
+    else if (rt <= 4) { if (two) BLOCKFFN_ROUTER(4, 1, 2); else BLOCKFFN_ROUTER(4, 1, 1); }
+    else if (rt <= 8) BLOCKFFN_ROUTER(8, 1, 1);
     else BLOCKFFN_ROUTER(16, 1, 1);
 #undef BLOCKFFN_ROUTER
   } else

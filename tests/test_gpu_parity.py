@@ -255,15 +255,18 @@ def test_full_size_spec_k8_sampled_chunks():
 
 
 @pytest.mark.parametrize("E", [5, 16, 31, 64, 100, 128, 130, 256])
-@pytest.mark.parametrize("k", [1, 8, 11, 20, 28])
+@pytest.mark.parametrize("k", [1, 8, 11, 16, 20, 28, 48])
 def test_router_with_many_token_tiles(E, k):
-    """Enough token tiles that the router takes its many-tile kernel (the matrix-core one for bf16
-    weights), every count of 16-expert row tiles, a hidden size that ends in a partial K-step
-    (520 = 16 * 32 + 8), gain and three weight sets; scores, masks and pre-activations against the
-    oracle's router.  k = 20 and 28 come with enough chunks that a workgroup takes two or four
-    token tiles of a chunk per pass over the router matrix, the last one ragged or past the chunk."""
+    """Enough token tiles that the router takes its many-tile kernels (the matrix-core ones for bf16
+    weights), every count of 16-expert row tiles, a hidden size that ends in a partial pair of
+    K-steps (520 = 8 * 64 + 8), gain and three weight sets that the chunks rotate through; scores,
+    masks and pre-activations against the oracle's router.  k < 16: tiles of 8 tokens of a chunk.
+    k >= 16: tiles of 16 tokens, with enough chunks that (up to 64 experts) a workgroup takes two
+    tiles per pass over the router matrix: the two of a chunk, the second ragged (k = 20, 28);
+    of two chunks, i.e. of two layers and two passes (k = 16); of one chunk or of two (k = 48)."""
     import oracle
-    d, C, n_layers = 520, (300 if k <= 11 else 1500), 3
+    d, n_layers = 520, 3
+    C = {1: 300, 8: 300, 11: 300, 16: 2100, 20: 1500, 28: 1500, 48: 700}[k]
     w = wl.Workload("t", d=d, E=E, d_e=8, wdtype="bf16", gated=False, k=k, n_chunks=C, sigma=0.3, seed=E * 31 + k)
     layers = wl.make_layers(w, n_layers, gain=True)
     cl = wl.make_chunk_layer(w, n_layers)
