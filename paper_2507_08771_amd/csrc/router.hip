@@ -4,9 +4,9 @@
 // The sign of A^0 decides a mask bit, so every product is an exact fp32 product and every sum is
 // fp32.
 //
-// router_mfma_kernel, router_mfma8_kernel (bf16 weights, enough tokens to fill the chip): x is
-// carried as three bf16 pieces that add up to the fp32 value exactly, and the matrix cores do the
-// contraction; a workgroup (4 waves) takes tiles of 16 tokens, or of 8 tokens of one chunk.
+// router_mfma_kernel (bf16 weights, enough tokens to fill the chip): x is carried as three bf16
+// pieces that add up to the fp32 value exactly, and the matrix cores do the contraction; a
+// workgroup (4 waves) takes tiles of 16 tokens.
 // router_kernel (fp32 weights, and launches of tens of tiles, where blockIdx.y spreads the expert
 // groups over workgroups; a handful of tiles take router_expert_kernel, one workgroup per
 // expert and share of the tile's tokens): vector ALUs, a workgroup per tile of up to 8 tokens of
@@ -354,13 +354,6 @@ __global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel
         const int wcol = pair * 64 + (lane & 7) * 8;
         const int wc = wcol < d ? wcol : 0;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-          for (int hh = 0; hh < 2; ++hh) {
-            const int row = min(rt * 16 + hh * 8 + line_row(lane), E - 1);   // rows at or above E repeat the last one; never read back
-            a[u][rt][hh] = *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + wc);
-          }
-#pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int col = (pair * 2 + h) * 32 + g * 8;
           xok[u][h] = col < d;
@@ -371,7 +364,17 @@ __global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel
             xb[u][h][tt] = px[1];
           }
         }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int row = min(rt * 16 + hh * 8 + line_row(lane), E - 1);   // rows at or above E repeat the last one; never read back
+            a[u][rt][hh] = *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + wc);
+          }
       }
+      // every load of the iteration is in flight before the first is used: left alone, the
+      // scheduler (short of registers) sinks each tile's loads to its use and waits for them there
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < KP; ++u) {
         uint4 bh[2][T], bm[2][T], bl[2][T];   // B operands of the pair's two K-steps: the h, m and l pieces
@@ -427,114 +430,6 @@ __global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel
       if (which) finish_tile(L, layer, part[tt], tile_tok0[tt], which, scores, token_mask, preact);
     }
     if (pend) __syncthreads();   // the next pass writes part again
-  }
-}
-
-// Chunks of fewer than 16 tokens that may be of different layers: a 16-token tile would be part
-// empty, or span router matrices and take a pass per layer, and measured slower.  For them a
-// tile is up to 8 tokens of one chunk and a token's three pieces sit in two B fragments (columns
-// 0-7: h of tokens 0-7, 8-15: m; second fragment 0-7: l, rest zero), 2 * RT MFMAs per K-step.
-// The four waves take the K-steps w, w + 4, ... (KB of them loaded together), the weights are
-// loaded in operand order, and T tiles of one chunk share a pass over the matrix.  At the end
-// the h + m + l columns are added inside the wave.
-template <int RT, int KB, int T>
-__global__ __launch_bounds__(kThreads) void router_mfma8_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
-                                                               const float *__restrict__ x, int k,
-                                                               int tiles_per_chunk, float *__restrict__ scores,
-                                                               uint64_t *__restrict__ token_mask,
-                                                               float *__restrict__ preact) {
-  __shared__ float part[T][4][RT * 16][kTok];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = lane & 15, g = lane >> 4;
-  const int groups = (tiles_per_chunk + T - 1) / T;   // T token tiles of one chunk per workgroup
-  const int64_t c = blockIdx.x / groups;
-  const int tile0 = (int)(blockIdx.x % groups) * T;
-  const int layer = clamp_layer(chunk_layer, c, L.n_layers);
-  const int d = L.d, E = L.E;
-  const uint16_t *wr = static_cast<const uint16_t *>(L.w_router) + (size_t)layer * E * d;
-  const int tok = n & 7;
-  bool tok_ok[T];
-  const float *xrow[T];
-#pragma unroll
-  for (int tt = 0; tt < T; ++tt) {
-    const int t0 = (tile0 + tt) * kTok;
-    tok_ok[tt] = t0 + tok < k;
-    xrow[tt] = x + (c * (int64_t)k + (tok_ok[tt] ? t0 + tok : 0)) * d;
-  }
-  const int n_ksteps = (d + 31) / 32;
-
-  f32x4 acc[T][RT][2];
-#pragma unroll
-  for (int tt = 0; tt < T; ++tt)
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) acc[tt][rt][0] = acc[tt][rt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  for (int ks0 = wave; ks0 < n_ksteps; ks0 += 4 * KB) {
-    uint4 a[KB][RT];
-    float4 xa[KB][T], xb[KB][T];
-#pragma unroll
-    for (int u = 0; u < KB; ++u) {
-      const int col = (ks0 + 4 * u) * 32 + g * 8;   // d is a multiple of 8: a lane's 8 elements are all in or all out
-      const bool ok = col < d;
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        const int row = min(rt * 16 + n, E - 1);   // rows at or above E repeat the last one; never read back
-        a[u][rt] = ok ? *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + col) : make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int tt = 0; tt < T; ++tt) {
-        const float4 *px = reinterpret_cast<const float4 *>(xrow[tt] + col);
-        xa[u][tt] = ok ? px[0] : make_float4(0.f, 0.f, 0.f, 0.f);
-        xb[u][tt] = ok ? px[1] : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < KB; ++u) {
-#pragma unroll
-      for (int tt = 0; tt < T; ++tt) {
-        const float xv[8] = {xa[u][tt].x, xa[u][tt].y, xa[u][tt].z, xa[u][tt].w,
-                             xb[u][tt].x, xb[u][tt].y, xb[u][tt].z, xb[u][tt].w};
-        uint32_t p0[8], p1[8];   // this lane's piece for the first and for the second B fragment
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const uint32_t h = bf16_bits(xv[q]);
-          const float r1 = xv[q] - __uint_as_float(h << 16);
-          const uint32_t m = bf16_bits(r1);
-          const float r2 = r1 - __uint_as_float(m << 16);
-          const uint32_t l = bf16_bits(r2);
-          p0[q] = tok_ok[tt] ? (n < 8 ? h : m) : 0u;
-          p1[q] = (tok_ok[tt] && n < 8) ? l : 0u;
-        }
-        const uint4 b0 = make_uint4(p0[0] | p0[1] << 16, p0[2] | p0[3] << 16, p0[4] | p0[5] << 16, p0[6] | p0[7] << 16);
-        const uint4 b1 = make_uint4(p1[0] | p1[1] << 16, p1[2] | p1[3] << 16, p1[4] | p1[5] << 16, p1[6] | p1[7] << 16);
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-          acc[tt][rt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8, a[u][rt]), __builtin_bit_cast(bf16x8, b0), acc[tt][rt][0], 0, 0, 0);
-          acc[tt][rt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(bf16x8, a[u][rt]), __builtin_bit_cast(bf16x8, b1), acc[tt][rt][1], 0, 0, 0);
-        }
-      }
-    }
-  }
-  // accumulator element q of lane (n, g) is expert rt * 16 + 4 * g + q, column n: token n & 7,
-  // piece h (n < 8) or m (n >= 8) in the first fragment, l (n < 8) in the second
-#pragma unroll
-  for (int tt = 0; tt < T; ++tt)
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float hm = acc[tt][rt][0][q] + __shfl_xor(acc[tt][rt][0][q], 8, kWave);
-        const int i = rt * 16 + 4 * g + q;
-        if (n < 8) part[tt][wave][i][n] = hm + acc[tt][rt][1][q];
-      }
-  __syncthreads();
-#pragma unroll
-  for (int tt = 0; tt < T; ++tt) {
-    const int t0 = (tile0 + tt) * kTok;
-    if (t0 < k)
-      finish_tile(L, layer, part[tt], c * (int64_t)k + t0, (1u << min(kTok, k - t0)) - 1u, scores, token_mask, preact);
   }
 }
 
@@ -641,20 +536,6 @@ hipError_t launch_router(const LayerView &L, int wdtype, const int32_t *chunk_la
   if (wdtype == BLOCKFFN_BF16) {
     const int rt = (L.E + 15) / 16;
     const bool one_layer = chunk_layer == nullptr || L.n_layers == 1;
-    if (!one_layer && k < kTile) {
-      // short chunks of possibly different layers: tiles of 8 tokens of one chunk
-#define BLOCKFFN_ROUTER8(RT, KB, T)                                                                        \
-  hipLaunchKernelGGL((router_mfma8_kernel<RT, KB, T>), dim3((unsigned)(n_chunks * ((tiles + T - 1) / T))), block, 0, \
-                     s, L, chunk_layer, x, k, tiles, scores, token_mask, preact)
-      const bool multi = tiles >= 2 && blocks / 2 >= 1024;   // two tiles per pass while four workgroups per CU remain
-      if (rt <= 1) { if (multi) BLOCKFFN_ROUTER8(1, 4, 2); else BLOCKFFN_ROUTER8(1, 4, 1); }
-      else if (rt <= 2) { if (multi) BLOCKFFN_ROUTER8(2, 2, 2); else BLOCKFFN_ROUTER8(2, 2, 1); }
-      else if (rt <= 4) { if (multi) BLOCKFFN_ROUTER8(4, 2, 2); else BLOCKFFN_ROUTER8(4, 2, 1); }
-      else if (rt <= 8) { if (multi) BLOCKFFN_ROUTER8(8, 1, 2); else BLOCKFFN_ROUTER8(8, 2, 1); }
-      else BLOCKFFN_ROUTER8(16, 1, 1);
-#undef BLOCKFFN_ROUTER8
-      return hipGetLastError();
-    }
     // Tiles of 16 tokens, of the token stream where every chunk is of the same layer for sure or
     // where they are the chunks' own tiles anyway; else tiles of each chunk: a tile across chunks
     // of different layers takes one pass over a router matrix per layer, one after the other.

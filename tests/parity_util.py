@@ -113,18 +113,16 @@ def preact_roundings(d):
     """Number of fp32 roundings on the longest chain of additions behind one pre-activation A^0 in
     the router kernels (products are exact: fused multiply-adds on the vector ALUs, bf16 x bf16
     on the matrix cores).
-      matrix cores: a wave accumulates every fourth K-step of 32 elements (tiles of 8 tokens:
-        ceil(ceil(d / 32) / 4) accumulator updates) or every fourth pair of K-steps (tiles of 16
-        tokens: 2 ceil(ceil(d / 64) / 4) updates), each update taking in a 32-term dot product (a
-        tree of depth 5); then the h / m / l sums (2), the four waves pairwise (2), the bias (1);
+      matrix cores: a wave accumulates every fourth pair of K-steps of 32 elements,
+        2 ceil(ceil(d / 64) / 4) accumulator updates, each taking in a 32-term dot product (a tree
+        of depth 5); then the h / m / l sums (2), the four waves pairwise (2), the bias (1);
       vector ALUs: chains of 8 fused multiply-adds per 2048 columns, a 6-level reduction across
         the wave, one addition per 2048-column block, the four waves (2), the bias (1).
     Each rounding moves the sum by at most 2^-24 of its magnitude, which is bounded by
     mag = |b| + sum_j |x_j| |W_ij|; so |A^0 - exact| <= preact_roundings(d) * 2^-24 * mag to first
     order, whatever the order of the additions inside those chains."""
-    ksteps = -(-d // 32)
     pairs = -(-d // 64)
-    mfma = max(-(-ksteps // 4), 2 * -(-pairs // 4)) + 5 + 2 + 2 + 1
+    mfma = 2 * -(-pairs // 4) + 5 + 2 + 2 + 1
     blocks = -(-d // 2048)
     valu = 8 * blocks + 6 + blocks + 2 + 1
     return max(mfma, valu)

@@ -257,13 +257,14 @@ def test_full_size_spec_k8_sampled_chunks():
 @pytest.mark.parametrize("E", [5, 16, 31, 64, 100, 128, 130, 256])
 @pytest.mark.parametrize("k", [1, 8, 11, 16, 20, 28, 48])
 def test_router_with_many_token_tiles(E, k):
-    """Enough token tiles that the router takes its many-tile kernels (the matrix-core ones for bf16
+    """Enough token tiles that the router takes its many-tile kernel (the matrix-core one for bf16
     weights), every count of 16-expert row tiles, a hidden size that ends in a partial pair of
     K-steps (520 = 8 * 64 + 8), gain and three weight sets that the chunks rotate through; scores,
-    masks and pre-activations against the oracle's router.  k < 16: tiles of 8 tokens of a chunk.
-    k >= 16: tiles of 16 tokens, with enough chunks that (up to 64 experts) a workgroup takes two
-    tiles per pass over the router matrix: the two of a chunk, the second ragged (k = 20, 28);
-    of two chunks, i.e. of two layers and two passes (k = 16); of one chunk or of two (k = 48)."""
+    masks and pre-activations against the oracle's router.  Tiles of 16 tokens: of one chunk each,
+    part empty (k < 16) or full (k = 16); k = 20, 28, 48 with enough chunks that (up to 64 experts)
+    a workgroup takes two tiles per pass over the router matrix: the two of a chunk, the second
+    ragged (k = 20, 28), or - three tiles per chunk - of one chunk or of two, i.e. of two layers
+    and two passes (k = 48)."""
     import oracle
     d, n_layers = 520, 3
     C = {1: 300, 8: 300, 11: 300, 16: 2100, 20: 1500, 28: 1500, 48: 700}[k]
