@@ -299,16 +299,20 @@ def test_router_with_many_token_tiles(E, k):
 
 
 @pytest.mark.parametrize("E,k,C,fine", [
-    (70, 8, 200, False),     # two mask words, one token tile per workgroup (5 row tiles of 16 experts)
-    (70, 16, 1100, True),    # two token tiles of a chunk per workgroup
-    (64, 32, 1100, True),    # four token tiles per workgroup
-    (30, 28, 1200, False),   # four token tiles, the last one ragged, a partial row tile of experts
+    (70, 8, 200, False),     # two mask words, 5 row tiles of 16 experts, two chunks per token tile
+    (70, 16, 1100, True),    # a token tile per chunk
+    (64, 32, 1100, True),    # two token tiles per workgroup: a chunk
+    (30, 28, 1200, False),   # two token tiles per workgroup across chunk boundaries, a partial row tile of experts
     (16, 8, 300, True),      # a single row tile
     (130, 11, 300, True),    # three mask words, nine row tiles, ragged token tile
+    (64, 1, 3000, True),     # one layer: tiles of 16 tokens across 16 chunks of one token
+    (128, 3, 1000, False),   # tiles across chunk boundaries, eight row tiles
+    (16, 1, 33000, True),    # two such tiles per workgroup, the last tile half full, the last workgroup with one tile
 ])
 def test_exact_arithmetic_router_fixture_on_the_matrix_cores(E, k, C, fine):
     """The exact-arithmetic fixture with bf16 weights and enough token tiles that the matrix-core
-    router is dispatched, with one, two and four token tiles of a chunk per workgroup.  Weights are
+    router is dispatched, with one and two token tiles per workgroup; one weight set, so the tiles
+    of 16 tokens are cut from the token stream whatever k is.  Weights are
     j / 64 with |j| <= 8 (exact in bf16), the bias a multiple of 2^-8, the hidden size 520 ends in a
     partial K-step.  x is i / 4 with |i| <= 4 (one bf16 piece), or `fine`: i / 1024 with
     |i| <= 2048 (12 significant bits: two or three bf16 pieces).  Every product is a multiple of
