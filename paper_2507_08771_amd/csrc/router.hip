@@ -269,11 +269,9 @@ __global__ __launch_bounds__(kThreads) void router_expert_kernel(LayerView L, co
 constexpr int kTile = 16;   // tokens per tile of the MFMA kernel
 
 template <int RT, int KP, int T>
-__global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel(LayerView L, const int32_t *__restrict__ chunk_layer,
-                                                               const float *__restrict__ x, int k, int64_t n_chunks,
-                                                               int tiles_per_chunk, float *__restrict__ scores,
-                                                               uint64_t *__restrict__ token_mask,
-                                                               float *__restrict__ preact) {
+__global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel(
+    LayerView L, const int32_t *__restrict__ chunk_layer, const float *__restrict__ x, int k, int64_t n_chunks,
+    int tiles_per_chunk, float *__restrict__ scores, uint64_t *__restrict__ token_mask, float *__restrict__ preact) {
   static_assert(T * kTile <= 32, "one bit per token of the workgroup");
   __shared__ float part[T][4][RT * 16][kTile];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -321,7 +319,8 @@ __global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel
     }
     uint32_t act = 0;
     bool tok_ok[T];
-    const float *xr[T];   // a lane without a token in this pass reads the first token's row again: no memory traffic of its own
+    // a lane without a token in this pass reads the first token's row again: no memory traffic of its own
+    const float *xr[T];
 #pragma unroll
     for (int tt = 0; tt < T; ++tt) {
       tok_ok[tt] = ((pend >> (tt * kTile + n)) & 1u) && lay[tt] == layer;
@@ -368,7 +367,8 @@ __global__ __launch_bounds__(kThreads, RT >= 16 ? 1 : 2) void router_mfma_kernel
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
           for (int hh = 0; hh < 2; ++hh) {
-            const int row = min(rt * 16 + hh * 8 + line_row(lane), E - 1);   // rows at or above E repeat the last one; never read back
+            // rows at or above E repeat the last one; never read back
+            const int row = min(rt * 16 + hh * 8 + line_row(lane), E - 1);
             a[u][rt][hh] = *reinterpret_cast<const uint4 *>(wr + (size_t)row * d + wc);
           }
       }
