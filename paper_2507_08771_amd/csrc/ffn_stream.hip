@@ -47,6 +47,19 @@ constexpr int up_group(int NB, int RT, int NM) {
   return cap / per_slot > 4 ? 4 : (cap / per_slot < 1 ? 1 : cap / per_slot);
 }
 
+// Groups of four waves per workgroup of the double-buffered up kernel.  Two where the accumulators
+// allow the full four slots per group of waves: an item is then eight slots, and the chunk's x
+// goes through LDS once per eight slots instead of four, with items no longer in time (k = 32,
+// Eq. 2 experts of 128: the fills were 7 % of the kernel).
+constexpr int up_halves(int NB, int RT, int NM) { return NB == 4 && up_group(NB, RT, NM) == 4 ? 2 : 1; }
+// Shapes the double-buffered kernel takes (given more than one K-chunk): those where it holds more
+// than one slot per group of waves; 8 fragments per tile (k > 16) need an even number of tiles
+// per slot.  (One slot per group of waves, two groups: `tree_k32` 24.6 ms against 23.7 ms for the
+// single-buffer kernel.)
+constexpr bool up_db_shape(int NB, int RT, int NM) {
+  return (NB == 2 || (NB == 4 && (RT * NM) % 2 == 0)) && up_group(NB, RT, NM) > 1;
+}
+
 // Flat work list: items[i] = chunk * E + slot for every `group`-th slot below n_active[chunk]
 // (an item stands for up to `group` consecutive slots of one chunk).  The persistent workgroups
 // take items at a fixed stride, so the list is ordered by size: first every item of `group`
@@ -63,7 +76,7 @@ constexpr int up_group(int NB, int RT, int NM) {
 // one coalesced sweep over n_active per workgroup (64 workgroups x 256 KiB at 65 536 chunks),
 // far less than a launch costs, and no workgroup ever waits for another.
 constexpr int kListChunks = 1024;   // chunks per workgroup = threads per workgroup
-constexpr int kMaxGroup = 4;
+constexpr int kMaxGroup = 8;
 
 __device__ __forceinline__ int items_of(int n_act, int group, int pass, int &first) {
   const int full = n_act / group, rem = n_act - full * group;
@@ -481,15 +494,18 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 // The weight stream's order is (item, K-chunk, slot, row tile, matrix, K-step); a cursor that
 // runs exactly 16 fragments (the ring) ahead of the consumer produces the prefetch addresses, so
 // it crosses tile, slot, K-chunk and item boundaries without special cases.  FPT is 8 or 16:
-// the cursor then changes tile exactly when the consumer does.  An item is up to G slots of one
-// chunk whose accumulators stay in registers across the K-chunks.
-template <int NB, int NM, int RT, int G>
-__global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
+// the cursor then changes tile exactly when the consumer does.  An item is up to G * HW slots of
+// one chunk: the workgroup is HW groups of four waves, group h takes slots h, h + HW, ... of the
+// item (up to G, whose accumulators stay in registers across the K-chunks) and all of them share
+// the buffers of x, the barriers and nothing else.
+template <int NB, int NM, int RT, int G, int HW>
+__global__ __launch_bounds__(kThreads * HW, 2 / HW) void up_stream_db_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
     int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits) {
   static_assert(NB == 2 || NB == 4, "8 or 16 K-steps per buffer");
+  static_assert(HW == 1 || HW == 2, "one or two groups of four waves");
   constexpr int FPT = 32 / NB;            // K-steps (fragments of one tile) per K-chunk
   constexpr int KB = 32 * FPT;            // contraction elements per buffer
   constexpr int kBuf = FPT * NB * 64;     // uint4 per buffer (2048 = 32 KiB)
@@ -497,7 +513,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   static_assert(FPT == 16 || TPS % 2 == 0, "with 8 fragments per tile the ring half must follow from (rr, m)");
   constexpr int NA = acc_tiles(NB);
   extern __shared__ uint4 xB[];           // [2][K-step][NB][64 lanes]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // wave = w4 of half `half`: the halves of a workgroup take every HW-th slot of the item each and
+  // share the buffers of x
+  const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, half = tid >> 8;
   const int lsrc = line_src(lane);
   const int E = L.E, d = L.d, d_e = L.d_e;
   const int total = *total_ptr;
@@ -514,8 +532,13 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     c = code / E;
     s = code - (int)c * E;
     const int n_act = active_idx ? min(max(n_active[c], 0), E) : E;
-    ns = max(1, min(G, n_act - s));
+    ns = max(1, min(G * HW, n_act - s));   // slots of the item, this half's among them: s + half, s + half + HW, ...
   };
+  // Slot sl of this half is slot s0 + sl * HW + half of the chunk; the half has (ns - half + HW - 1) / HW
+  // of them.  A half without any (the chunk's last item, one slot left) streams the item's first
+  // slot once more and writes nothing: the walk over the weights has no empty item.
+  auto half_slots = [&](int ns) { return max(1, (ns - half + HW - 1) / HW); };
+  auto half_slot = [&](int s0, int sl, int ns) { return half < ns ? s0 + sl * HW + half : s0; };
   // per-lane byte pointer to fragment 0 of tile t = rr * NM + m of (layer, expert)
   auto tile_ptr = [&](int layer, int e, int t) -> const char * {
     const int rr = t / NM, m = t % NM;
@@ -531,8 +554,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   auto slots_experts = [&](int64_t c, int s0, int ns) {
     uint32_t v = 0;
 #pragma unroll
-    for (int sl = 0; sl < G; ++sl) v |= (uint32_t)slot_expert(c, s0 + min(sl, ns - 1)) << (8 * sl);
-    return v;   // slots past ns repeat the last one and are never used
+    for (int sl = 0; sl < G; ++sl) v |= (uint32_t)slot_expert(c, half_slot(s0, min(sl, half_slots(ns) - 1), ns)) << (8 * sl);
+    return v;   // slots past the half's last repeat it and are never used
   };
   // bit sl set: the list entry of slot sl is outside [0, E) (an invalid input): an empty slot, for
   // which a valid expert is streamed (the clamped index) and no row of mid is written
@@ -541,16 +564,18 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     if (active_idx) {
 #pragma unroll
       for (int sl = 0; sl < G; ++sl)
-        v |= ((unsigned)active_idx[c * E + s0 + min(sl, ns - 1)] >= (unsigned)E ? 1u : 0u) << sl;
+        v |= ((unsigned)active_idx[c * E + half_slot(s0, min(sl, half_slots(ns) - 1), ns)] >= (unsigned)E ? 1u : 0u) << sl;
     }
-    return v;
+    return half < ns ? v : ~0u;   // a half without a slot of its own writes nothing
   };
-  // LDS-direct fill of one buffer: 32 KiB, 8 loads per wave
+  // LDS-direct fill of one buffer: 32 KiB, 8 / HW loads per wave
   auto fill = [&](int64_t c, int kc, int buf) {
-    const uint4 *src = xS + ((size_t)c * (d / 32) + (size_t)kc * FPT) * NB * 64 + wave * (kBuf / 4) + lane;
-    uint4 *dst = xB + buf * kBuf + wave * (kBuf / 4);
+    constexpr int per_wave = kBuf / (4 * HW);
+    const int fw = half * 4 + wave;
+    const uint4 *src = xS + ((size_t)c * (d / 32) + (size_t)kc * FPT) * NB * 64 + fw * per_wave + lane;
+    uint4 *dst = xB + buf * kBuf + fw * per_wave;
 #pragma unroll
-    for (int j = 0; j < kBuf / 4 / 64; ++j) load_to_lds16(src + j * 64, dst + j * 64);
+    for (int j = 0; j < per_wave / 64; ++j) load_to_lds16(src + j * 64, dst + j * 64);
   };
 
   // Router scores and mask words of the item's tokens, [item parity][slot][score, mask lo, mask
@@ -559,16 +584,16 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   // made the epilogue start with a wait for "every load so far" (the compiler cannot count across
   // the K-chunk loop), i.e. for the ring's 16 loads of the next item; this way the kernel has no
   // such wait at all.
-  __shared__ uint32_t scoreS[2][G][3][64];
+  __shared__ uint32_t scoreS[2][HW][G][3][64];
   auto request_scores = [&](int ipar, int64_t c, uint32_t es, int k) {
     if (wave < G) {   // uniform over the wave; a slot past ns repeats the last one
       const int e = pick(es, wave);
       const int64_t tok = c * k + min(lane & 31, k - 1);
-      load_to_lds4(scores + tok * E + e, &scoreS[ipar][wave][0][0]);
+      load_to_lds4(scores + tok * E + e, &scoreS[ipar][half][wave][0][0]);
       if (token_mask) {
         const uint32_t *m = reinterpret_cast<const uint32_t *>(token_mask + tok * L.W + (e >> 6));
-        load_to_lds4(m, &scoreS[ipar][wave][1][0]);
-        load_to_lds4(m + 1, &scoreS[ipar][wave][2][0]);
+        load_to_lds4(m, &scoreS[ipar][half][wave][1][0]);
+        load_to_lds4(m + 1, &scoreS[ipar][half][wave][2][0]);
       }
     }
   };
@@ -577,9 +602,9 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
 #pragma unroll
     for (int q = 0; q < NA; ++q) {
       const int t = q * 16 + n;   // NB = 2: one accumulator tile, tokens 0-15
-      const uint32_t word = token_mask ? scoreS[ipar][sl][1 + ((e >> 5) & 1)][t] : ~0u;
+      const uint32_t word = token_mask ? scoreS[ipar][half][sl][1 + ((e >> 5) & 1)][t] : ~0u;
       const bool on = valid && t < k && ((word >> (e & 31)) & 1);
-      f_tok[q] = on ? __uint_as_float(scoreS[ipar][sl][0][t]) : 0.0f;
+      f_tok[q] = on ? __uint_as_float(scoreS[ipar][half][sl][0][t]) : 0.0f;
     }
   };
 
@@ -620,7 +645,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
   // branches: control flow between two tiles makes the compiler's counted waits for the ring's
   // loads collapse to "wait for everything" at the join.
   auto cu_advance = [&]() {
-    const int nsl = cu_next ? ns_n : ns;
+    const int nsl = half_slots(cu_next ? ns_n : ns);
     const bool wrap_t = cu_t + 1 == TPS;
     const int t = wrap_t ? 0 : cu_t + 1;
     const bool wrap_s = wrap_t && cu_sl + 1 == nsl;
@@ -673,7 +698,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
       const uint4 *xb = xB + par * kBuf;
 #pragma unroll
       for (int sl = 0; sl < G; ++sl) {
-        if (sl >= ns) break;   // uniform over the workgroup
+        if (sl >= half_slots(ns)) break;   // uniform over the half
 #pragma unroll
         for (int rr = 0; rr < RT; ++rr) {
 #pragma unroll
@@ -712,7 +737,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_db_kernel(
     for (int sl = 0; sl < G; ++sl) read_scores(f_tok[sl], ipar, sl, pick(es, sl), !((bad >> sl) & 1));
 #pragma unroll
     for (int sl = 0; sl < G; ++sl)
-      if (sl < ns) up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, s0 + sl, lane, wave, midB, tok_bits);
+      if (sl < half_slots(ns) && half < ns)   // a half without a slot of its own has nothing to write
+        up_epilogue_f<NB, NM, RT>(acc[sl], f_tok[sl], L, c, half_slot(s0, sl, ns), lane, wave, midB, tok_bits);
     ipar ^= 1;   // the next item's scores go to the other half: a slower wave may still be reading this one
 
     if (!has_next) break;
@@ -1675,19 +1701,19 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4
   return hipGetLastError();
 }
 
-template <int NB, int NM, int RT, int G>
+template <int NB, int NM, int RT, int G, int HW>
 hipError_t launch_up_db(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                         const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                         const int32_t *items, const int32_t *total, int64_t max_items, int k, uint16_t *midB,
                         uint32_t *tok_bits, hipStream_t s) {
   static PerDeviceOnce lds_limit;   // one per instantiation
-  auto kern = up_stream_db_kernel<NB, NM, RT, G>;
+  auto kern = up_stream_db_kernel<NB, NM, RT, G, HW>;
   const hipError_t e = lds_limit.run([&] {
     return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kXBytes);
   });
   if (e != hipSuccess) return e;
-  const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
+  const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2 / HW) + 7) / 8 * 8;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads * HW), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
                      active_idx, n_active, items, total, k, midB, tok_bits);
   return hipGetLastError();
 }
@@ -1815,8 +1841,8 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   // of more than one slot fit in registers (otherwise it has nothing over the single buffer).
   // 8 fragments per tile (k > 16) need an even number of tiles per slot.
   const int nm = gated ? 2 : 1;
-  const bool use_db = L.d > 2048 / NB && (NB == 2 || (NB == 4 && (RT * nm) % 2 == 0)) && up_group(NB, RT, nm) > 1;
-  const int group = use_db ? up_group(NB, RT, nm) : (L.d <= 2048 / NB ? 2 : 1);
+  const bool use_db = L.d > 2048 / NB && up_db_shape(NB, RT, nm);
+  const int group = use_db ? up_group(NB, RT, nm) * up_halves(NB, RT, nm) : (L.d <= 2048 / NB ? 2 : 1);
   hipError_t err = launch_worklist(n_active, n_chunks, L.E, group, w.items, w.total, s);
   if (err != hipSuccess) return err;
   {
@@ -1834,9 +1860,9 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   }
 #define BLOCKFFN_CASE(nb, nm, rt)                                                                         \
   if (NB == nb && (gated ? 2 : 1) == nm && RT == rt) {                                                    \
-    if constexpr ((nb == 2 || (nb == 4 && (rt * nm) % 2 == 0)) && up_group(nb, rt, nm) > 1)               \
+    if constexpr (up_db_shape(nb, rt, nm))                                                                \
       if (use_db)                                                                                         \
-        return launch_up_db<nb, nm, rt, up_group(nb, rt, nm)>(L, chunk_layer, w.xS, scores, token_mask, active_idx, \
+        return launch_up_db<nb, nm, rt, up_group(nb, rt, nm), up_halves(nb, rt, nm)>(L, chunk_layer, w.xS, scores, token_mask, active_idx, \
                                                               n_active, w.items, w.total, max_items, k, w.midB,     \
                                                               w.tok_bits, s);                                         \
     return launch_up<nb, nm, rt>(L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, \

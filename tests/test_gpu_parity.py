@@ -60,8 +60,8 @@ def impl(request):
     (3072, 40, 256, 12, 3),   # two token tiles, three K-chunks
     (1024, 48, 256, 32, 3),   # four token tiles, two K-chunks of 512
     (2560, 64, 256, 24, 2),   # four token tiles with a ragged last one, five K-chunks
-    (2048, 64, 128, 32, 3),   # k = 32 at d_e = 128: double-buffered x, items of 2 (gated) or 4 slots
-    (2048, 64, 64, 24, 3),    # d_e = 64: one row tile per wave (gated: two tiles per slot, items of 4)
+    (2048, 64, 128, 32, 3),   # k = 32 at d_e = 128: double-buffered x, items of 2 (gated) or 8 slots
+    (2048, 64, 64, 24, 3),    # d_e = 64: one row tile per wave (gated: two tiles per slot), items of 8 slots
     (2048, 48, 128, 16, 3),   # k = 16 at d_e = 128: 16 fragments per tile and buffer
     (512, 256, 64, 8, 5),     # the most experts: four full mask words, 16 router row tiles
     (256, 8, 1024, 4, 2),     # the widest expert
@@ -412,6 +412,46 @@ def test_list_entry_out_of_range_is_an_empty_slot(d, E, d_e, k, C):
     y_ref = oracle.sparse_ffn(pu.oracle_layer(layers, 0), x.numpy(), gpu["scores"], gpu["token_mask"], ref_idx, ref_n, k)
     e = pu.row_rel_err(y.cpu().numpy(), y_ref).max(initial=0.0)
     assert e <= (pu.GEMM_BAR if k > 32 else pu.TIGHT["bf16"]), e
+
+
+@pytest.mark.parametrize("d,E,d_e,k,gated", [
+    (1024, 32, 128, 32, False),   # items of 8 slots over two groups of four waves
+    (2048, 64, 64, 24, True),     # the same with gated experts of 64
+    (2048, 64, 128, 32, True),    # items of 2 slots
+    (2048, 64, 128, 8, True),     # k = 8: items of 2 slots, the whole x in LDS
+])
+def test_lists_of_every_length(d, E, d_e, k, gated):
+    """Chunks whose lists have 0, 1, 2, ... entries, so that a chunk's last work item has every
+    number of slots an item can have (one slot left: a group of waves without a slot of its own).
+    The lists are the unions cut short, or filled up with experts no token of the chunk has
+    (they contribute nothing); the oracle's FFN runs over the same lists."""
+    import oracle
+    lengths = list(range(0, min(E, 19))) + [min(E, 24), min(E, 25), E]
+    C = len(lengths)
+    w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.3, seed=5 * k + E,
+                    p_active=0.3)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k)
+    L, buf = gpu["_layer"], gpu["_buf"]
+    idx, n_act = gpu["active_idx"], gpu["n_active"]
+    new_idx = np.full_like(idx, -1)
+    for c, m in enumerate(lengths):
+        own = list(idx[c, :n_act[c]])
+        others = [e for e in range(E) if e not in own]
+        chosen = sorted(own[:m] + others[:max(0, m - len(own))])
+        new_idx[c, :m] = chosen
+    new_n = np.asarray(lengths, np.int32)
+    buf.active_idx.copy_(torch.tensor(new_idx))
+    buf.n_active.copy_(torch.tensor(new_n))
+    y = torch.full_like(buf.y, float("nan"))
+    B.blockffn_sparse_ffn(L, x.cuda(), buf.scores, buf.token_mask, buf.active_idx, buf.n_active, C, k, y, buf.workspace)
+    torch.cuda.synchronize()
+    y_ref = oracle.sparse_ffn(pu.oracle_layer(layers, 0), x.numpy(), gpu["scores"], gpu["token_mask"], new_idx, new_n, k)
+    got = y.cpu().numpy()
+    assert np.all(got[:k] == 0)   # the empty list
+    e = pu.row_rel_err(got, y_ref).max(initial=0.0)
+    assert e <= pu.TIGHT["bf16"], e
 
 
 def test_work_list_of_many_chunks():
