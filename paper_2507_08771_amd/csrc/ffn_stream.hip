@@ -251,7 +251,7 @@ template <int NB, int NM, int RT>
 __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_tiles(NB)],
                                               const float (&f_tok)[acc_tiles(NB)], const LayerView &L, int64_t c,
                                               int s, int lane, int wave, uint16_t *__restrict__ midB,
-                                              uint32_t *__restrict__ tok_bits) {
+                                              uint32_t *__restrict__ tok_bits, bool one_token = false) {
   constexpr int NA = acc_tiles(NB);
   const int E = L.E, d_e = L.d_e;
   const int g = lane >> 4;
@@ -281,7 +281,13 @@ __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_til
       }
       const uint2 vhi = make_uint2(phi[0] | phi[1] << 16, phi[2] | phi[3] << 16);
       const uint2 vlo = make_uint2(plo[0] | plo[1] << 16, plo[2] | plo[3] << 16);
-      if (NB == 1) {
+      if (NB == 1 && one_token) {
+        // k = 1 (mid_one_token): columns 0 and 8 only, as rows [hi | lo][d_e] of the slot
+        if ((n & 7) == 0)
+          store_stream(reinterpret_cast<uint2 *>(midB + (((size_t)c * E + s) * 2 + (n >> 3)) * d_e +
+                                                 (rr * 4 + wave) * 16 + 4 * g),
+                       n < 8 ? vhi : vlo);
+      } else if (NB == 1) {
         // fragment column n: hi for n < 8, lo of token n - 8 for n >= 8
         store_stream(mid_entry(midB, ((size_t)c * E + s) * (d_e / 32), rr * 4 + wave, g, n), n < 8 ? vhi : vlo);
       } else if (on) {
@@ -303,7 +309,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
-    int group, int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits) {
+    int group, int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits, int one_token) {
   extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
   __shared__ uint32_t scoreS[2][4][3][64];   // [slot parity][wave]: see request_scores
   int spar = 0;
@@ -476,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");
     read_scores<NB>(f_tok, scoreS[spar][wave], token_mask != nullptr, e, e_ok, k, lane);
     spar ^= 1;
-    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits);
+    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits, NB == 1 && one_token);
 
     if (!has_next) break;
     item = next_item;
@@ -1392,7 +1398,7 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, int64_t n_chunks, int k, int col_blocks, int splits,
     const uint16_t *__restrict__ midB, const uint32_t *__restrict__ tok_bits, const uint4 *__restrict__ zero16,
-    float *__restrict__ out, size_t split_stride) {
+    float *__restrict__ out, size_t split_stride, int one_token) {
   constexpr int kFrag = KSD * MW;             // weight fragments per slot and wave
   static_assert(kFrag % RING == 0, "ring must divide the fragments of a slot");
   constexpr int kStage = KSD * NB * 64;       // uint4 of mid per slot
@@ -1453,13 +1459,18 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
 #pragma unroll
       for (int i = 0; i < RING; ++i) ring[i] = load_stream(p + frag_off(i));
     }
-    const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (NB * 16) * d_e);
+    const bool one = NB == 1 && one_token;   // mid_one_token: rows [hi | lo][d_e] per slot
+    const uint4 *mid_c = reinterpret_cast<const uint4 *>(midB + (size_t)c * E * (one ? 2 : NB * 16) * d_e);
     // B-operand order in LDS is [K-step][NB][lane = gg * 16 + n] of 8 bf16.  k <= 8: mid is stored
     // like that.  k > 8: mid is token-major and holds only the rows of the tokens in `bits`; entry
     // (K-step, fragment bf, gg, n) is 16 bytes of row (token 16 (bf / 2) + n, hi or lo = bf & 1),
     // or of the block of zeros.
     auto slot_bits = [&](int s) { return NB == 1 ? 0u : tok_bits[c * E + min(s, s_hi - 1)]; };
     auto stage_src = [&](int s, int idx, uint32_t bits) -> const uint4 * {
+      if (one) {   // column 0: the token's hi part, column 8: its lo part, the others zero
+        const int ln = idx & 63, ks = idx >> 6, n = ln & 15, gg = ln >> 4;
+        return (n & 7) == 0 ? mid_c + ((size_t)s * 2 + (n >> 3)) * (d_e / 8) + ks * 4 + gg : zero16;
+      }
       if (NB == 1) return mid_c + (size_t)s * kStage + idx;
       const int ln = idx & 63, bf = (idx >> 6) % NB, ks = idx / (64 * NB);
       const int n = ln & 15, gg = ln >> 4, t = (bf >> 1) * 16 + n;
@@ -1688,7 +1699,7 @@ template <int NB, int NM, int RT>
 hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4 *xS, const float *scores,
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                      const int32_t *items, const int32_t *total, int group, int64_t max_items, int k, uint16_t *midB,
-                     uint32_t *tok_bits, hipStream_t s) {
+                     uint32_t *tok_bits, bool one_token, hipStream_t s) {
   static PerDeviceOnce lds_limit;   // one per instantiation
   auto kern = up_stream_kernel<NB, NM, RT>;
   const hipError_t e = lds_limit.run([&] {
@@ -1697,7 +1708,7 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4
   if (e != hipSuccess) return e;
   const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
-                     active_idx, n_active, items, total, group, k, midB, tok_bits);
+                     active_idx, n_active, items, total, group, k, midB, tok_bits, one_token ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -1737,13 +1748,15 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
                        const uint4 *zero16, float *part, float *y, hipStream_t s) {
   const int splits = down_splits(L, n_chunks);
   const size_t stride = (size_t)n_chunks * k * L.d;
+  const int one_token = NB == 1 && mid_one_token(L, n_chunks, k) ? 1 : 0;
   if (splits == 0) {
     constexpr int MW = (NB == 4 && KSD >= 8) ? 4 : 8;   // 8 row tiles x 2 accumulator tiles do not fit beside 64 fragments of addresses
     const int col_blocks = L.d / (4 * MW * 16);
     const int64_t grid = down_grid_chunks(n_chunks) * col_blocks;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, kRing>), dim3((unsigned)grid), dim3(kThreads), 0, s, L,
-                       chunk_layer, active_idx, n_active, n_chunks, k, col_blocks, 1, midB, tok_bits, zero16, y, stride);
+                       chunk_layer, active_idx, n_active, n_chunks, k, col_blocks, 1, midB, tok_bits, zero16, y, stride,
+                       one_token);
     return hipGetLastError();
   }
   constexpr int MW = 8 / KSD;
@@ -1756,7 +1769,7 @@ hipError_t launch_down(const LayerView &L, const int32_t *chunk_layer, const int
     const int64_t grid = down_grid_chunks(n_chunks) * col_blocks * splits;
     hipLaunchKernelGGL((down_stream_kernel<NB, KSD, MW, 8>), dim3((unsigned)grid), dim3(kThreads), 0, s, L, chunk_layer,
                        active_idx, n_active, n_chunks, k, col_blocks, splits, midB, tok_bits, zero16,
-                       splits > 1 ? part : y, stride);
+                       splits > 1 ? part : y, stride, one_token);
   }
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || splits == 1) return err;
@@ -1866,7 +1879,7 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
                                                               n_active, w.items, w.total, max_items, k, w.midB,     \
                                                               w.tok_bits, s);                                         \
     return launch_up<nb, nm, rt>(L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, \
-                                 group, max_items, k, w.midB, w.tok_bits, s);                             \
+                                 group, max_items, k, w.midB, w.tok_bits, mid_one_token(L, n_chunks, k), s);  \
   }
   BLOCKFFN_CASE(1, 1, 1) BLOCKFFN_CASE(1, 1, 2) BLOCKFFN_CASE(1, 1, 4)
   BLOCKFFN_CASE(1, 2, 1) BLOCKFFN_CASE(1, 2, 2) BLOCKFFN_CASE(1, 2, 4)
