@@ -416,6 +416,28 @@ def test_list_entry_out_of_range_is_an_empty_slot(d, E, d_e, k, C):
     assert e <= (pu.GEMM_BAR if k > 32 else pu.TIGHT["bf16"]), e
 
 
+@pytest.mark.parametrize("k,C", [(1, 100), (1, 40), (32, 70)])
+def test_two_halves_equal_the_combined_call(k, C):
+    """blockffn_sparse_ffn_up then _down (what the benchmark times) give the bits of
+    blockffn_sparse_ffn, on the layouts of mid the other tests reach only through the combined
+    call: one-token chunks (64 or more: the token's hi and lo rows; fewer: the k <= 8 fragment
+    order) and the token-major rows of k = 32; the workspace is dirty from the call before."""
+    w = wl.Workload("t", d=1024, E=32, d_e=128, wdtype="bf16", gated=True, k=k, n_chunks=C, sigma=0.3, seed=9 + k)
+    layers = wl.make_layers(w, 1)
+    x = wl.make_tokens(w, layers)
+    gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), w.k)
+    L, buf = gpu["_layer"], gpu["_buf"]
+    y1 = buf.y.clone()
+    y2 = torch.full_like(buf.y, float("nan"))
+    xd = x.cuda()
+    B.blockffn_sparse_ffn_up(L, xd, buf.scores, buf.token_mask, buf.active_idx, buf.n_active, C, k, buf.workspace)
+    B.blockffn_sparse_ffn_down(L, buf.active_idx, buf.n_active, C, k, y2, buf.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y1)
+    ref = pu.run_oracle(layers, x, k)
+    assert pu.row_rel_err(y2.cpu().numpy(), ref["y"]).max(initial=0.0) <= pu.TIGHT["bf16"]
+
+
 @pytest.mark.parametrize("d,E,d_e,k,gated", [
     (1024, 32, 128, 32, False),   # items of 8 slots over two groups of four waves
     (2048, 64, 64, 24, True),     # the same with gated experts of 64
