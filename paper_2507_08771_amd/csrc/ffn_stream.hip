@@ -223,6 +223,32 @@ __device__ __forceinline__ void request_scores(uint32_t (&area)[3][64], const La
 }
 
 // 0 where the mask bit is clear, the token is past the chunk or the list entry was invalid
+// One-token chunks on the many-chunk kernels (mid_one_token): of the 16 columns of the NB = 1
+// layout only columns 0 (hi) and 8 (lo) hold anything, so xS keeps those two alone,
+// [chunk][K-step][gg][hi, lo] of 8 bf16 (8 KiB per chunk at d = 2048 instead of 64), and the up
+// kernel, which zeroes its LDS copy once, refills only them.  One thread per 16-byte entry.
+__global__ __launch_bounds__(kThreads) void split_x1_kernel(const float *__restrict__ x, int64_t n_chunks, int d,
+                                                            uint4 *__restrict__ xS) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t per_chunk = (int64_t)(d / 32) * 8;
+  if (idx >= n_chunks * per_chunk) return;
+  const int64_t c = idx / per_chunk;
+  const int rem = (int)(idx - c * per_chunk);
+  const int kstep = rem >> 3, gg = (rem >> 1) & 3;
+  const bool want_lo = rem & 1;
+  const float4 *p = reinterpret_cast<const float4 *>(x + c * d + kstep * 32 + gg * 8);
+  const float4 a = p[0], b = p[1];
+  const float xv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  uint32_t h[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    uint32_t hi, lo;
+    split_bf16(xv[q], hi, lo);
+    h[q] = want_lo ? lo : hi;
+  }
+  xS[idx] = make_uint4(h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16);
+}
+
 template <int NB>
 __device__ __forceinline__ void read_scores(float (&f_tok)[acc_tiles(NB)], const uint32_t (&area)[3][64], bool has_mask,
                                             int e, bool valid, int k, int lane) {
@@ -304,12 +330,13 @@ __device__ __forceinline__ void up_epilogue_f(const f32x4 (&acc)[RT][NM][acc_til
 
 // NB: B fragments per K-step (see the top of the file); NM: 1 (Eq. 2) or 2 (gated); RT: 64-row
 // groups of the expert (d_e = 64 * RT).  Wave w owns row tiles rr*4 + w.
-template <int NB, int NM, int RT>
+template <int NB, int NM, int RT, bool ONE>
 __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     LayerView L, const int32_t *__restrict__ chunk_layer, const uint4 *__restrict__ xS,
     const float *__restrict__ scores, const uint64_t *__restrict__ token_mask, const int32_t *__restrict__ active_idx,
     const int32_t *__restrict__ n_active, const int32_t *__restrict__ items, const int32_t *__restrict__ total_ptr,
-    int group, int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits, int one_token) {
+    int group, int k, uint16_t *__restrict__ midB, uint32_t *__restrict__ tok_bits) {
+  static_assert(!ONE || NB == 1, "one-token chunks are k = 1");
   extern __shared__ uint4 xB[];   // [K-step][NB][64 lanes] of 8 bf16
   __shared__ uint32_t scoreS[2][4][3][64];   // [slot parity][wave]: see request_scores
   int spar = 0;
@@ -345,6 +372,15 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     const size_t row = ((size_t)layer * E + e) * d_e + (rr * 4 + wave) * 16 + line_row(lane);
     return w + row * row_bytes + line_byte(lane);
   };
+
+  // One-token chunks (see split_x1_kernel): xS holds 8 entries per K-step, entry i of which belongs
+  // at column 0 or 8 of its gg; the other columns of the LDS copy are zeroed here, once.
+  constexpr bool one = ONE;   // mid_one_token
+  auto x_entries = [&](int kc_len) { return one ? (kc_len / 32) * 8 : (kc_len / 32) * NB * 64; };
+  auto x_src = [&](int64_t c, int kc0) { return xS + ((size_t)c * (d / 32) + kc0 / 32) * (one ? 8 : NB * 64); };
+  auto x_dst = [&](int idx) { return one ? (idx >> 3) * 64 + ((idx >> 1) & 3) * 16 + (idx & 1) * 8 : idx; };
+  if (one)
+    for (int i = tid; i < kXBytes / 16; i += kThreads) xB[i] = make_uint4(0, 0, 0, 0);
 
   uint4 ring[kRing];
   // workgroup b runs on XCD b mod 8: consecutive items (slots of one chunk, same split x) go to
@@ -408,8 +444,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       if (refill) __syncthreads();   // every wave is done with the previous contents of xB
       // copy the K-chunk's slice of the chunk's split x into LDS, 8 loads in flight per lane
       if (refill) {
-        const int n16 = (kc_len / 32) * NB * 64;
-        const uint4 *src = xS + ((size_t)c * (d / 32) + kc0 / 32) * NB * 64;
+        const int n16 = x_entries(kc_len);
+        const uint4 *src = x_src(c, kc0);
         for (int base = 0; base < n16; base += PF * kThreads) {
           if (base > 0 || !pf_valid) {   // the first batch may have been loaded ahead
 #pragma unroll
@@ -421,7 +457,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
 #pragma unroll
           for (int j = 0; j < PF; ++j) {
             const int idx = base + j * kThreads + tid;
-            if (idx < n16) xB[idx] = pf[j];
+            if (idx < n16) xB[x_dst(idx)] = pf[j];
           }
         }
       }
@@ -434,8 +470,8 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
       const int64_t c_f = last_kc ? c_n : c;
       const int k_f = last_kc ? 0 : kc0 + KC;
       const bool need_f = last_kc ? (has_next && (c_n != c || kc0 != 0)) : true;
-      const int n16_f = (min(KC, d - k_f) / 32) * NB * 64;
-      const uint4 *src_f = xS + ((size_t)c_f * (d / 32) + k_f / 32) * NB * 64;
+      const int n16_f = x_entries(min(KC, d - k_f));
+      const uint4 *src_f = x_src(c_f, k_f);
 #pragma unroll
       for (int rr = 0; rr < RT; ++rr) {
 #pragma unroll
@@ -482,7 +518,7 @@ __global__ __launch_bounds__(kThreads, 2) void up_stream_kernel(
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRing) : "memory");
     read_scores<NB>(f_tok, scoreS[spar][wave], token_mask != nullptr, e, e_ok, k, lane);
     spar ^= 1;
-    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits, NB == 1 && one_token);
+    up_epilogue_f<NB, NM, RT>(acc, f_tok, L, c, s, lane, wave, midB, tok_bits, ONE);
 
     if (!has_next) break;
     item = next_item;
@@ -1700,15 +1736,28 @@ hipError_t launch_up(const LayerView &L, const int32_t *chunk_layer, const uint4
                      const uint64_t *token_mask, const int32_t *active_idx, const int32_t *n_active,
                      const int32_t *items, const int32_t *total, int group, int64_t max_items, int k, uint16_t *midB,
                      uint32_t *tok_bits, bool one_token, hipStream_t s) {
-  static PerDeviceOnce lds_limit;   // one per instantiation
-  auto kern = up_stream_kernel<NB, NM, RT>;
+  static PerDeviceOnce lds_limit, lds_limit_one;   // one per instantiation
+  const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
+  if constexpr (NB == 1) {
+    if (one_token) {
+      auto kern = up_stream_kernel<NB, NM, RT, true>;
+      const hipError_t e = lds_limit_one.run([&] {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kXBytes);
+      });
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
+                         active_idx, n_active, items, total, group, k, midB, tok_bits);
+      return hipGetLastError();
+    }
+  }
+  auto kern = up_stream_kernel<NB, NM, RT, false>;
   const hipError_t e = lds_limit.run([&] {
     return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kXBytes);
   });
   if (e != hipSuccess) return e;
-  const int64_t grid = (std::min<int64_t>(max_items, (int64_t)num_cus() * 2) + 7) / 8 * 8;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), kXBytes, s, L, chunk_layer, xS, scores, token_mask,
-                     active_idx, n_active, items, total, group, k, midB, tok_bits, one_token ? 1 : 0);
+                     active_idx, n_active, items, total, group, k, midB, tok_bits);
   return hipGetLastError();
 }
 
@@ -1862,7 +1911,10 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
     const int64_t entries = n_chunks * (int64_t)(L.d / 32) * NB * 64;
     const int64_t blocks = (entries + kThreads - 1) / kThreads;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (NB == 1)
+    if (NB == 1 && mid_one_token(L, n_chunks, k))
+      hipLaunchKernelGGL(split_x1_kernel, dim3((unsigned)((n_chunks * (L.d / 32) * 8 + kThreads - 1) / kThreads)),
+                         dim3(kThreads), 0, s, x, n_chunks, L.d, w.xS);
+    else if (NB == 1)
       hipLaunchKernelGGL(split_x_kernel<1>, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, n_chunks, k, L.d, w.xS);
     else if (NB == 2)
       hipLaunchKernelGGL(split_x_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), 0, s, x, n_chunks, k, L.d, w.xS);

@@ -162,7 +162,8 @@ inline bool few_chunks(const LayerView &L, int64_t n_chunks, int k) {
 // hold anything (the token's hi and lo parts), and what a store costs the weight stream goes by
 // the 128-byte lines it touches, not by its bytes (32 lines per slot at d_e = 128, mostly zeros).
 // Mid is then [chunk][slot][hi | lo][d_e] bf16: 4 lines per slot; the down kernel stages the
-// other 14 columns from a block of zeros.  (`decode_k1`: up kernel - 4.3 %.)
+// other 14 columns from a block of zeros.  (`decode_k1`: up kernel - 4.3 %.)  The chunk's split x
+// likewise keeps its two columns only (split_x1_kernel).
 inline bool mid_one_token(const LayerView &L, int64_t n_chunks, int k) {
   return k == 1 && n_chunks >= 64 && !few_chunks(L, n_chunks, k);
 }
