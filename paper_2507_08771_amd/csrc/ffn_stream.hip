@@ -1927,9 +1927,9 @@ hipError_t launch_up_stream(const LayerView &L, bool gated, const int32_t *chunk
   if (NB == nb && (gated ? 2 : 1) == nm && RT == rt) {                                                    \
     if constexpr (up_db_shape(nb, rt, nm))                                                                \
       if (use_db)                                                                                         \
-        return launch_up_db<nb, nm, rt, up_group(nb, rt, nm), up_halves(nb, rt, nm)>(L, chunk_layer, w.xS, scores, token_mask, active_idx, \
-                                                              n_active, w.items, w.total, max_items, k, w.midB,     \
-                                                              w.tok_bits, s);                                         \
+        return launch_up_db<nb, nm, rt, up_group(nb, rt, nm), up_halves(nb, rt, nm)>(                   \
+            L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, max_items, k, \
+            w.midB, w.tok_bits, s);                                                                       \
     return launch_up<nb, nm, rt>(L, chunk_layer, w.xS, scores, token_mask, active_idx, n_active, w.items, w.total, \
                                  group, max_items, k, w.midB, w.tok_bits, mid_one_token(L, n_chunks, k), s);  \
   }
