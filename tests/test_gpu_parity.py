@@ -69,6 +69,8 @@ def impl(request):
     (512, 32, 64, 8, 67),     # 64 chunks or more: a chunk's down-projection workgroups share an XCD; ragged count
     (1024, 32, 128, 1, 70),   # 64 chunks or more of one token: mid holds the token's hi and lo rows only
     (512, 16, 64, 1, 100),    # the same at d_e = 64
+    (4096, 16, 64, 1, 80),    # the same with two K-chunks of x
+    (2304, 16, 128, 1, 70),   # the same with a short second K-chunk
 ])
 def test_shapes(d, E, d_e, k, C, wdtype, gated, impl):
     if impl == "generic" and wdtype == "f32":
