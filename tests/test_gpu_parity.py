@@ -418,6 +418,50 @@ def test_list_entry_out_of_range_is_an_empty_slot(d, E, d_e, k, C):
     assert e <= (pu.GEMM_BAR if k > 32 else pu.TIGHT["bf16"]), e
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes(seed):
+    """Twelve shapes per seed drawn from the sizes at which the kernels switch (hidden sizes with
+    one, two and a short last K-chunk; one to three mask words; experts of 64 and 128; k from 1 to
+    32; 1 to 300 chunks; one to three weight sets, gain on).  Integers bit-exact; y against the
+    oracle's FFN over the scores, masks and lists the HIP path produced; scores within the
+    allowance derived from the fp32 additions behind them."""
+    import random
+    import oracle
+    rng = random.Random(seed)
+    for case in range(12):
+        d = rng.choice([512, 1024, 2048, 2304, 4096])
+        E = rng.choice([8, 16, 32, 64, 130])
+        d_e = rng.choice([64, 128])
+        k = rng.choice([1, 1, 3, 8, 12, 16, 24, 32])
+        C = rng.choice([1, 5, 65, 70, 130, 300])
+        if C * k > 2100:
+            C = 65
+        gated = rng.random() < 0.5
+        n_layers = rng.choice([1, 1, 2, 3])
+        w = wl.Workload("t", d=d, E=E, d_e=d_e, wdtype="bf16", gated=gated, k=k, n_chunks=C, sigma=0.3,
+                        seed=rng.randrange(1 << 20), p_active=rng.choice([0.2, 0.4]))
+        print("case", case, w, "layers", n_layers, flush=True)
+        layers = wl.make_layers(w, n_layers, gain=True)
+        cl = wl.make_chunk_layer(w, n_layers) if n_layers > 1 else None
+        x = wl.make_tokens(w, layers, cl)
+        ref = pu.run_oracle(layers, x, k, cl, dense=False, use_gain=True)
+        gpu = pu.run_gpu(pu.to_device(layers), x.cuda(), k, cl, dense=False, use_gain=True)
+        pu.assert_integers_equal(gpu, ref)
+        cls = np.zeros(C, np.int64) if cl is None else cl.numpy()
+        xs = x.numpy()
+        for l in range(n_layers):
+            cs = np.nonzero(cls == l)[0]
+            if len(cs) == 0:
+                continue
+            tok = (cs[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+            y_ref = oracle.sparse_ffn(pu.oracle_layer(layers, l), xs[tok], gpu["scores"][tok], gpu["token_mask"][tok],
+                                      gpu["active_idx"][cs], gpu["n_active"][cs], k)
+            e = pu.row_rel_err(gpu["y"][tok], y_ref).max(initial=0.0)
+            assert e <= pu.TIGHT["bf16"], (case, l, e)
+        pu.assert_scores_within_allowance(gpu["scores"], ref["scores"],
+                                          pu.score_error_allowed(layers, x, k, cl, ref["scores"]))
+
+
 @pytest.mark.parametrize("k,C", [(1, 100), (1, 40), (32, 70)])
 def test_two_halves_equal_the_combined_call(k, C):
     """blockffn_sparse_ffn_up then _down (what the benchmark times) give the bits of
