@@ -1575,6 +1575,48 @@ __global__ __launch_bounds__(kThreads, 2) void down_stream_kernel(
   }
 
   const int n = lane & 15;
+  // The unsplit launch writes y as whole 128-byte lines: the values of two column tiles (64 bytes
+  // of a token's row each) are brought together so that the 64 lanes of a store cover 8 token rows
+  // x 128 bytes, lane = 8 row + piece.  Piece p is element group p & 3 of the first (p < 4) or
+  // second tile; it sits in lane (p & 3) * 16 + token.  k <= 8: lanes n and n + 8 hold the same
+  // totals, so lane n sends the first tile's and lane n + 8 the second's.  k > 8: rows 0-7 and
+  // rows 8-15 of a 16-token tile go out as two stores; for each, the lanes of the other eight
+  // tokens pass on their partner's second-tile values (a rotation by 8 within 16 lanes).
+  if (splits == 1 && MW % 2 == 0) {
+    const int r = lane >> 3, p = lane & 7;
+#pragma unroll
+    for (int q = 0; q < NA; ++q) {
+#pragma unroll
+      for (int pair = 0; pair < MW / 2; ++pair) {
+        float a[4], b[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          a[j] = acc[2 * pair][q][j];
+          b[j] = acc[2 * pair + 1][q][j];
+          if (NB == 1) {
+            a[j] += __shfl_xor(a[j], 8, kWave);
+            b[j] += __shfl_xor(b[j], 8, kWave);
+          }
+        }
+#pragma unroll
+        for (int h = 0; h < (NB == 1 ? 1 : 2); ++h) {
+          const bool first = NB == 1 ? n < 8 : (n >> 3) == h;   // this lane sends its first-tile values
+          const int src = ((p & 3) * 16 + r + (NB == 1 ? (p >= 4 ? 8 : 0) : ((p >= 4) == (h == 0) ? 8 : 0))) * 4;
+          float4 v;
+          float *vp = reinterpret_cast<float *>(&v);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t other = NB == 1 ? __float_as_uint(b[j]) : ror8_into<0xf>(0u, __float_as_uint(b[j]));
+            const uint32_t send = first ? __float_as_uint(a[j]) : other;
+            vp[j] = __uint_as_float((uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)send));
+          }
+          const int t = NB == 1 ? r : q * 16 + 8 * h + r;
+          if (t < k) store_stream(reinterpret_cast<float4 *>(y + (c * k + t) * d + col0 + pair * 32 + 4 * p), v);
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int q = 0; q < NA; ++q) {
     const int t = NB == 1 ? (n & 7) : q * 16 + n;
